@@ -1,0 +1,333 @@
+"""Pins for the float64 oracle: closed forms, invariants, library special cases
+and brute force.  Nothing here touches the HIP library.
+
+Each pin is chosen so that a plausible slip in the oracle (a dropped term, a
+wrong sign or index, a transposed operand, sample instead of population std,
+floor instead of ceil, ...) fails at least one test.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import compactor_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "leverage_closed_forms.txt")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------- golden file
+def _parse_matrix(txt):
+    return np.array([[float(Fraction(x)) for x in row.split()] for row in txt.split(";")])
+
+
+def _load_cases():
+    cases, cur = [], None
+    with open(GOLDEN) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, _, rest = line.partition(" ")
+            if key == "case":
+                cur = {"name": rest, "ridge_rel": 0.0, "Phi": None}
+                cases.append(cur)
+            elif key == "K":
+                cur["K"] = _parse_matrix(rest)
+            elif key == "Phi":
+                cur["Phi"] = _parse_matrix(rest)
+            elif key == "ridge_rel":
+                cur["ridge_rel"] = float(rest)
+            elif key == "expect":
+                cur["expect"] = np.array([float(Fraction(x)) for x in rest.split()])
+            elif key == "cite":
+                cur["cite"] = rest
+    return cases
+
+
+@pytest.mark.parametrize("case", _load_cases(), ids=lambda c: c["name"])
+def test_closed_form_cases(case):
+    K, Phi, rr, want = case["K"], case["Phi"], case["ridge_rel"], case["expect"]
+    full_rank = np.linalg.matrix_rank(K) == K.shape[1]
+    if Phi is None:
+        if rr == 0.0:
+            np.testing.assert_allclose(O.leverage_svd(K), want, atol=1e-12)
+            np.testing.assert_allclose(O.leverage_hat_diagonal(K), want, atol=1e-12)
+        if full_rank or rr > 0:
+            np.testing.assert_allclose(O.leverage_ridge_exact(K, rr), want, atol=1e-12)
+    else:
+        np.testing.assert_allclose(O.approx_leverage_alg1(K, Phi), want, atol=1e-12)
+        np.testing.assert_allclose(O.approx_leverage_ridge(K, Phi, rr), want, atol=1e-12)
+        np.testing.assert_allclose(O.approx_leverage_qr(K, Phi), want, atol=1e-12)
+        np.testing.assert_allclose(O.approx_leverage_eig(K, Phi, eps=1e-300), want, atol=1e-12)
+
+
+# ---------------------------------------------------------------- bf16 widening
+def test_bf16_widening_is_exact():
+    bits = np.array([0x0000, 0x3F80, 0xBF80, 0x4000, 0x3F00, 0x41A0, 0x3DCD, 0x8000], dtype=np.uint16)
+    want = np.array([0.0, 1.0, -1.0, 2.0, 0.5, 20.0, 0.10009765625, -0.0])
+    got = O.bf16_bits_to_f64(bits)
+    assert np.array_equal(got, want)
+    assert np.signbit(got[-1])
+
+
+# ---------------------------------------------------------------- P1, P2
+@pytest.mark.parametrize("n,d", [(40, 7), (300, 16), (129, 128)])
+def test_exact_scores_in_unit_interval_and_sum_to_rank(n, d):
+    K = _rng(n + d).standard_normal((n, d))
+    for o in (O.leverage_svd(K), O.leverage_ridge_exact(K), O.leverage_hat_diagonal(K)):
+        assert o.min() >= -1e-12 and o.max() <= 1 + 1e-12
+        assert abs(o.sum() - d) < 1e-8          # Definition 1: sum = rank(K)
+
+
+def test_sum_is_rank_for_rank_deficient_K():
+    r = _rng(0)
+    K = r.standard_normal((200, 5)) @ r.standard_normal((5, 12))   # rank 5
+    assert abs(O.leverage_svd(K).sum() - 5) < 1e-8
+    assert abs(O.leverage_hat_diagonal(K).sum() - 5) < 1e-6
+
+
+@pytest.mark.parametrize("ridge_rel", [1e-4, 0.3, 2.0])
+def test_ridge_sum_closed_form(ridge_rel):
+    # sum_i k_i^T (G + rho I)^-1 k_i = trace(G (G + rho I)^-1) = sum_j mu_j / (mu_j + rho)
+    r = _rng(3)
+    K = r.standard_normal((150, 9)) * r.uniform(0.1, 5.0, 9)
+    mu = np.linalg.eigvalsh(K.T @ K)
+    rho = ridge_rel * mu.sum() / 9
+    o = O.leverage_ridge_exact(K, ridge_rel)
+    assert abs(o.sum() - np.sum(mu / (mu + rho))) < 1e-9
+    assert o.min() >= 0 and o.max() <= 1
+    # a ridge can only lower every score
+    assert np.all(o <= O.leverage_ridge_exact(K, 0.0) + 1e-12)
+
+    Phi = r.standard_normal((9, 4))
+    Kh = K @ Phi
+    mu = np.linalg.eigvalsh(Kh.T @ Kh)
+    rho = ridge_rel * mu.sum() / 4
+    assert abs(O.approx_leverage_ridge(K, Phi, ridge_rel).sum() - np.sum(mu / (mu + rho))) < 1e-9
+
+
+# ---------------------------------------------------------------- P3
+def test_exact_scores_invariant_under_right_multiplication():
+    r = _rng(4)
+    K = r.standard_normal((120, 10))
+    A = r.standard_normal((10, 10)) + 3 * np.eye(10)
+    base = O.leverage_ridge_exact(K)
+    np.testing.assert_allclose(O.leverage_ridge_exact(K @ A), base, atol=1e-9)
+    # the 4 outlier channels x20 of the synthetic keys must not move exact scores
+    s = np.ones(10); s[[1, 4, 6, 9]] = 20.0
+    np.testing.assert_allclose(O.leverage_ridge_exact(K * s), base, atol=1e-9)
+    np.testing.assert_allclose(O.leverage_svd(K * s), base, atol=1e-9)
+
+
+# ---------------------------------------------------------------- P4
+def test_orthonormal_special_cases():
+    r = _rng(5)
+    Q, _ = np.linalg.qr(r.standard_normal((60, 8)))
+    want = np.sum(Q * Q, axis=1)
+    for f in (O.leverage_svd, O.leverage_ridge_exact, O.leverage_hat_diagonal):
+        np.testing.assert_allclose(f(Q), want, atol=1e-10)
+    # square invertible K: every row has leverage 1
+    Ksq = r.standard_normal((8, 8)) + 4 * np.eye(8)
+    np.testing.assert_allclose(O.leverage_ridge_exact(Ksq), np.ones(8), atol=1e-9)
+    # rank one
+    u, v = r.standard_normal(30), r.standard_normal(6)
+    np.testing.assert_allclose(O.leverage_svd(np.outer(u, v)), u * u / (u @ u), atol=1e-10)
+
+
+# ---------------------------------------------------------------- P5
+@pytest.mark.parametrize("seed", [0, 1])
+def test_three_independent_routes_agree(seed):
+    r = _rng(10 + seed)
+    K = r.standard_normal((257, 24)) * r.uniform(0.05, 20.0, 24)
+    hat = O.leverage_hat_diagonal(K)
+    U, _, _ = np.linalg.svd(K, full_matrices=False)
+    Q, _ = np.linalg.qr(K)
+    np.testing.assert_allclose(O.leverage_ridge_exact(K), hat, rtol=1e-7, atol=1e-10)
+    np.testing.assert_allclose(O.leverage_svd(K), np.sum(U * U, axis=1), atol=1e-10)
+    np.testing.assert_allclose(O.leverage_ridge_exact(K), np.sum(Q * Q, axis=1), rtol=1e-7, atol=1e-10)
+
+
+# ---------------------------------------------------------------- Algorithm 1
+def _sketch_case(seed, n=400, d=32, ks=12):
+    r = _rng(seed)
+    K = r.standard_normal((n, d)) * r.uniform(0.1, 10.0, d)
+    Phi = r.standard_normal((d, ks)) / math.sqrt(ks)
+    return r, K, Phi
+
+
+def test_alg1_equals_leverage_of_sketched_matrix():
+    # Theorem 2 defines the approximate score as the leverage score of K Phi.
+    _, K, Phi = _sketch_case(20)
+    want = O.leverage_svd(K @ Phi)
+    np.testing.assert_allclose(O.approx_leverage_alg1(K, Phi), want, rtol=1e-8, atol=1e-12)
+    np.testing.assert_allclose(O.approx_leverage_ridge(K, Phi, 0.0), want, rtol=1e-8, atol=1e-12)
+    np.testing.assert_allclose(O.approx_leverage_qr(K, Phi), want, rtol=1e-8, atol=1e-12)
+    np.testing.assert_allclose(O.approx_leverage_eig(K, Phi, eps=1e-300), want, rtol=1e-8, atol=1e-12)
+    assert abs(want.sum() - Phi.shape[1]) < 1e-8             # rank(K Phi) = k_s
+
+
+def test_sketched_scores_depend_only_on_range_of_K_Phi():       # P6
+    r, K, Phi = _sketch_case(21)
+    base = O.approx_leverage_ridge(K, Phi)
+    B = r.standard_normal((12, 12)) + 3 * np.eye(12)
+    np.testing.assert_allclose(O.approx_leverage_ridge(K, Phi @ B), base, rtol=1e-8, atol=1e-12)
+    np.testing.assert_allclose(O.approx_leverage_alg1(K, 7.5 * Phi), base, rtol=1e-8, atol=1e-12)
+    # k_s = d and invertible Phi: the sketch is a change of basis, scores are exact
+    Phi_sq = r.standard_normal((32, 32)) + 5 * np.eye(32)
+    np.testing.assert_allclose(O.approx_leverage_ridge(K, Phi_sq), O.leverage_ridge_exact(K),
+                               rtol=1e-7, atol=1e-12)
+    np.testing.assert_allclose(O.approx_leverage_alg1(K, Phi_sq), O.leverage_svd(K),
+                               rtol=1e-7, atol=1e-12)
+
+
+def test_sketched_score_never_exceeds_exact_score():             # P7
+    # range(K Phi) is a subspace of range(K): projecting onto less can only shrink.
+    _, K, Phi = _sketch_case(22)
+    assert np.all(O.approx_leverage_ridge(K, Phi) <= O.leverage_ridge_exact(K) + 1e-10)
+
+
+def test_alg1_pseudo_inverse_when_sketched_gram_is_singular():
+    r = _rng(23)
+    K = r.standard_normal((50, 3)) @ r.standard_normal((3, 16))      # rank 3 < k_s
+    Phi = r.standard_normal((16, 6))
+    o = O.approx_leverage_alg1(K, Phi)
+    assert abs(o.sum() - 3) < 1e-6 and o.max() <= 1 + 1e-9
+    np.testing.assert_allclose(o, O.leverage_svd(K @ Phi), atol=1e-7)
+
+
+def test_eig_clamp_only_lowers_scores():
+    _, K, Phi = _sketch_case(24)
+    assert np.all(O.approx_leverage_eig(K, Phi, eps=1e-6) <= O.approx_leverage_alg1(K, Phi) + 1e-12)
+
+
+# ---------------------------------------------------------------- P8
+def test_duplicates_and_row_permutation():
+    r = _rng(30)
+    K = r.standard_normal((90, 6))
+    K[[7, 20, 55]] = K[3]                                   # 4 identical rows
+    o = O.leverage_ridge_exact(K)
+    assert o[3] == o[7] == o[20] == o[55]
+    assert o[3] <= 0.25 + 1e-12                             # m copies: each at most 1/m
+    p = r.permutation(90)
+    np.testing.assert_allclose(O.leverage_ridge_exact(K[p]), o[p], atol=1e-10)
+    Phi = r.standard_normal((6, 3))
+    os_ = O.approx_leverage_ridge(K, Phi)
+    assert os_[3] == os_[7] == os_[20] == os_[55]
+    np.testing.assert_allclose(O.approx_leverage_ridge(K[p], Phi), os_[p], atol=1e-10)
+
+
+# ---------------------------------------------------------------- P9 select / compact
+def _brute_topk(s, k):
+    """Repeatedly take the largest remaining score, lowest index among equals."""
+    s = [(-math.inf if (x != x) else float(np.float32(x))) for x in s]
+    left = list(range(len(s)))
+    out = []
+    for _ in range(k):
+        best = left[0]
+        for i in left[1:]:
+            if s[i] > s[best]:
+                best = i
+        out.append(best)
+        left.remove(best)
+    return sorted(out)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_select_matches_brute_force(seed):
+    r = _rng(40 + seed)
+    n = int(r.integers(1, 60))
+    s = r.integers(-3, 4, n).astype(np.float64) / 4.0       # many exact ties, both signs, zeros
+    if seed == 3:
+        s[r.integers(0, n)] = np.nan
+    if seed == 4:
+        s = np.where(s == 0, -0.0, s)                       # -0.0 ties with +0.0
+    for k in {1, max(1, n // 3), n}:
+        got = O.select_topk(s, k)
+        assert got.dtype == np.int32
+        assert got.tolist() == _brute_topk(s, k)
+
+
+def test_select_properties_and_compact():
+    r = _rng(50)
+    n, k = 1000, 317
+    s = r.standard_normal(n)
+    kept = O.select_topk(s, k)
+    assert len(kept) == k and np.all(np.diff(kept) > 0)
+    mask = np.zeros(n, bool); mask[kept] = True
+    assert s[mask].min() >= s[~mask].max()
+    Kb = r.integers(0, 65536, (n, 8)).astype(np.uint16)
+    Vb = r.integers(0, 65536, (n, 8)).astype(np.uint16)
+    Kp, Vp = O.compact_rows(Kb, Vb, kept)
+    assert np.array_equal(Kp, Kb[kept]) and np.array_equal(Vp, Vb[kept])
+    # r = 1 keeps everything in order
+    assert np.array_equal(O.select_topk(s, n), np.arange(n))
+
+
+@pytest.mark.parametrize("n,r,want", [
+    (4096, 0.5, 2048), (32768, 0.3, 9831), (131072, 0.2, 26215), (100000, 0.32, 32000),
+    (10, 1.0, 10), (10, 1e-6, 1), (7, 0.5, 4), (1, 0.2, 1), (0, 0.5, 0), (1000, 0.001, 1),
+    (3, 1 / 3, 1),
+])
+def test_keep_count(n, r, want):
+    assert O.keep_count(n, r) == want
+
+
+# ---------------------------------------------------------------- P10 blend
+def test_blend():
+    r = _rng(60)
+    a, o = np.exp(r.standard_normal(500)), r.uniform(0, 1, 500)
+    za, zo = O.zscore(a), O.zscore(o)
+    for z in (za, zo):
+        assert abs(z.mean()) < 1e-12 and abs(np.mean(z * z) - 1) < 1e-12   # population std
+    s = O.blend_scores(a, o, 0.3)
+    np.testing.assert_allclose(s, za + 0.3 * zo, atol=1e-12)
+    # hand value: a=(1,3), o=(4,0): z(a)=(-1,1), z(o)=(1,-1) -> s=(-1+lam, 1-lam)
+    np.testing.assert_allclose(O.blend_scores(np.array([1.0, 3.0]), np.array([4.0, 0.0]), 0.3),
+                               [-0.7, 0.7], atol=1e-15)
+    # lam = 0 ranks by a only; constant a ranks by o only; a = None is s = o
+    assert np.array_equal(np.argsort(-O.blend_scores(a, o, 0.0)), np.argsort(-a))
+    assert np.array_equal(np.argsort(-O.blend_scores(np.full(500, 2.0), o, 0.3)), np.argsort(-o))
+    assert np.array_equal(O.blend_scores(None, o), o)
+
+
+# ---------------------------------------------------------------- P11 calibration
+@pytest.mark.parametrize("b", [0.5, 3.0, 10.0])
+@pytest.mark.parametrize("tau", [0.5, 0.9, 0.95])
+def test_calibration_curve_and_inverse(b, tau):
+    alpha, beta, nll = 0.7, 0.2, (b - 0.2) / 0.7
+    f = lambda r: float(O.calibration_curve(r, nll, alpha, beta))
+    assert abs(f(0.0)) < 1e-15 and abs(f(1.0) - 1.0) < 1e-15
+    rs = np.linspace(0, 1, 101)
+    assert np.all(np.diff(O.calibration_curve(rs, nll, alpha, beta)) > 0)
+    rstar = O.calibrated_ratio(nll, alpha, beta, tau)
+    assert 0 < rstar <= 1 and abs(f(rstar) - tau) < 1e-12
+    assert f(rstar - 1e-6) < tau                              # smallest such r
+
+
+def test_calibration_hand_value():
+    # b = ln 2, tau = 1/2: f(r) = (2^r/2 - 1/2)/(1/2) = 2^r - 1 >= 1/2  <=>  r >= log2(3/2)
+    assert abs(O.calibrated_ratio(1.0, math.log(2.0), 0.0, 0.5) - math.log2(1.5)) < 1e-14
+    assert O.calibrated_ratio(1.0, 1.0, 0.0, 1.0) == 1.0
+
+
+# ---------------------------------------------------------------- end to end on one head
+def test_compress_head_end_to_end_small():
+    r = _rng(70)
+    n, d, ks = 300, 16, 6
+    K = r.standard_normal((n, d)); K[:, [2, 9]] *= 20
+    Kb = r.integers(0, 65536, (n, d)).astype(np.uint16)
+    Vb = r.integers(0, 65536, (n, d)).astype(np.uint16)
+    Phi = r.standard_normal((d, ks)) / math.sqrt(ks)
+    s, kept, Kp, Vp = O.compress_head(K, Kb, Vb, 0.25, Phi)
+    assert len(kept) == 75
+    np.testing.assert_allclose(s, O.leverage_svd(K @ Phi), rtol=1e-8)
+    assert np.array_equal(Kp, Kb[kept]) and np.array_equal(Vp, Vb[kept])
+    s2, kept2, _, _ = O.compress_head(K, Kb, Vb, 0.25, None)
+    np.testing.assert_allclose(s2, O.leverage_hat_diagonal(K), rtol=1e-7)
+    assert kept2.tolist() == _brute_topk(s2, 75)
