@@ -1,0 +1,170 @@
+/*
+ * compactor.h -- C boundary of the MI355X (gfx950) Compactor hot path.
+ *
+ * Compactor is a query-agnostic KV-cache eviction method: every cached token of
+ * every (layer, kv-head) gets an importance score, the top ceil(r*N) tokens per
+ * head are retained, and their key/value rows form the compressed cache
+ * (paper Sec. 3, "Preliminaries & Overview").  This library runs that path on
+ * one GPU:
+ *
+ *   score    outlier scores o = approximate statistical leverage scores of the
+ *            head's key matrix (Sec. 3.1 Definition 1 and Eq. "fast_svd";
+ *            Sec. 3.2 Algorithm 1), optionally blended with caller-supplied
+ *            attention scores a as s = z(a) + lambda*z(o) (Sec. 3.3 Eq. "scoring")
+ *   select   per-head top-ceil(r*N) of s (Sec. 3.3, "KV selection")
+ *   compact  gather of the retained K/V rows into a packed cache
+ *   compress the three fused on one stream
+ *
+ * General conventions
+ *   - Every pointer marked "device" is GPU memory owned by the caller; every
+ *     pointer marked "host" is ordinary host memory owned by the caller.  The
+ *     library never allocates, frees or synchronises: all work is enqueued on
+ *     the stream that is passed in (a hipStream_t cast to void*, NULL = the
+ *     default stream) and outputs are valid once that stream has drained.
+ *   - Keys and values are bfloat16 (raw 16-bit patterns), head_dim contiguous.
+ *   - Heads are numbered request-major: head g = (sum of L*H of earlier
+ *     requests) + layer*H + kv_head.  All per-head outputs use this order and
+ *     the element offsets reported by compactor_layout().
+ *   - Return value: COMPACTOR_OK or a negative COMPACTOR_E* code.  Errors are
+ *     detected on the host before anything is enqueued; a failing call leaves
+ *     the outputs untouched.  Numerical trouble inside a head never aborts: it
+ *     is reported in that head's status word (see COMPACTOR_STATUS_*).
+ *   - Thread safety: no global mutable state; concurrent calls are safe when
+ *     they use distinct workspaces and output buffers.
+ */
+#ifndef COMPACTOR_H
+#define COMPACTOR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define COMPACTOR_OK                   0
+#define COMPACTOR_EINVAL             (-1)  /* null pointer, n <= 0, ratio outside (0,1], ... */
+#define COMPACTOR_EUNSUPPORTED       (-2)  /* head_dim != 128, sketch_dim not in {0,16,32,48,64} */
+#define COMPACTOR_EWORKSPACE         (-3)  /* workspace pointer null or too small */
+#define COMPACTOR_EALIGN             (-4)  /* a pointer or a row stride is not 16-byte aligned */
+#define COMPACTOR_EHIP               (-5)  /* a HIP runtime call failed (launch error) */
+
+/* per-head status bits written by the scoring step */
+#define COMPACTOR_STATUS_OK            0
+#define COMPACTOR_STATUS_PIVOT         1   /* the factored Gram matrix was numerically singular:
+                                              the offending direction was dropped */
+#define COMPACTOR_STATUS_NONFINITE     2   /* a non-finite score was produced (non-finite input) */
+
+/* One request = one context whose cache is compressed (Sec. 3: K, V in R^{N x d}
+ * per head; retention r in (0,1]). */
+typedef struct compactor_request {
+  const void  *k_score;   /* device, bf16 [L,H,n,d]: keys that are scored.  The paper scores the
+                             keys before positional encoding (Sec. 3.1/3.2). */
+  const void  *k_cache;   /* device, bf16 [L,H,n,d]: keys that are packed (the cached, position-
+                             encoded keys); NULL = pack k_score. Same strides as k_score. */
+  const void  *v_cache;   /* device, bf16 [L,H,n,d]: values that are packed. Same strides. */
+  const float *attn;      /* device, fp32 [L,H,n] contiguous attention scores a, or NULL.
+                             NULL gives s = o, the paper's "only o" variant. */
+  int64_t stride_l;       /* element strides of the three bf16 tensors; d has stride 1 */
+  int64_t stride_h;
+  int64_t stride_t;       /* >= head_dim and a multiple of 8 elements (16 bytes) */
+  int32_t n;              /* tokens N in this context, 1 <= n < 2^31 - 64 */
+  float   ratio;          /* retention r in (0,1], requested or context-calibrated (Sec. 3.4) */
+} compactor_request_t;
+
+typedef struct compactor_params {
+  int32_t layers;         /* L >= 1 */
+  int32_t kv_heads;       /* H >= 1 */
+  int32_t head_dim;       /* d; 128 is the only supported value */
+  int32_t sketch_dim;     /* k_s of Algorithm 1: 16, 32, 48 (paper default) or 64;
+                             0 = exact leverage scores (no sketch, Definition 1) */
+  const float *phi;       /* device, fp32 [d, k_s] row-major right-sketch Phi, entries
+                             N(0, 1/k_s) (Algorithm 1 line 1); drawn by the caller so that the
+                             library holds no random state.  Ignored when sketch_dim = 0. */
+  float   ridge_rel;      /* >= 0.  rho = ridge_rel * trace(M)/order(M) is added to the diagonal
+                             of the Gram matrix M that is factored (M = Phi^T K^T K Phi, or
+                             K^T K in exact mode).  0 is Algorithm 1 as printed. */
+  float   lambda_blend;   /* lambda of Eq. "scoring" (paper default 0.3); used only where
+                             attn != NULL */
+  int64_t group_bytes;    /* tuning: heads are processed in groups whose keys total about this
+                             many bytes so that the second pass over a group's keys hits the
+                             last-level cache; 0 = library default */
+} compactor_params_t;
+
+/* Fills *p with the paper's defaults (Sec. 4: k = 48, lambda = 0.3), d = 128,
+ * ridge_rel = 0, phi = NULL.  host. */
+void compactor_default_params(compactor_params_t *p, int32_t layers, int32_t kv_heads);
+
+/* k_keep = clamp(ceil(r*N), 1, N) (Sec. 3: "top-k with k = ceil(r N)").  r is widened to
+ * double and the product shrunk by (1 - 2^-23) before the ceiling, so that a float32 ratio whose
+ * product with N is an integer on paper does not round up to the next integer.
+ * Returns 0 for n <= 0. host. */
+int32_t compactor_keep_count(int32_t n, float ratio);
+
+/* Element offsets of each request inside the flat output buffers. host.
+ *   score_off[b]  offset (floats)  of request b in scores:   prefix sum of L*H*n_b
+ *   kept_off[b]   offset (rows)    of request b in kept_idx / k_packed / v_packed:
+ *                 prefix sum of L*H*k_keep_b; within a request, head (l,h) starts at
+ *                 kept_off[b] + (l*H+h)*k_keep_b
+ *   k_keep[b]     retained tokens per head of request b
+ * score_off and kept_off have nreq+1 entries (the last is the total); k_keep has nreq.
+ * Any of the three may be NULL. */
+int compactor_layout(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                     int64_t *score_off, int64_t *kept_off, int32_t *k_keep);
+
+/* Bytes of device workspace that score / select / compress need for this batch. host.
+ * The workspace must be 256-byte aligned; its contents are scratch (no state is kept
+ * between calls). */
+int compactor_workspace_size(const compactor_params_t *p, const compactor_request_t *reqs,
+                             int32_t nreq, size_t *bytes);
+
+/* Scores every token of every head.
+ *   scores  device, fp32 [sum_b L*H*n_b] at compactor_layout's score_off: s (= o when a request
+ *           has attn == NULL, else Eq. "scoring")
+ *   status  device, int32 [nreq*L*H]: COMPACTOR_STATUS_* bits per head
+ * Sec. 3.1-3.3; Algorithm 1 evaluated as o_i = ||L^{-1} Phi^T k_i||^2 with
+ * L L^T = Phi^T K^T K Phi + rho I, equal to diag(U~ U~^T) of Algorithm 1 when rho = 0. */
+int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                    float *scores, int32_t *status, void *workspace, size_t workspace_bytes,
+                    void *stream);
+
+/* Per-head top-k_keep of the given scores (Sec. 3.3 step 2, selection "within a single head").
+ *   scores    device, fp32, layout as written by compactor_score
+ *   kept_idx  device, int32 [sum_b L*H*k_keep_b] at kept_off: token indices of the retained
+ *             tokens of each head, ascending
+ *   kept_cnt  device, int32 [nreq*L*H]: number of indices written per head (= k_keep_b)
+ * Order: higher score first, equal scores by lower token index; NaN ranks below every number
+ * and -0.0 equals +0.0.  The reqs' tensors are not read, only n and ratio. */
+int compactor_select(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                     const float *scores, int32_t *kept_idx, int32_t *kept_cnt,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* Gathers the retained rows: k_packed[row j of head g] = k_cache[kept_idx[j]], same for v.
+ *   k_packed, v_packed  device, bf16 [sum_b L*H*k_keep_b, d] dense rows at kept_off
+ * Bit copies.  An index outside [0, n) is a caller error; such a row is written as zeros. */
+int compactor_compact(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                      const int32_t *kept_idx, const int32_t *kept_cnt,
+                      void *k_packed, void *v_packed, void *stream);
+
+/* score -> select -> compact on one stream, with no host synchronisation in between.
+ * scores may be NULL (they then live in the workspace only). */
+int compactor_compress(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                       float *scores, int32_t *kept_idx, int32_t *kept_cnt,
+                       void *k_packed, void *v_packed, int32_t *status,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Context-calibrated retention (Sec. 3.4): the smallest r in (0,1] with
+ * f(r) = (exp(r b - b) - exp(-b)) / (1 - exp(-b)) >= tau, b = alpha*nll + beta, i.e.
+ * r* = 1 + ln(tau (1 - e^-b) + e^-b) / b (r* = tau in the limit b -> 0). host. */
+double compactor_calibrated_ratio(double nll, double alpha, double beta, double tau);
+
+/* Human-readable text for a return code. host; the string is static. */
+const char *compactor_error_string(int code);
+
+/* Library version, "major.minor". host; static string. */
+const char *compactor_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMPACTOR_H */

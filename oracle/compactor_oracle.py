@@ -225,23 +225,20 @@ def keep_count(n: int, ratio: float) -> int:
     return max(1, min(n, k))
 
 
-def _sanitise(s: np.ndarray) -> np.ndarray:
-    """Scores as the selection sees them: float32 values, NaN ranked last,
-    -0.0 equal to +0.0 (adding +0.0 turns -0.0 into +0.0)."""
-    s32 = np.asarray(s, dtype=np.float32) + np.float32(0.0)
-    return np.where(np.isnan(s32), -np.inf, s32.astype(np.float64))
-
-
 def select_topk(s: np.ndarray, k_keep: int) -> np.ndarray:
     """Indices of the k_keep largest scores, ascending.
 
     Order: higher score first; equal scores by lower index first (the paper
     leaves ties open; this rule is deterministic and position-stable).
-    Scores are compared as float32 values, the precision the library stores.
+    Scores are compared as float32 values, the precision the library stores;
+    -0.0 equals +0.0 and a NaN ranks below every number, -inf included.
     """
-    key = _sanitise(s)
-    n = key.shape[0]
-    order = np.lexsort((np.arange(n), -key))  # primary: -score, secondary: index
+    s32 = np.asarray(s, dtype=np.float32)
+    isnan = np.isnan(s32)
+    val = np.where(isnan, 0.0, s32.astype(np.float64))
+    n = val.shape[0]
+    # lexsort: last key is the primary one
+    order = np.lexsort((np.arange(n), -val, isnan))
     kept = np.sort(order[:k_keep])
     return kept.astype(np.int32)
 

@@ -1,0 +1,262 @@
+"""Thin ctypes binding of libcompactor.so (argument marshalling only).
+
+Every function here has the name of the C entry point it calls
+(include/compactor.h) and does nothing but turn torch tensors into raw device
+pointers, allocate the outputs with torch, and check the return code.  All of
+the method's arithmetic runs in the HIP kernels; there is no CPU fallback: if
+the shared library is missing the import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcompactor.so")
+
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        "libcompactor.so is not built: run `python -m paper_2507_08143_amd.build` "
+        "(needs hipcc; cross-compiles for gfx950 without a GPU)")
+
+_lib = C.CDLL(_LIB_PATH)
+
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EALIGN, EHIP = 0, -1, -2, -3, -4, -5
+STATUS_OK, STATUS_PIVOT, STATUS_NONFINITE = 0, 1, 2
+
+
+class _Request(C.Structure):
+    _fields_ = [("k_score", C.c_void_p), ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
+                ("attn", C.c_void_p), ("stride_l", C.c_int64), ("stride_h", C.c_int64),
+                ("stride_t", C.c_int64), ("n", C.c_int32), ("ratio", C.c_float)]
+
+
+class _Params(C.Structure):
+    _fields_ = [("layers", C.c_int32), ("kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("sketch_dim", C.c_int32), ("phi", C.c_void_p), ("ridge_rel", C.c_float),
+                ("lambda_blend", C.c_float), ("group_bytes", C.c_int64)]
+
+
+_PP, _RP = C.POINTER(_Params), C.POINTER(_Request)
+_lib.compactor_default_params.argtypes = [_PP, C.c_int32, C.c_int32]
+_lib.compactor_default_params.restype = None
+_lib.compactor_keep_count.argtypes = [C.c_int32, C.c_float]
+_lib.compactor_keep_count.restype = C.c_int32
+_lib.compactor_layout.argtypes = [_PP, _RP, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                  C.POINTER(C.c_int32)]
+_lib.compactor_workspace_size.argtypes = [_PP, _RP, C.c_int32, C.POINTER(C.c_size_t)]
+_lib.compactor_score.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.c_size_t, C.c_void_p]
+_lib.compactor_select.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.compactor_compact.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_void_p]
+_lib.compactor_compress.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                    C.c_void_p]
+_lib.compactor_calibrated_ratio.argtypes = [C.c_double] * 4
+_lib.compactor_calibrated_ratio.restype = C.c_double
+_lib.compactor_error_string.argtypes = [C.c_int]
+_lib.compactor_error_string.restype = C.c_char_p
+_lib.compactor_version.restype = C.c_char_p
+
+EXPORTS = ["compactor_default_params", "compactor_keep_count", "compactor_layout",
+           "compactor_workspace_size", "compactor_score", "compactor_select",
+           "compactor_compact", "compactor_compress", "compactor_calibrated_ratio",
+           "compactor_error_string", "compactor_version"]
+
+
+class CompactorError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__("libcompactor: %s (%d)" % (compactor_error_string(code), code))
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise CompactorError(rc)
+
+
+@dataclass
+class Params:
+    layers: int
+    kv_heads: int
+    sketch_dim: int = 48
+    phi: Optional[torch.Tensor] = None        # fp32 [128, sketch_dim] on the device
+    ridge_rel: float = 0.0
+    lambda_blend: float = 0.3
+    group_bytes: int = 0
+    head_dim: int = 128
+
+    def c(self) -> _Params:
+        phi = 0
+        if self.phi is not None:
+            assert self.phi.dtype == torch.float32 and self.phi.is_contiguous()
+            phi = self.phi.data_ptr()
+        return _Params(self.layers, self.kv_heads, self.head_dim, self.sketch_dim, phi,
+                       self.ridge_rel, self.lambda_blend, self.group_bytes)
+
+
+@dataclass
+class Request:
+    k_score: torch.Tensor                      # bf16 [L, H, n, d], d contiguous
+    v_cache: torch.Tensor                      # bf16, same shape and strides
+    ratio: float
+    k_cache: Optional[torch.Tensor] = None     # bf16, same shape and strides; None = k_score
+    attn: Optional[torch.Tensor] = None        # fp32 [L, H, n] contiguous
+
+    def c(self) -> _Request:
+        k = self.k_score
+        assert k.dtype == torch.bfloat16 and k.dim() == 4 and k.stride(3) == 1
+        for t in (self.v_cache, self.k_cache):
+            if t is not None:
+                assert t.dtype == torch.bfloat16 and t.shape == k.shape and t.stride() == k.stride()
+        if self.attn is not None:
+            assert self.attn.dtype == torch.float32 and self.attn.is_contiguous()
+        return _Request(k.data_ptr(),
+                        self.k_cache.data_ptr() if self.k_cache is not None else 0,
+                        self.v_cache.data_ptr() if self.v_cache is not None else 0,
+                        self.attn.data_ptr() if self.attn is not None else 0,
+                        k.stride(0), k.stride(1), k.stride(2), k.shape[2], self.ratio)
+
+
+def _marshal(params: Params, reqs: Sequence[Request]):
+    arr = (_Request * len(reqs))(*[r.c() for r in reqs])
+    return C.byref(params.c()), arr, len(reqs)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return 0 if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _device(reqs):
+    return reqs[0].k_score.device
+
+
+def compactor_version() -> str:
+    return _lib.compactor_version().decode()
+
+
+def compactor_error_string(code: int) -> str:
+    return _lib.compactor_error_string(code).decode()
+
+
+def compactor_keep_count(n: int, ratio: float) -> int:
+    return int(_lib.compactor_keep_count(n, ratio))
+
+
+def compactor_calibrated_ratio(nll: float, alpha: float, beta: float, tau: float) -> float:
+    return float(_lib.compactor_calibrated_ratio(nll, alpha, beta, tau))
+
+
+def compactor_default_params(layers: int, kv_heads: int) -> Params:
+    p = _Params()
+    _lib.compactor_default_params(C.byref(p), layers, kv_heads)
+    return Params(p.layers, p.kv_heads, p.sketch_dim, None, p.ridge_rel, p.lambda_blend,
+                  p.group_bytes, p.head_dim)
+
+
+def compactor_layout(params: Params, reqs: Sequence[Request]):
+    """-> (score_off[nreq+1], kept_off[nreq+1], k_keep[nreq]) as Python lists."""
+    pp, arr, n = _marshal(params, reqs)
+    so, ko, kk = (C.c_int64 * (n + 1))(), (C.c_int64 * (n + 1))(), (C.c_int32 * n)()
+    _check(_lib.compactor_layout(pp, arr, n, so, ko, kk))
+    return list(so), list(ko), list(kk)
+
+
+def compactor_workspace_size(params: Params, reqs: Sequence[Request]) -> int:
+    pp, arr, n = _marshal(params, reqs)
+    out = C.c_size_t(0)
+    _check(_lib.compactor_workspace_size(pp, arr, n, C.byref(out)))
+    return int(out.value)
+
+
+def _workspace(params, reqs, workspace):
+    if workspace is None:
+        nbytes = max(256, compactor_workspace_size(params, reqs))
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=_device(reqs))
+    return workspace
+
+
+def compactor_score(params: Params, reqs: Sequence[Request], scores=None, status=None,
+                    workspace=None, stream=None):
+    """-> (scores fp32 [sum L*H*n], status int32 [nreq*L*H])"""
+    so, _, _ = compactor_layout(params, reqs)
+    dev = _device(reqs)
+    if scores is None:
+        scores = torch.empty(so[-1], dtype=torch.float32, device=dev)
+    if status is None:
+        status = torch.empty(len(reqs) * params.layers * params.kv_heads, dtype=torch.int32, device=dev)
+    workspace = _workspace(params, reqs, workspace)
+    pp, arr, n = _marshal(params, reqs)
+    _check(_lib.compactor_score(pp, arr, n, _ptr(scores), _ptr(status), _ptr(workspace),
+                                workspace.numel(), _stream(stream)))
+    return scores, status
+
+
+def compactor_select(params: Params, reqs: Sequence[Request], scores: torch.Tensor,
+                     kept_idx=None, kept_cnt=None, stream=None):
+    """-> (kept_idx int32 [sum L*H*k_keep], kept_cnt int32 [nreq*L*H])"""
+    _, ko, _ = compactor_layout(params, reqs)
+    dev = scores.device
+    if kept_idx is None:
+        kept_idx = torch.empty(ko[-1], dtype=torch.int32, device=dev)
+    if kept_cnt is None:
+        kept_cnt = torch.empty(len(reqs) * params.layers * params.kv_heads, dtype=torch.int32, device=dev)
+    pp, arr, n = _marshal(params, reqs)
+    _check(_lib.compactor_select(pp, arr, n, _ptr(scores), _ptr(kept_idx), _ptr(kept_cnt), 0, 0,
+                                 _stream(stream)))
+    return kept_idx, kept_cnt
+
+
+def compactor_compact(params: Params, reqs: Sequence[Request], kept_idx: torch.Tensor,
+                      kept_cnt: torch.Tensor, k_packed=None, v_packed=None, stream=None):
+    """-> (k_packed, v_packed) bf16 [sum L*H*k_keep, d]"""
+    _, ko, _ = compactor_layout(params, reqs)
+    dev = _device(reqs)
+    if k_packed is None:
+        k_packed = torch.empty(ko[-1], params.head_dim, dtype=torch.bfloat16, device=dev)
+    if v_packed is None:
+        v_packed = torch.empty(ko[-1], params.head_dim, dtype=torch.bfloat16, device=dev)
+    pp, arr, n = _marshal(params, reqs)
+    _check(_lib.compactor_compact(pp, arr, n, _ptr(kept_idx), _ptr(kept_cnt), _ptr(k_packed),
+                                  _ptr(v_packed), _stream(stream)))
+    return k_packed, v_packed
+
+
+def compactor_compress(params: Params, reqs: Sequence[Request], want_scores: bool = False,
+                       scores=None, kept_idx=None, kept_cnt=None, k_packed=None, v_packed=None,
+                       status=None, workspace=None, stream=None):
+    """Fused score -> select -> compact.  -> dict of the output tensors."""
+    so, ko, _ = compactor_layout(params, reqs)
+    dev = _device(reqs)
+    nh = len(reqs) * params.layers * params.kv_heads
+    if scores is None and want_scores:
+        scores = torch.empty(so[-1], dtype=torch.float32, device=dev)
+    if kept_idx is None:
+        kept_idx = torch.empty(ko[-1], dtype=torch.int32, device=dev)
+    if kept_cnt is None:
+        kept_cnt = torch.empty(nh, dtype=torch.int32, device=dev)
+    if k_packed is None:
+        k_packed = torch.empty(ko[-1], params.head_dim, dtype=torch.bfloat16, device=dev)
+    if v_packed is None:
+        v_packed = torch.empty(ko[-1], params.head_dim, dtype=torch.bfloat16, device=dev)
+    if status is None:
+        status = torch.empty(nh, dtype=torch.int32, device=dev)
+    workspace = _workspace(params, reqs, workspace)
+    pp, arr, n = _marshal(params, reqs)
+    _check(_lib.compactor_compress(pp, arr, n, _ptr(scores), _ptr(kept_idx), _ptr(kept_cnt),
+                                   _ptr(k_packed), _ptr(v_packed), _ptr(status), _ptr(workspace),
+                                   workspace.numel(), _stream(stream)))
+    return {"scores": scores, "kept_idx": kept_idx, "kept_cnt": kept_cnt, "k_packed": k_packed,
+            "v_packed": v_packed, "status": status, "workspace": workspace}

@@ -1,0 +1,336 @@
+// C boundary of libcompactor: argument checks, output layout, workspace carving and the
+// stream-ordered launch sequence.  Declarations and their contracts: include/compactor.h.
+#include <math.h>
+#include <string.h>
+
+#include "common.h"
+
+using namespace cmp;
+
+namespace {
+
+constexpr long long DEFAULT_GROUP_BYTES = 1ll << 40;   // one group unless the caller asks
+constexpr size_t WS_ALIGN = 256;
+
+inline size_t align_up(size_t x) { return (x + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+enum Need { NEED_SCORE = 1, NEED_PACK = 2 };
+
+int check_params(const compactor_params_t *p, bool scoring) {
+  if (!p) return COMPACTOR_EINVAL;
+  if (p->layers < 1 || p->kv_heads < 1) return COMPACTOR_EINVAL;
+  if ((long long)p->layers * p->kv_heads > (1 << 20)) return COMPACTOR_EINVAL;
+  if (p->head_dim != D) return COMPACTOR_EUNSUPPORTED;
+  const int ks = p->sketch_dim;
+  if (!(ks == 0 || ks == 16 || ks == 32 || ks == 48 || ks == 64)) return COMPACTOR_EUNSUPPORTED;
+  if (scoring) {
+    if (ks > 0 && !p->phi) return COMPACTOR_EINVAL;
+    if (ks > 0 && !aligned16(p->phi)) return COMPACTOR_EALIGN;
+    if (!(p->ridge_rel >= 0.f) || !isfinite(p->ridge_rel)) return COMPACTOR_EINVAL;
+    if (!isfinite(p->lambda_blend)) return COMPACTOR_EINVAL;
+  }
+  if (p->group_bytes < 0) return COMPACTOR_EINVAL;
+  return COMPACTOR_OK;
+}
+
+int check_requests(const compactor_request_t *reqs, int32_t nreq, int need) {
+  if (!reqs || nreq < 1 || nreq > (1 << 20)) return COMPACTOR_EINVAL;
+  for (int b = 0; b < nreq; ++b) {
+    const compactor_request_t &r = reqs[b];
+    if (r.n < 1 || r.n > 0x7fffffff - 64) return COMPACTOR_EINVAL;
+    if (!(r.ratio > 0.f && r.ratio <= 1.f)) return COMPACTOR_EINVAL;
+    if (need) {
+      if ((need & NEED_SCORE) && !r.k_score) return COMPACTOR_EINVAL;
+      if ((need & NEED_PACK) && (!r.v_cache || (!r.k_cache && !r.k_score))) return COMPACTOR_EINVAL;
+      if (r.stride_t < D || r.stride_l < 0 || r.stride_h < 0) return COMPACTOR_EINVAL;
+      if ((r.stride_t & 7) || (r.stride_l & 7) || (r.stride_h & 7)) return COMPACTOR_EALIGN;
+      if (!aligned16(r.k_score) || !aligned16(r.k_cache) || !aligned16(r.v_cache) ||
+          (reinterpret_cast<uintptr_t>(r.attn) & 3u))
+        return COMPACTOR_EALIGN;
+    }
+  }
+  return COMPACTOR_OK;
+}
+
+// Rows of one Gram workgroup: large enough that the 64 KB partial it writes stays a small
+// fraction of the keys it reads, small enough that the launch fills 256 compute units.
+int gram_rows_for(long long group_rows) {
+  int rows = 4096;
+  while (rows > 512 && group_rows / rows < 1024) rows >>= 1;
+  return rows;
+}
+
+struct GroupBytes {
+  size_t partials, g64, wt, scores;
+  size_t total() const { return partials + g64 + wt + scores; }
+};
+
+GroupBytes group_bytes_needed(const SegTable &T, int ks, bool need_scores) {
+  long long rows = 0;
+  for (int i = 0; i < T.nseg; ++i) rows += (long long)T.s[i].n * T.s[i].head_count;
+  const int m = ks > 0 ? ks : D;
+  GroupBytes g;
+  g.partials = align_up((size_t)total_blocks(T, gram_rows_for(rows), false) * D * D * sizeof(float));
+  g.g64 = align_up((size_t)T.nheads * D * D * sizeof(double));
+  g.wt = align_up((size_t)T.nheads * W_TERMS * m * D * sizeof(uint16_t));
+  g.scores = need_scores ? align_up((size_t)rows * sizeof(float)) : 0;
+  return g;
+}
+
+// Walks the batch in head order and cuts it into launch groups of about group_rows key rows
+// (at most MAX_SEG request pieces each).  fn(T, group_score_rows) is called per group; with
+// local_scores the segments' score offsets address a group-local buffer.
+template <class F>
+int for_each_group(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                   long long group_rows, bool local_scores, F &&fn) {
+  const int LH = p->layers * p->kv_heads;
+  long long score_off = 0, kept_off = 0;
+  int b = 0, h = 0;
+  while (b < nreq) {
+    SegTable T;
+    memset(&T, 0, sizeof(T));
+    long long rows = 0, local_off = 0;
+    while (b < nreq && T.nseg < MAX_SEG && rows < group_rows) {
+      const compactor_request_t &r = reqs[b];
+      const int kk = compactor_keep_count(r.n, r.ratio);
+      long long can = (group_rows - rows + r.n - 1) / r.n;
+      if (can < 1) can = 1;
+      const int take = (int)(can < (long long)(LH - h) ? can : (long long)(LH - h));
+      Seg &s = T.s[T.nseg++];
+      s.k_score = static_cast<const uint16_t *>(r.k_score);
+      s.k_cache = static_cast<const uint16_t *>(r.k_cache);
+      s.v_cache = static_cast<const uint16_t *>(r.v_cache);
+      s.attn = r.attn;
+      s.stride_l = r.stride_l; s.stride_h = r.stride_h; s.stride_t = r.stride_t;
+      s.score_off = local_scores ? local_off - (long long)h * r.n : score_off;
+      s.kept_off = kept_off;
+      s.n = r.n; s.k_keep = kk;
+      s.head_begin = h; s.head_count = take;
+      s.ghead0 = b * LH; s.lhead0 = T.nheads; s.H = p->kv_heads;
+      T.nheads += take;
+      rows += (long long)take * r.n;
+      local_off += (long long)take * r.n;
+      h += take;
+      if (h == LH) {
+        score_off += (long long)LH * r.n;
+        kept_off += (long long)LH * kk;
+        h = 0;
+        ++b;
+      }
+    }
+    const int rc = fn(T, rows);
+    if (rc != COMPACTOR_OK) return rc;
+  }
+  return COMPACTOR_OK;
+}
+
+long long group_rows_of(const compactor_params_t *p) {
+  const long long gb = p->group_bytes > 0 ? p->group_bytes : DEFAULT_GROUP_BYTES;
+  long long r = gb / (D * 2);
+  return r < 1 ? 1 : r;
+}
+
+int workspace_need(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                   bool local_scores, size_t *bytes) {
+  size_t need = 0;
+  const int rc = for_each_group(p, reqs, nreq, group_rows_of(p), local_scores,
+                                [&](const SegTable &T, long long) {
+                                  const size_t t = group_bytes_needed(T, p->sketch_dim, local_scores).total();
+                                  if (t > need) need = t;
+                                  return COMPACTOR_OK;
+                                });
+  *bytes = need;
+  return rc;
+}
+
+#define HIP_TRY(expr)                                \
+  do {                                               \
+    if ((expr) != hipSuccess) return COMPACTOR_EHIP; \
+  } while (0)
+
+// score (+ blend) of one group
+int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows, float *scores,
+                  int32_t *status, unsigned char *ws, hipStream_t st) {
+  const GroupBytes gb = group_bytes_needed(T, p->sketch_dim, false);
+  float *partials = reinterpret_cast<float *>(ws);
+  double *g64 = reinterpret_cast<double *>(ws + gb.partials);
+  uint16_t *wt = reinterpret_cast<uint16_t *>(ws + gb.partials + gb.g64);
+  const int rpw = gram_rows_for(rows);
+  HIP_TRY(launch_gram(T, rpw, partials, st));
+  HIP_TRY(launch_gram_reduce(T, rpw, partials, g64, st));
+  HIP_TRY(launch_solve(T, p->sketch_dim, p->phi, p->ridge_rel, g64, wt, status, st));
+  HIP_TRY(launch_score(T, p->sketch_dim, wt, scores, status, st));
+  HIP_TRY(launch_blend(T, p->lambda_blend, scores, st));
+  return COMPACTOR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+void compactor_default_params(compactor_params_t *p, int32_t layers, int32_t kv_heads) {
+  if (!p) return;
+  memset(p, 0, sizeof(*p));
+  p->layers = layers;
+  p->kv_heads = kv_heads;
+  p->head_dim = D;
+  p->sketch_dim = 48;
+  p->phi = nullptr;
+  p->ridge_rel = 0.f;
+  p->lambda_blend = 0.3f;
+  p->group_bytes = 0;
+}
+
+int32_t compactor_keep_count(int32_t n, float ratio) {
+  if (n <= 0) return 0;
+  const double x = ((double)ratio * (double)n) * (1.0 - 0x1p-23);
+  double k = ceil(x);
+  if (!(k >= 1.0)) k = 1.0;
+  if (k > (double)n) k = (double)n;
+  return (int32_t)k;
+}
+
+int compactor_layout(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                     int64_t *score_off, int64_t *kept_off, int32_t *k_keep) {
+  int rc = check_params(p, false);
+  if (rc) return rc;
+  rc = check_requests(reqs, nreq, 0);
+  if (rc) return rc;
+  const long long LH = (long long)p->layers * p->kv_heads;
+  long long so = 0, ko = 0;
+  for (int b = 0; b < nreq; ++b) {
+    const int kk = compactor_keep_count(reqs[b].n, reqs[b].ratio);
+    if (score_off) score_off[b] = so;
+    if (kept_off) kept_off[b] = ko;
+    if (k_keep) k_keep[b] = kk;
+    so += LH * reqs[b].n;
+    ko += LH * kk;
+  }
+  if (score_off) score_off[nreq] = so;
+  if (kept_off) kept_off[nreq] = ko;
+  return COMPACTOR_OK;
+}
+
+int compactor_workspace_size(const compactor_params_t *p, const compactor_request_t *reqs,
+                             int32_t nreq, size_t *bytes) {
+  if (!bytes) return COMPACTOR_EINVAL;
+  int rc = check_params(p, false);
+  if (rc) return rc;
+  rc = check_requests(reqs, nreq, 0);
+  if (rc) return rc;
+  // sized for the fused call that keeps its scores in the workspace, the largest user
+  return workspace_need(p, reqs, nreq, true, bytes);
+}
+
+int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                    float *scores, int32_t *status, void *workspace, size_t workspace_bytes,
+                    void *stream) {
+  int rc = check_params(p, true);
+  if (rc) return rc;
+  rc = check_requests(reqs, nreq, NEED_SCORE);
+  if (rc) return rc;
+  if (!scores || !status) return COMPACTOR_EINVAL;
+  size_t need;
+  rc = workspace_need(p, reqs, nreq, false, &need);
+  if (rc) return rc;
+  if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned char *ws = static_cast<unsigned char *>(workspace);
+  return for_each_group(p, reqs, nreq, group_rows_of(p), false, [&](const SegTable &T, long long rows) {
+    return enqueue_score(p, T, rows, scores, status, ws, st);
+  });
+}
+
+int compactor_select(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                     const float *scores, int32_t *kept_idx, int32_t *kept_cnt,
+                     void * /*workspace*/, size_t /*workspace_bytes*/, void *stream) {
+  int rc = check_params(p, false);
+  if (rc) return rc;
+  rc = check_requests(reqs, nreq, 0);
+  if (rc) return rc;
+  if (!scores || !kept_idx || !kept_cnt) return COMPACTOR_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return for_each_group(p, reqs, nreq, 1ll << 60, false, [&](const SegTable &T, long long) {
+    HIP_TRY(launch_select(T, scores, kept_idx, kept_cnt, st));
+    return COMPACTOR_OK;
+  });
+}
+
+int compactor_compact(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                      const int32_t *kept_idx, const int32_t *kept_cnt, void *k_packed,
+                      void *v_packed, void *stream) {
+  int rc = check_params(p, false);
+  if (rc) return rc;
+  rc = check_requests(reqs, nreq, NEED_PACK);
+  if (rc) return rc;
+  if (!kept_idx || !kept_cnt || !k_packed || !v_packed) return COMPACTOR_EINVAL;
+  if (!aligned16(k_packed) || !aligned16(v_packed)) return COMPACTOR_EALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return for_each_group(p, reqs, nreq, 1ll << 60, false, [&](const SegTable &T, long long) {
+    HIP_TRY(launch_gather(T, kept_idx, static_cast<uint16_t *>(k_packed),
+                          static_cast<uint16_t *>(v_packed), st));
+    return COMPACTOR_OK;
+  });
+}
+
+int compactor_compress(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                       float *scores, int32_t *kept_idx, int32_t *kept_cnt, void *k_packed,
+                       void *v_packed, int32_t *status, void *workspace, size_t workspace_bytes,
+                       void *stream) {
+  int rc = check_params(p, true);
+  if (rc) return rc;
+  rc = check_requests(reqs, nreq, NEED_SCORE | NEED_PACK);
+  if (rc) return rc;
+  if (!kept_idx || !kept_cnt || !k_packed || !v_packed || !status) return COMPACTOR_EINVAL;
+  if (!aligned16(k_packed) || !aligned16(v_packed)) return COMPACTOR_EALIGN;
+  const bool local_scores = scores == nullptr;
+  size_t need;
+  rc = workspace_need(p, reqs, nreq, local_scores, &need);
+  if (rc) return rc;
+  if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned char *ws = static_cast<unsigned char *>(workspace);
+  return for_each_group(p, reqs, nreq, group_rows_of(p), local_scores,
+                        [&](const SegTable &T, long long rows) {
+    float *sc = scores;
+    if (local_scores) {
+      const GroupBytes gb = group_bytes_needed(T, p->sketch_dim, true);
+      sc = reinterpret_cast<float *>(ws + gb.partials + gb.g64 + gb.wt);
+    }
+    const int rc2 = enqueue_score(p, T, rows, sc, status, ws, st);
+    if (rc2) return rc2;
+    HIP_TRY(launch_select(T, sc, kept_idx, kept_cnt, st));
+    HIP_TRY(launch_gather(T, kept_idx, static_cast<uint16_t *>(k_packed),
+                          static_cast<uint16_t *>(v_packed), st));
+    return (int)COMPACTOR_OK;
+  });
+}
+
+double compactor_calibrated_ratio(double nll, double alpha, double beta, double tau) {
+  const double b = alpha * nll + beta;
+  double r = (b == 0.0) ? tau : 1.0 + log(tau * (1.0 - exp(-b)) + exp(-b)) / b;
+  if (!(r > 0.0)) r = 4.9406564584124654e-324;
+  if (r > 1.0) r = 1.0;
+  return r;
+}
+
+const char *compactor_error_string(int code) {
+  switch (code) {
+    case COMPACTOR_OK: return "ok";
+    case COMPACTOR_EINVAL: return "invalid argument";
+    case COMPACTOR_EUNSUPPORTED: return "unsupported shape (head_dim must be 128; sketch_dim 0, 16, 32, 48 or 64)";
+    case COMPACTOR_EWORKSPACE: return "workspace missing or too small";
+    case COMPACTOR_EALIGN: return "pointer or stride not 16-byte aligned";
+    case COMPACTOR_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+const char *compactor_version(void) { return "0.1"; }
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,126 @@
+// Internal declarations shared by the HIP translation units of libcompactor.
+// Nothing here is part of the public boundary (see include/compactor.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "compactor.h"
+
+namespace cmp {
+
+constexpr int D = 128;            // head_dim, the only supported value
+constexpr int MAX_SEG = 24;       // segments (request x head range) per launch
+constexpr int KS_MAX = 128;       // largest factored order (exact mode)
+constexpr int W_TERMS = 3;        // W is carried as a sum of this many bf16 terms (24 mantissa bits)
+
+// Launch-time tile sizes.
+constexpr int GRAM_TILE = 64;         // rows staged in LDS per step of the Gram kernel
+constexpr int SCORE_SUB = 8;          // 16-token sub-tiles per wave in the score kernel
+constexpr int SCORE_TOKENS = 4 * 16 * SCORE_SUB;  // tokens per score workgroup (4 waves)
+constexpr int SELECT_THREADS = 1024;
+constexpr int GATHER_ROWS = 64;       // kept rows per gather workgroup
+
+// One contiguous head range of one request, as seen by one launch.
+struct Seg {
+  const uint16_t *k_score;
+  const uint16_t *k_cache;
+  const uint16_t *v_cache;
+  const float *attn;
+  long long stride_l, stride_h, stride_t;  // elements
+  long long score_off;   // float offset of this request's head (0,0) in the scores buffer
+  long long kept_off;    // row offset of this request in kept_idx / packed buffers
+  int n;                 // tokens
+  int k_keep;            // retained tokens per head
+  int head_begin;        // first head (l*H+h) of the request covered by this segment
+  int head_count;        // heads covered
+  int ghead0;            // global index of the request's head 0 (status / kept_cnt)
+  int lhead0;            // launch-local index of this segment's first head (workspace arrays)
+  int H;                 // kv heads per layer
+  int pad_;
+};
+
+struct SegTable {
+  Seg s[MAX_SEG];
+  int nseg;
+  int nheads;            // launch-local heads in total
+};
+
+// Where a workgroup works: segment, head inside the request, tile inside the head.
+struct Where {
+  int seg;
+  int head;      // l*H + h inside the request
+  int lhead;     // launch-local head index
+  int tile;
+};
+
+// blocks-per-head is ceil(units(seg) / per_block), units = n or k_keep;
+// per_block <= 0 means one block per head.
+__host__ __device__ __forceinline__ int blocks_per_head(int units, int per_block) {
+  return per_block <= 0 ? 1 : (int)(((long long)units + per_block - 1) / per_block);
+}
+
+__device__ __forceinline__ Where locate_block(const SegTable &T, int blk, int per_block,
+                                              bool by_keep) {
+  Where w{0, 0, 0, 0};
+  int base = 0;
+  for (int i = 0; i < T.nseg; ++i) {
+    const int units = by_keep ? T.s[i].k_keep : T.s[i].n;
+    const int bph = blocks_per_head(units, per_block);
+    const int nb = bph * T.s[i].head_count;
+    if (blk < base + nb || i == T.nseg - 1) {
+      const int local = blk - base;
+      const int hh = local / bph;
+      w.seg = i;
+      w.head = T.s[i].head_begin + hh;
+      w.lhead = T.s[i].lhead0 + hh;
+      w.tile = local - hh * bph;
+      return w;
+    }
+    base += nb;
+  }
+  return w;
+}
+
+__device__ __forceinline__ const uint16_t *head_ptr(const uint16_t *base, const Seg &s, int head) {
+  const int l = head / s.H, h = head - l * s.H;
+  return base + (long long)l * s.stride_l + (long long)h * s.stride_h;
+}
+
+// ---- host-side launchers (one per translation unit) -------------------------------------
+// All of them enqueue on `st` and return the hipGetLastError() of their launches.
+
+// Partial Gram matrices: one fp32 [128][128] per (head, row split), split-major inside a head.
+hipError_t launch_gram(const SegTable &T, int rows_per_wg, float *partials, hipStream_t st);
+
+// G64[lhead] = sum over splits of the head's partials, in fp64.
+hipError_t launch_gram_reduce(const SegTable &T, int rows_per_wg, const float *partials,
+                              double *g64, hipStream_t st);
+
+// Factor and emit W^T (as W_TERMS bf16 planes, [term][ks_pad][128] per head) and status.
+hipError_t launch_solve(const SegTable &T, int ks, const float *phi, float ridge_rel,
+                        const double *g64, uint16_t *wt, int32_t *status, hipStream_t st);
+
+// scores[i] = || W^T k_i ||^2
+hipError_t launch_score(const SegTable &T, int ks, const uint16_t *wt, float *scores,
+                        int32_t *status, hipStream_t st);
+
+// s = z(a) + lambda z(o) in place over the scores of heads whose request has attn
+hipError_t launch_blend(const SegTable &T, float lambda, float *scores, hipStream_t st);
+
+hipError_t launch_select(const SegTable &T, const float *scores, int32_t *kept_idx,
+                         int32_t *kept_cnt, hipStream_t st);
+
+hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, uint16_t *k_packed,
+                         uint16_t *v_packed, hipStream_t st);
+
+// Total workgroups of a launch whose blocks-per-head rule is (per_block, by_keep).
+inline long long total_blocks(const SegTable &T, int per_block, bool by_keep) {
+  long long nb = 0;
+  for (int i = 0; i < T.nseg; ++i)
+    nb += (long long)blocks_per_head(by_keep ? T.s[i].k_keep : T.s[i].n, per_block) *
+          T.s[i].head_count;
+  return nb;
+}
+
+}  // namespace cmp

@@ -1,0 +1,57 @@
+// Gather-compaction: the retained K/V rows of every head, in ascending token order, copied
+// into a dense packed cache (paper Sec. 3: the compressed cache consists of the retained
+// key/value pairs).  Pure copy, bit exact: 16 lanes move one 256-byte row with 16-byte
+// accesses, four rows per wave instruction, K and V in the same pass.
+#include "common.h"
+
+namespace cmp {
+
+__global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
+                                                     const int32_t *__restrict__ kept_idx,
+                                                     uint16_t *__restrict__ k_packed,
+                                                     uint16_t *__restrict__ v_packed) {
+  const Where w = locate_block(T, blockIdx.x, GATHER_ROWS, true);
+  const Seg &s = T.s[w.seg];
+  const int k = s.k_keep;
+  const long long row0 = s.kept_off + (long long)w.head * k;      // first packed row of the head
+  const int32_t *idx = kept_idx + row0;
+  const uint16_t *ksrc = head_ptr(s.k_cache ? s.k_cache : s.k_score, s, w.head);
+  const uint16_t *vsrc = head_ptr(s.v_cache, s, w.head);
+  const int chunk = threadIdx.x & 15, sub = threadIdx.x >> 4;     // 16 rows per pass
+
+  uint4 kv[GATHER_ROWS / 16], vv[GATHER_ROWS / 16];
+#pragma unroll
+  for (int p = 0; p < GATHER_ROWS / 16; ++p) {
+    const int j = w.tile * GATHER_ROWS + p * 16 + sub;
+    kv[p] = make_uint4(0, 0, 0, 0);
+    vv[p] = make_uint4(0, 0, 0, 0);
+    if (j < k) {
+      const int tok = idx[j];
+      if (tok >= 0 && tok < s.n) {
+        const long long off = (long long)tok * s.stride_t + chunk * 8;
+        kv[p] = *reinterpret_cast<const uint4 *>(ksrc + off);
+        vv[p] = *reinterpret_cast<const uint4 *>(vsrc + off);
+      }
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < GATHER_ROWS / 16; ++p) {
+    const int j = w.tile * GATHER_ROWS + p * 16 + sub;
+    if (j < k) {
+      const long long off = (row0 + j) * D + chunk * 8;
+      *reinterpret_cast<uint4 *>(k_packed + off) = kv[p];
+      *reinterpret_cast<uint4 *>(v_packed + off) = vv[p];
+    }
+  }
+}
+
+hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, uint16_t *k_packed,
+                         uint16_t *v_packed, hipStream_t st) {
+  const long long nb = total_blocks(T, GATHER_ROWS, true);
+  if (nb <= 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_kernel, dim3((unsigned)nb), dim3(256), 0, st, T, kept_idx, k_packed,
+                     v_packed);
+  return hipGetLastError();
+}
+
+}  // namespace cmp

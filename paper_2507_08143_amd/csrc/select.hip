@@ -1,0 +1,204 @@
+// Per-head top-k selection (paper Sec. 3.3: retain the top ceil(r N) tokens by score, within a
+// single head) and the score blend of Eq. "scoring".
+//
+// Selection is an exact radix select on an order-preserving 32-bit key of the fp32 score
+// (12 + 12 + 8 bits, LDS histograms), followed by an ordered emit: tokens above the threshold
+// key, plus the lowest-indexed tokens equal to it until k_keep is reached, written in
+// ascending token order.  Ties therefore go to the lower index, deterministically.
+// One workgroup of 1024 threads per head; wave ballots and popcounts give the prefix sums.
+#include "common.h"
+
+namespace cmp {
+
+// Order-preserving key: larger score <=> larger key.  NaN ranks below everything (key 0);
+// -0.0 is folded onto +0.0 first.
+__device__ __forceinline__ uint32_t score_key(float s) {
+  s += 0.0f;
+  if (s != s) return 0u;
+  const uint32_t u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Exclusive prefix sum of one int per thread over the 1024-thread workgroup; *total gets the
+// workgroup sum.  wsum is 16 ints of LDS.
+__device__ __forceinline__ int block_exclusive_scan(int v, int *wsum, int *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  __syncthreads();                       // wsum may still be read from a previous call
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < SELECT_THREADS / 64; ++i) {
+    const int x = wsum[i];
+    if (i < wave) base += x;
+    tot += x;
+  }
+  *total = tot;
+  return base + inc - v;
+}
+
+// One radix pass: histogram `bits` bits at `shift` of the keys whose higher bits equal
+// `prefix` (hi_shift = 32 means no prefix), then find the digit where the descending
+// cumulative count reaches `need`.  Returns the digit; *need becomes the count still wanted
+// inside that digit.
+__device__ int radix_pass(const float *__restrict__ sp, int n, int shift, int bits, int hi_shift,
+                          uint32_t prefix, int *need, int *hist, int *wsum, int *found) {
+  const int nb = 1 << bits;
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 4096; i += SELECT_THREADS) hist[i] = 0;
+  __syncthreads();
+  for (int i = tid; i < n; i += SELECT_THREADS) {
+    const uint32_t k = score_key(sp[i]);
+    if (hi_shift >= 32 || (k >> hi_shift) == prefix) atomicAdd(&hist[(k >> shift) & (nb - 1)], 1);
+  }
+  __syncthreads();
+  // thread t owns the 4 digits nb-1-4t .. nb-4-4t (descending), so that an ascending scan over
+  // threads is a descending scan over digits
+  int c[4], sum = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int dgt = nb - 1 - (4 * tid + q);
+    c[q] = dgt >= 0 ? hist[dgt] : 0;
+    sum += c[q];
+  }
+  int total;
+  int before = block_exclusive_scan(sum, wsum, &total);   // keys in higher digits
+  const int want = *need;
+  __syncthreads();                                         // everyone has read *need
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if (before < want && want <= before + c[q]) {          // exactly one (thread, q) matches
+      found[0] = nb - 1 - (4 * tid + q);
+      found[1] = want - before;
+    }
+    before += c[q];
+  }
+  __syncthreads();
+  *need = found[1];
+  return found[0];
+}
+
+__global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T,
+                                                                const float *__restrict__ scores,
+                                                                int32_t *__restrict__ kept_idx,
+                                                                int32_t *__restrict__ kept_cnt) {
+  __shared__ int hist[4096];
+  __shared__ int wsum[SELECT_THREADS / 64];
+  __shared__ int found[2];
+
+  const Where w = locate_block(T, blockIdx.x, 0, false);
+  const Seg &s = T.s[w.seg];
+  const int n = s.n, k = s.k_keep;
+  const float *sp = scores + s.score_off + (long long)w.head * n;
+  int32_t *out = kept_idx + (s.kept_off + (long long)w.head * k);
+  const int tid = threadIdx.x;
+  if (tid == 0) kept_cnt[s.ghead0 + w.head] = k;
+
+  // threshold key: the k-th largest
+  int need = k;
+  const uint32_t d1 = radix_pass(sp, n, 20, 12, 32, 0u, &need, hist, wsum, found);
+  const uint32_t d2 = radix_pass(sp, n, 8, 12, 20, d1, &need, hist, wsum, found);
+  const uint32_t d3 = radix_pass(sp, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
+  const uint32_t thr = (d1 << 20) | (d2 << 8) | d3;
+  const int need_eq = need;             // how many keys equal to thr are kept (lowest indices)
+
+  // ordered emit, 4 consecutive tokens per thread per round
+  int carry_gt = 0, carry_eq = 0;
+  for (int base = 0; base < n; base += 4 * SELECT_THREADS) {
+    const int i0 = base + 4 * tid;
+    uint32_t key[4];
+    int gt = 0, eq = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      key[q] = 0;
+      if (i0 + q < n) {
+        key[q] = score_key(sp[i0 + q]);
+        gt += key[q] > thr;
+        eq += key[q] == thr;
+      } else {
+        key[q] = 0xffffffffu;           // marks "past the end" below
+      }
+    }
+    int total;
+    const int packed = block_exclusive_scan(gt | (eq << 16), wsum, &total);
+    int pg = carry_gt + (packed & 0xffff), pe = carry_eq + (packed >> 16);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (i0 + q < n) {
+        const bool is_gt = key[q] > thr, is_eq = key[q] == thr;
+        const int pos = pg + min(pe, need_eq);
+        if ((is_gt || (is_eq && pe < need_eq)) && pos < k) out[pos] = i0 + q;
+        pg += is_gt;
+        pe += is_eq;
+      }
+    }
+    carry_gt += total & 0xffff;
+    carry_eq += total >> 16;
+  }
+}
+
+// ---- blend: s = z(a) + lambda z(o), population standard deviation, fp64 statistics --------
+__device__ __forceinline__ double block_sum(double v, double *wd) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+  __syncthreads();
+  if (lane == 0) wd[wave] = v;
+  __syncthreads();
+  double t = 0.0;
+#pragma unroll
+  for (int i = 0; i < SELECT_THREADS / 64; ++i) t += wd[i];
+  return t;
+}
+
+__global__ __launch_bounds__(SELECT_THREADS) void blend_kernel(const SegTable T, float lambda,
+                                                               float *__restrict__ scores) {
+  __shared__ double wd[SELECT_THREADS / 64];
+  const Where w = locate_block(T, blockIdx.x, 0, false);
+  const Seg &s = T.s[w.seg];
+  if (s.attn == nullptr) return;
+  const int n = s.n, tid = threadIdx.x;
+  float *o = scores + s.score_off + (long long)w.head * n;
+  const float *a = s.attn + (long long)w.head * n;
+
+  double so = 0.0, sa = 0.0;
+  for (int i = tid; i < n; i += SELECT_THREADS) { so += o[i]; sa += a[i]; }
+  const double mo = block_sum(so, wd) / n, ma = block_sum(sa, wd) / n;
+  double vo = 0.0, va = 0.0;
+  for (int i = tid; i < n; i += SELECT_THREADS) {
+    const double x = o[i] - mo, y = a[i] - ma;
+    vo += x * x;
+    va += y * y;
+  }
+  const double sdo = sqrt(block_sum(vo, wd) / n), sda = sqrt(block_sum(va, wd) / n);
+  // a constant vector (std 0) contributes nothing
+  const double io = sdo > 0.0 ? (double)lambda / sdo : 0.0;
+  const double ia = sda > 0.0 ? 1.0 / sda : 0.0;
+  for (int i = tid; i < n; i += SELECT_THREADS)
+    o[i] = (float)((a[i] - ma) * ia + (o[i] - mo) * io);
+}
+
+hipError_t launch_select(const SegTable &T, const float *scores, int32_t *kept_idx,
+                         int32_t *kept_cnt, hipStream_t st) {
+  if (T.nheads <= 0) return hipSuccess;
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)T.nheads), dim3(SELECT_THREADS), 0, st, T,
+                     scores, kept_idx, kept_cnt);
+  return hipGetLastError();
+}
+
+hipError_t launch_blend(const SegTable &T, float lambda, float *scores, hipStream_t st) {
+  bool any = false;
+  for (int i = 0; i < T.nseg; ++i) any |= T.s[i].attn != nullptr;
+  if (!any || T.nheads <= 0) return hipSuccess;
+  hipLaunchKernelGGL(blend_kernel, dim3((unsigned)T.nheads), dim3(SELECT_THREADS), 0, st, T,
+                     lambda, scores);
+  return hipGetLastError();
+}
+
+}  // namespace cmp

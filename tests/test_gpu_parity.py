@@ -1,0 +1,243 @@
+"""GPU parity: the HIP library (through its C-ABI binding) against the float64 oracle,
+element by element, on seeded inputs that span several tiles and ragged tails."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import compactor_oracle as O
+from paper_2507_08143_amd import workloads as W
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def C():
+    return U.binding()
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ select (integer work: exact)
+def _select_case(C, ns, ratios, L, H, maker, seed):
+    rng = np.random.default_rng(seed)
+    params = C.Params(L, H, sketch_dim=48)
+    reqs, host_scores = [], []
+    for n, r in zip(ns, ratios):
+        k = torch.empty(L, H, n, 128, dtype=torch.bfloat16, device=DEV)   # never read by select
+        reqs.append(C.Request(k_score=k, v_cache=k, ratio=r))
+        host_scores.append(maker(rng, L * H * n).astype(np.float32))
+    flat = torch.from_numpy(np.concatenate(host_scores)).to(DEV)
+    kept, cnt = C.compactor_select(params, reqs, flat)
+    torch.cuda.synchronize()
+    so, ko, kk = C.compactor_layout(params, reqs)
+    kept, cnt = kept.cpu().numpy(), cnt.cpu().numpy()
+    for b, n in enumerate(ns):
+        assert kk[b] == O.keep_count(n, ratios[b])
+        for g in range(L * H):
+            want = O.select_topk(host_scores[b][g * n:(g + 1) * n], kk[b])
+            got = kept[ko[b] + g * kk[b]: ko[b] + (g + 1) * kk[b]]
+            assert cnt[b * L * H + g] == kk[b]
+            assert np.array_equal(got, want), "select mismatch: req %d head %d n=%d k=%d" % (b, g, n, kk[b])
+
+
+def test_select_random_scores(C):
+    _say("select: gaussian scores, ragged batch")
+    _select_case(C, [1, 5, 63, 1023, 1024, 4097, 70001], [1.0, 0.5, 0.3, 0.2, 0.999, 0.6, 0.25],
+                 2, 3, lambda r, m: r.standard_normal(m), 1)
+
+
+def test_select_heavy_ties_signs_and_specials(C):
+    _say("select: ties, zeros of both signs, NaN, infinities")
+
+    def maker(r, m):
+        s = r.integers(-4, 5, m).astype(np.float32) / 8.0
+        s[r.integers(0, m, max(1, m // 50))] = np.nan
+        s[r.integers(0, m, max(1, m // 60))] = -np.inf
+        s[r.integers(0, m, max(1, m // 70))] = np.inf
+        z = np.flatnonzero(s == 0)
+        s[z[::2]] = -0.0
+        return s
+    _select_case(C, [7, 300, 4096, 9000, 33000], [0.5, 0.9, 0.1, 0.45, 0.32], 1, 2, maker, 2)
+
+
+def test_select_all_equal_and_leverage_like(C):
+    _say("select: all-equal scores; tiny positive leverage-like scores")
+    _select_case(C, [5000, 131072], [0.37, 0.2], 1, 1, lambda r, m: np.full(m, 0.25), 3)
+    _select_case(C, [100000], [0.32], 1, 2, lambda r, m: r.chisquare(48, m) / m, 4)
+
+
+# ------------------------------------------------------------------ compact (byte work: exact)
+def test_compact_matches_oracle_with_strided_input(C):
+    _say("compact: strided K/V views, oracle indices")
+    L, H, n = 2, 3, 3000
+    g = torch.Generator(device=DEV); g.manual_seed(5)
+    big_k = torch.randn(L, H, n, 256, generator=g, device=DEV).to(torch.bfloat16)
+    big_v = torch.randn(L, H, n, 256, generator=g, device=DEV).to(torch.bfloat16)
+    k, v = big_k[..., :128], big_v[..., :128]        # row stride 256 elements
+    params = C.Params(L, H)
+    reqs = [C.Request(k_score=k, v_cache=v, ratio=0.4)]
+    _, ko, kk = C.compactor_layout(params, reqs)
+    rng = np.random.default_rng(6)
+    idx = np.concatenate([np.sort(rng.choice(n, kk[0], replace=False)) for _ in range(L * H)]).astype(np.int32)
+    cnt = torch.full((L * H,), kk[0], dtype=torch.int32, device=DEV)
+    kp, vp = C.compactor_compact(params, reqs, torch.from_numpy(idx).to(DEV), cnt)
+    torch.cuda.synchronize()
+    for l in range(L):
+        for h in range(H):
+            gi = l * H + h
+            sel = idx[gi * kk[0]:(gi + 1) * kk[0]]
+            want_k, want_v = O.compact_rows(W.bf16_bits(k[l, h]), W.bf16_bits(v[l, h]), sel)
+            rows = slice(gi * kk[0], (gi + 1) * kk[0])
+            assert np.array_equal(W.bf16_bits(kp[rows]), want_k)
+            assert np.array_equal(W.bf16_bits(vp[rows]), want_v)
+
+
+# ------------------------------------------------------------------ scoring + fused path
+def test_config1_full_sketched_and_exact(C):
+    _say("config 1: single head n=4096, sketched then exact")
+    w = W.config1(device=DEV)
+    st, out = U.run_and_check(C, w, DEV)
+    _say("  sketched: max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+    assert abs(float(out["scores"].double().sum()) - 48) < 1e-2       # sum = rank(K Phi)
+    w.sketch_dim = 0
+    st, out = U.run_and_check(C, w, DEV)
+    _say("  exact:    max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+    assert abs(float(out["scores"].double().sum()) - 128) < 2e-2      # sum = rank(K)
+
+
+@pytest.mark.parametrize("n", [1, 17, 129, 777, 5000])
+def test_ragged_token_counts(C, n):
+    _say("gaussian+outlier keys, 2x2 heads, n=%d" % n)
+    w = W.config1(device=DEV, L=2, H=2, n=n, ratio=0.37)
+    params, reqs = U.make_call(C, w, DEV)
+    if n < 48:      # K Phi cannot have rank 48: the head must be flagged, outputs still valid
+        out = C.compactor_compress(params, reqs, want_scores=True)
+        torch.cuda.synchronize()
+        assert np.all(out["status"].cpu().numpy() & C.STATUS_PIVOT)
+        s = out["scores"].cpu().numpy()
+        assert np.all(np.isfinite(s))
+        k = C.compactor_keep_count(n, 0.37)
+        for g in range(4):
+            U.check_selection_valid(s[g * n:(g + 1) * n], out["kept_idx"].cpu().numpy()[g * k:(g + 1) * k], k)
+    else:
+        st, _ = U.run_and_check(C, w, DEV)
+        _say("  max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+
+
+def test_config2_small(C):
+    _say("config 2 shape, 2 layers x 8 heads, n=6000")
+    st, _ = U.run_and_check(C, W.config2(device=DEV, L=2, H=8, n=6000), DEV)
+    _say("  max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+
+
+def test_config3_small(C):
+    _say("config 3 shape, 2 layers x 4 heads, n=9001")
+    st, _ = U.run_and_check(C, W.config3(device=DEV, L=2, H=4, n=9001), DEV)
+    _say("  max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+
+
+def test_config4_small_ragged_batch(C):
+    _say("config 4 shape: 6 requests, n in [300, 5000], 2x8 heads")
+    w = W.config4(device=DEV, L=2, H=8, n_req=6, n_lo=300, n_hi=5000)
+    st, _ = U.run_and_check(C, w, DEV)
+    _say("  max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+
+
+def test_config5_small_sketched_and_exact_ridge(C):
+    _say("config 5 shape (rank 96 + duplicates), 1 layer x 8 heads, n=7000")
+    w = W.config5(device=DEV, L=1, H=8, n=7000)
+    st, out = U.run_and_check(C, w, DEV)
+    _say("  sketched: max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+    # bit-identical rows must get bit-identical scores
+    bits = W.bf16_bits(w.requests[0].k[0, 0])
+    _, inv, cnt = np.unique(bits, axis=0, return_inverse=True, return_counts=True)
+    s0 = out["scores"][:7000].cpu().numpy()
+    for gidx in np.flatnonzero(cnt > 1)[:20]:
+        assert len(set(s0[inv == gidx].tolist())) == 1
+    w = W.config5(device=DEV, L=1, H=8, n=7000, exact=True)
+    st, _ = U.run_and_check(C, w, DEV)
+    _say("  exact ridge 1e-4: max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+
+
+def test_blend_with_attention_scores(C):
+    _say("blend: s = z(a) + 0.3 z(o)")
+    w = W.config2(device=DEV, L=1, H=4, n=4100)
+    w.requests[0].attn = W.synthetic_attention_scores(1, 4, 4100, device=DEV)
+    params, reqs = U.make_call(C, w, DEV)
+    scores, status = C.compactor_score(params, reqs)
+    torch.cuda.synchronize()
+    assert not status.any()
+    phi = params.phi.double().cpu().numpy()
+    s = scores.cpu().numpy()
+    for h in range(4):
+        K = O.bf16_bits_to_f64(W.bf16_bits(w.requests[0].k[0, h]))
+        a = w.requests[0].attn[0, h].double().cpu().numpy()
+        o = O.approx_leverage_ridge(K, phi)
+        want = O.blend_scores(a, o, W.LAMBDA_BLEND)
+        mu, sd = o.mean(), o.std()
+        zo = (o - mu) / sd
+        bound = 1e-3 * W.LAMBDA_BLEND * ((o + mu) / sd + np.abs(zo) * (1 + (mu / sd) ** 2)) + 1e-5
+        assert np.all(np.abs(s[h * 4100:(h + 1) * 4100] - want) <= bound)
+    # and the fused path selects on the blended score
+    st, _ = U.run_and_check(C, w, DEV, kept_tol_scale=50.0)
+
+
+def test_separate_calls_equal_fused_call(C):
+    _say("score + select + compact == compress, bit for bit; grouping does not change results")
+    w = W.config4(device=DEV, L=2, H=3, n_req=4, n_lo=500, n_hi=3000)
+    params, reqs = U.make_call(C, w, DEV)
+    fused = C.compactor_compress(params, reqs, want_scores=True)
+    scores, status = C.compactor_score(params, reqs)
+    kept, cnt = C.compactor_select(params, reqs, scores)
+    kp, vp = C.compactor_compact(params, reqs, kept, cnt)
+    nosc = C.compactor_compress(params, reqs, want_scores=False)
+    params_g, _ = U.make_call(C, w, DEV, group_bytes=2 * 1024 * 1024)
+    grouped = C.compactor_compress(params_g, reqs, want_scores=True)
+    grouped_nosc = C.compactor_compress(params_g, reqs, want_scores=False)
+    torch.cuda.synchronize()
+    for other in (nosc, grouped, grouped_nosc):
+        assert torch.equal(fused["kept_idx"], other["kept_idx"])
+        assert torch.equal(fused["k_packed"].view(torch.int16), other["k_packed"].view(torch.int16))
+        assert torch.equal(fused["v_packed"].view(torch.int16), other["v_packed"].view(torch.int16))
+    assert torch.equal(fused["scores"].view(torch.int32), scores.view(torch.int32))
+    assert torch.equal(fused["scores"].view(torch.int32), grouped["scores"].view(torch.int32))
+    assert torch.equal(fused["kept_idx"], kept) and torch.equal(fused["kept_cnt"], cnt)
+    assert torch.equal(fused["k_packed"].view(torch.int16), kp.view(torch.int16))
+    assert torch.equal(fused["v_packed"].view(torch.int16), vp.view(torch.int16))
+    # run-to-run determinism
+    again = C.compactor_compress(params, reqs, want_scores=True)
+    torch.cuda.synchronize()
+    assert torch.equal(fused["scores"].view(torch.int32), again["scores"].view(torch.int32))
+
+
+def test_degenerate_inputs_are_flagged_not_fatal(C):
+    _say("all-zero keys and a NaN key: status flags, finite-or-flagged outputs, valid selection")
+    L, H, n = 1, 2, 600
+    w = W.config1(device=DEV, L=L, H=H, n=n, ratio=0.5)
+    w.requests[0].k[0, 0].zero_()                                  # head 0: K = 0
+    w.requests[0].k[0, 1, 17, 5] = float("nan")                    # head 1: one NaN
+    params, reqs = U.make_call(C, w, DEV)
+    out = C.compactor_compress(params, reqs, want_scores=True)
+    torch.cuda.synchronize()
+    status = out["status"].cpu().numpy()
+    assert status[0] & C.STATUS_PIVOT
+    assert status[1] != 0
+    s = out["scores"].cpu().numpy()
+    assert np.all(s[:n] == 0)
+    kept = out["kept_idx"].cpu().numpy()
+    assert np.array_equal(kept[:300], np.arange(300))              # all tie: lowest indices win
+    assert np.all(np.diff(kept[300:]) > 0)
+
+
+def test_error_codes_reach_python(C):
+    w = W.config1(device=DEV, L=1, H=1, n=64)
+    params, reqs = U.make_call(C, w, DEV)
+    with pytest.raises(C.CompactorError) as e:
+        C.compactor_compress(params, reqs, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == C.EWORKSPACE
