@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Throughput of the fused Compactor hot path (score -> select -> compact) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--group-mb M]
+
+A step is one compactor_compress call over the whole synthetic batch, inputs already
+resident in HBM.  Prints ONE JSON line: tokens compressed per second, the roofline of the
+dominant kernel (algorithmic bytes / its HIP-event duration, against the 8 TB/s HBM peak) and
+the float64 CPU oracle timed on a bounded sample of the same workload as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=int(os.environ.get("WORLD_SIZE", "1")))
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's own)")
+    ap.add_argument("--group-mb", type=float, default=0.0, help="head-group size in MiB (0 = library default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
+    return ap.parse_args()
+
+
+def build_workload(W, cfg, dev, layers):
+    kw = {"device": dev}
+    if layers:
+        kw["L"] = layers
+    return {1: W.config1, 2: W.config2, 3: W.config3, 4: W.config4, 5: W.config5}[cfg](**kw)
+
+
+# algorithmic HBM bytes per head-row of each stage (d = 128, bf16 K/V, fp32 scores, int32 idx)
+def stage_bytes(w, kk):
+    LH = w.layers * w.kv_heads
+    rows = sum(r.n for r in w.requests) * LH
+    kept = sum(k for k in kk) * LH
+    return {
+        "gram": 256.0 * rows,                 # K read once
+        "score": 260.0 * rows,                # K read again + fp32 score written
+        "select": 8.0 * rows + 4.0 * kept,    # scores read (histogram + emit), indices written
+        "gather": 1028.0 * kept,              # idx read, K and V rows read and written
+    }, rows, kept
+
+
+def stage_flops(w, ks):
+    LH = w.layers * w.kv_heads
+    rows = sum(r.n for r in w.requests) * LH
+    m = ks if ks > 0 else 128
+    return {"gram": 2.0 * 128 * 128 * rows, "score": 2.0 * 128 * m * rows}
+
+
+def cpu_baseline(W, O, w, phi, budget_s):
+    """The oracle as it stands on the host cores, on as many heads of the workload as fit the
+    time budget (at least one), scaled linearly to all heads (heads are independent)."""
+    import numpy as np
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    LH = w.layers * w.kv_heads
+    phi_np = phi.double().cpu().numpy() if phi is not None else None
+    t_total, done, head_rows = 0.0, 0, 0
+    for b, r in enumerate(w.requests):
+        for g in range(LH):
+            l, h = divmod(g, w.kv_heads)
+            kb = W.bf16_bits(r.k[l, h])
+            vb = W.bf16_bits(r.v[l, h])
+            t0 = time.perf_counter()
+            K = O.bf16_bits_to_f64(kb)
+            O.compress_head(K, kb, vb, r.ratio, phi_np, w.ridge_rel, None, W.LAMBDA_BLEND)
+            t_total += time.perf_counter() - t0
+            done += 1
+            head_rows += r.n
+            if t_total >= budget_s:
+                break
+        if t_total >= budget_s:
+            break
+    rows_per_s = head_rows / t_total
+    tokens_per_s = rows_per_s / LH          # a token carries L*H head-rows
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d of %d heads (%d head-rows) in %.1f s, scaled linearly in heads" %
+                      (done, LH * len(w.requests), head_rows, t_total)}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (heads are independent, "
+              "so more GPUs would each take a share of the heads with no communication). "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_08143_amd import compactor as C
+    from paper_2507_08143_amd import workloads as W
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = build_workload(W, a.config, dev, a.layers)
+    phi = W.make_phi(ks=w.sketch_dim, device=dev) if w.sketch_dim > 0 else None
+    ev = C.StageEvents()
+    group_bytes = int(a.group_mb * 1024 * 1024)
+    mk = lambda events: C.Params(w.layers, w.kv_heads, sketch_dim=w.sketch_dim, phi=phi,
+                                 ridge_rel=w.ridge_rel, group_bytes=group_bytes, stage_events=events)
+    params, params_ev = mk(None), mk(ev)
+    reqs = [C.Request(k_score=r.k, v_cache=r.v, ratio=r.ratio) for r in w.requests]
+    so, ko, kk = C.compactor_layout(params, reqs)
+    nh = len(reqs) * w.layers * w.kv_heads
+
+    # every output and the workspace are allocated once, outside the timed region
+    ws = torch.empty(max(256, C.compactor_workspace_size(params, reqs)), dtype=torch.uint8, device=dev)
+    bufs = dict(kept_idx=torch.empty(ko[-1], dtype=torch.int32, device=dev),
+                kept_cnt=torch.empty(nh, dtype=torch.int32, device=dev),
+                k_packed=torch.empty(ko[-1], 128, dtype=torch.bfloat16, device=dev),
+                v_packed=torch.empty(ko[-1], 128, dtype=torch.bfloat16, device=dev),
+                status=torch.empty(nh, dtype=torch.int32, device=dev), workspace=ws)
+
+    def step(p):
+        C.compactor_compress(p, reqs, want_scores=False, **bufs)
+
+    for _ in range(a.warmup):
+        step(params)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step(params)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / a.steps * 1e3
+    tokens = w.tokens
+    value = tokens / (dt / a.steps)
+    assert int(bufs["status"].max()) == 0, "a head was flagged during the benchmark"
+
+    # the same steps again with per-stage HIP events on the launch stream
+    stage_ms = {}
+    t1 = time.perf_counter()
+    for _ in range(a.steps):
+        step(params_ev)
+        torch.cuda.synchronize()
+        for k_, v_ in ev.elapsed_ms().items():
+            stage_ms[k_] = stage_ms.get(k_, 0.0) + v_ / a.steps
+    ms_per_step_ev = (time.perf_counter() - t1) / a.steps * 1e3
+
+    sbytes, rows, kept = stage_bytes(w, kk)
+    sflops = stage_flops(w, w.sketch_dim)
+    dominant = max(sbytes, key=lambda s: stage_ms.get(s, 0.0))
+    dom_ms = stage_ms[dominant]
+    achieved = sbytes[dominant] / (dom_ms * 1e-3) / 1e9
+    stages = {}
+    for s_, ms in stage_ms.items():
+        ent = {"ms": round(ms, 4)}
+        if s_ in sbytes and ms > 0:
+            ent["GB/s"] = round(sbytes[s_] / (ms * 1e-3) / 1e9, 1)
+        if s_ in sflops and ms > 0:
+            ent["TFLOP/s"] = round(sflops[s_] / (ms * 1e-3) / 1e12, 1)
+        stages[s_] = ent
+    total_bytes = sum(sbytes.values())
+
+    out = {
+        "metric": "tokens compressed/sec (score+select+compact) at 1 GPU",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "layers": w.layers, "kv_heads": w.kv_heads, "head_dim": 128,
+                   "requests": len(reqs), "tokens": tokens, "head_rows": rows,
+                   "kept_head_rows": kept, "sketch_dim": w.sketch_dim,
+                   "group_mb": a.group_mb},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+        "path_hbm": {"algorithmic_bytes": total_bytes,
+                     "achieved_GB/s": total_bytes / (ms_per_step * 1e-3) / 1e9,
+                     "frac_of_8TB/s": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "mfma": {"path_TFLOP/s": sum(sflops.values()) / (ms_per_step * 1e-3) / 1e12,
+                 "frac_of_bf16_peak": sum(sflops.values()) / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "stages": stages, "ms_per_step_with_events": ms_per_step_ev,
+    }
+    if not a.no_cpu_baseline:
+        from oracle import compactor_oracle as O
+        out["cpu_baseline"] = cpu_baseline(W, O, w, phi, a.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -89,7 +89,24 @@ typedef struct compactor_params {
   int64_t group_bytes;    /* tuning: heads are processed in groups whose keys total about this
                              many bytes so that the second pass over a group's keys hits the
                              last-level cache; 0 = library default */
+  void  **stage_events;   /* profiling aid, normally NULL.  host array of COMPACTOR_NUM_STAGES+1
+                             hipEvent_t created by the caller: event[0] is recorded on the stream
+                             before the first kernel of a group and event[i+1] after stage i's
+                             kernel (COMPACTOR_STAGE_*), so hipEventElapsedTime(event[i],
+                             event[i+1]) is stage i's duration.  With several groups the events
+                             hold the last group's times.  Stages a call does not run leave
+                             their events unrecorded. */
 } compactor_params_t;
+
+/* stage indices for compactor_params_t.stage_events */
+#define COMPACTOR_STAGE_GRAM     0   /* partial Gram matrices K^T K (MFMA) */
+#define COMPACTOR_STAGE_REDUCE   1   /* fp64 sum of the partials */
+#define COMPACTOR_STAGE_SOLVE    2   /* sketch, Cholesky, W */
+#define COMPACTOR_STAGE_SCORE    3   /* o_i = ||W^T k_i||^2 (MFMA) */
+#define COMPACTOR_STAGE_BLEND    4   /* Eq. "scoring" (only with attn) */
+#define COMPACTOR_STAGE_SELECT   5   /* per-head top-k */
+#define COMPACTOR_STAGE_GATHER   6   /* packed K/V rows */
+#define COMPACTOR_NUM_STAGES     7
 
 /* Fills *p with the paper's defaults (Sec. 4: k = 48, lambda = 0.3), d = 128,
  * ridge_rel = 0, phi = NULL.  host. */

@@ -40,21 +40,24 @@ def _run(cmd):
     return out
 
 
-def build(verbose: bool = False, jobs: int = 6) -> str:
-    os.makedirs(BUILD, exist_ok=True)
-    objs = [os.path.join(BUILD, s.replace(".hip", ".o")) for s in SOURCES]
+def build(verbose: bool = False, jobs: int = 6, extra_flags=(), lib: str = LIB,
+          build_dir: str = BUILD) -> str:
+    """Compile every source and link `lib`.  extra_flags (e.g. -DCMP_W_TERMS=2) and a different
+    output path serve experiments; the defaults give the product library."""
+    os.makedirs(build_dir, exist_ok=True)
+    objs = [os.path.join(build_dir, s.replace(".hip", ".o")) for s in SOURCES]
 
     def compile_one(pair):
         src, obj = pair
-        return _run([HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        return _run([HIPCC, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj])
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         outs = list(ex.map(compile_one, zip(SOURCES, objs)))
-    out = _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
+    out = _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib])
     if verbose:
         print("\n".join(o for o in outs + [out] if o.strip()))
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
 
 
 if __name__ == "__main__":

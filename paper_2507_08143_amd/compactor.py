@@ -16,7 +16,7 @@ from typing import List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libcompactor.so")
+_LIB_PATH = os.environ.get("COMPACTOR_LIB", os.path.join(_HERE, "libcompactor.so"))
 
 if not os.path.exists(_LIB_PATH):
     raise ImportError(
@@ -38,7 +38,8 @@ class _Request(C.Structure):
 class _Params(C.Structure):
     _fields_ = [("layers", C.c_int32), ("kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("sketch_dim", C.c_int32), ("phi", C.c_void_p), ("ridge_rel", C.c_float),
-                ("lambda_blend", C.c_float), ("group_bytes", C.c_int64)]
+                ("lambda_blend", C.c_float), ("group_bytes", C.c_int64),
+                ("stage_events", C.c_void_p)]
 
 
 _PP, _RP = C.POINTER(_Params), C.POINTER(_Request)
@@ -70,6 +71,43 @@ EXPORTS = ["compactor_default_params", "compactor_keep_count", "compactor_layout
            "compactor_error_string", "compactor_version"]
 
 
+STAGES = ["gram", "reduce", "solve", "score", "blend", "select", "gather"]
+
+
+class StageEvents:
+    """COMPACTOR_NUM_STAGES+1 raw hipEvent_t for compactor_params_t.stage_events, created
+    through the HIP runtime that torch has already loaded."""
+
+    def __init__(self):
+        self._hip = C.CDLL("libamdhip64.so")
+        self._hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self._hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self._hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self.array = (C.c_void_p * (len(STAGES) + 1))()
+        for i in range(len(STAGES) + 1):
+            ev = C.c_void_p()
+            if self._hip.hipEventCreate(C.byref(ev)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.array[i] = ev
+
+    def elapsed_ms(self):
+        """-> {stage: ms} for the stages whose two events were recorded (after a stream sync)."""
+        out = {}
+        for i, name in enumerate(STAGES):
+            ms = C.c_float(0)
+            if self._hip.hipEventElapsedTime(C.byref(ms), self.array[i], self.array[i + 1]) == 0:
+                out[name] = float(ms.value)
+        return out
+
+    def __del__(self):
+        try:
+            for ev in self.array:
+                if ev:
+                    self._hip.hipEventDestroy(ev)
+        except Exception:
+            pass
+
+
 class CompactorError(RuntimeError):
     def __init__(self, code: int):
         self.code = code
@@ -91,14 +129,16 @@ class Params:
     lambda_blend: float = 0.3
     group_bytes: int = 0
     head_dim: int = 128
+    stage_events: Optional["StageEvents"] = None   # profiling aid (see the header)
 
     def c(self) -> _Params:
         phi = 0
         if self.phi is not None:
             assert self.phi.dtype == torch.float32 and self.phi.is_contiguous()
             phi = self.phi.data_ptr()
+        ev = C.cast(self.stage_events.array, C.c_void_p) if self.stage_events is not None else None
         return _Params(self.layers, self.kv_heads, self.head_dim, self.sketch_dim, phi,
-                       self.ridge_rel, self.lambda_blend, self.group_bytes)
+                       self.ridge_rel, self.lambda_blend, self.group_bytes, ev)
 
 
 @dataclass

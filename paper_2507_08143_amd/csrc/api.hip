@@ -149,6 +149,22 @@ int workspace_need(const compactor_params_t *p, const compactor_request_t *reqs,
     if ((expr) != hipSuccess) return COMPACTOR_EHIP; \
   } while (0)
 
+// Optional profiling events (compactor_params_t.stage_events): mark(i) records event i.
+struct Marks {
+  void **ev;
+  hipStream_t st;
+  int mark(int i) const {
+    if (ev && ev[i] && hipEventRecord(static_cast<hipEvent_t>(ev[i]), st) != hipSuccess)
+      return COMPACTOR_EHIP;
+    return COMPACTOR_OK;
+  }
+};
+#define MARK(m, i)                       \
+  do {                                   \
+    const int rc_ = (m).mark(i);         \
+    if (rc_ != COMPACTOR_OK) return rc_; \
+  } while (0)
+
 // score (+ blend) of one group
 int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows, float *scores,
                   int32_t *status, unsigned char *ws, hipStream_t st) {
@@ -157,11 +173,18 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   double *g64 = reinterpret_cast<double *>(ws + gb.partials);
   uint16_t *wt = reinterpret_cast<uint16_t *>(ws + gb.partials + gb.g64);
   const int rpw = gram_rows_for(rows);
+  const Marks m{p->stage_events, st};
+  MARK(m, 0);
   HIP_TRY(launch_gram(T, rpw, partials, st));
+  MARK(m, COMPACTOR_STAGE_GRAM + 1);
   HIP_TRY(launch_gram_reduce(T, rpw, partials, g64, st));
+  MARK(m, COMPACTOR_STAGE_REDUCE + 1);
   HIP_TRY(launch_solve(T, p->sketch_dim, p->phi, p->ridge_rel, g64, wt, status, st));
+  MARK(m, COMPACTOR_STAGE_SOLVE + 1);
   HIP_TRY(launch_score(T, p->sketch_dim, wt, scores, status, st));
+  MARK(m, COMPACTOR_STAGE_SCORE + 1);
   HIP_TRY(launch_blend(T, p->lambda_blend, scores, st));
+  MARK(m, COMPACTOR_STAGE_BLEND + 1);
   return COMPACTOR_OK;
 }
 
@@ -181,6 +204,7 @@ void compactor_default_params(compactor_params_t *p, int32_t layers, int32_t kv_
   p->ridge_rel = 0.f;
   p->lambda_blend = 0.3f;
   p->group_bytes = 0;
+  p->stage_events = nullptr;
 }
 
 int32_t compactor_keep_count(int32_t n, float ratio) {
@@ -303,9 +327,12 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
     }
     const int rc2 = enqueue_score(p, T, rows, sc, status, ws, st);
     if (rc2) return rc2;
+    const Marks m{p->stage_events, st};
     HIP_TRY(launch_select(T, sc, kept_idx, kept_cnt, st));
+    MARK(m, COMPACTOR_STAGE_SELECT + 1);
     HIP_TRY(launch_gather(T, kept_idx, static_cast<uint16_t *>(k_packed),
                           static_cast<uint16_t *>(v_packed), st));
+    MARK(m, COMPACTOR_STAGE_GATHER + 1);
     return (int)COMPACTOR_OK;
   });
 }

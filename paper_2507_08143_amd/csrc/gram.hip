@@ -11,16 +11,28 @@
 namespace cmp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef bf16x4 __attribute__((address_space(3))) *lds_bf16x4_ptr;
 
-constexpr int PITCH = 136;                 // bf16 per LDS row: 272 B keeps 16-B alignment and
-                                           // puts rows 8 apart 32 banks apart
+constexpr int PITCH = 144;                 // bf16 per LDS row: 288 B keeps 16-B alignment and
+                                           // shifts consecutive rows by 8 banks, so the 4 rows x
+                                           // 32 B that a 16-lane transpose read touches do not
+                                           // collide
 constexpr int TILE_BYTES = GRAM_TILE * PITCH * 2;
 constexpr int RED_STRIDE = 65;             // floats per (block, register) line of the reduction
 constexpr int RED_BYTES = 10 * 16 * RED_STRIDE * 4;
 constexpr int GRAM_LDS = (2 * TILE_BYTES > RED_BYTES) ? 2 * TILE_BYTES : RED_BYTES;
 
 __device__ __forceinline__ int upper_block(int I, int J) { return I * 4 - (I * (I - 1)) / 2 + (J - I); }
+
+// LDS transpose read (ds_read_b64_tr_b16): within each group of 16 lanes, lane j receives
+// element (j & 3) of the 8-byte words addressed by lanes (j >> 2), 4 + (j >> 2), 8 + (j >> 2),
+// 12 + (j >> 2).  With lane i pointing at row (i >> 2), columns 4*(i & 3).. of a row-major
+// tile, lane j ends up with column j of rows 0..3: a 4 x 16 transpose.
+__device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char *p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p));
+}
 
 __global__ __launch_bounds__(256, 2) void gram_kernel(const SegTable T, int rows_per_wg,
                                                       float *__restrict__ partials) {
@@ -42,42 +54,30 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(const SegTable T, int rows
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
 
-  uint4 stage[4];
-  auto load_tile = [&](int t) {
+  const int ntiles = (r1 - r0 + GRAM_TILE - 1) / GRAM_TILE;
+  const uint16_t *lp0 = kp + (long long)(r0 + ld_row) * stride_t + ld_chunk * 8;
+  auto load_tile = [&](int t, uint4 (&stage)[4]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row = r0 + t * GRAM_TILE + ld_row + 16 * i;
+      const int roff = t * GRAM_TILE + 16 * i;
       stage[i] = make_uint4(0, 0, 0, 0);
-      if (row < r1)
-        stage[i] = *reinterpret_cast<const uint4 *>(kp + (long long)row * stride_t + ld_chunk * 8);
+      if (t < ntiles && r0 + roff + ld_row < r1)
+        stage[i] = *reinterpret_cast<const uint4 *>(lp0 + (long long)roff * stride_t);
     }
   };
 
-  const int ntiles = (r1 - r0 + GRAM_TILE - 1) / GRAM_TILE;
-  if (ntiles > 0) load_tile(0);
+  // transpose-read addressing of this lane (see lds_read_tr): 16-lane group = (channel half,
+  // token group of 8); inside the group the lane points at token (lane>>2)&3, channels 4*(lane&3)
+  const int c16 = lane & 15, half = (lane >> 4) & 1, g = lane >> 5;
+  const int tr_off = ((16 * wave + 8 * g + (c16 >> 2)) * PITCH + 16 * half + 4 * (c16 & 3)) * 2;
 
-  const int c = lane & 31, g = lane >> 5;
-  for (int t = 0; t < ntiles; ++t) {
-    unsigned char *buf = smem + (t & 1) * TILE_BYTES;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<uint4 *>(buf + ((ld_row + 16 * i) * PITCH + ld_chunk * 8) * 2) = stage[i];
-    __syncthreads();
-    if (t + 1 < ntiles) load_tile(t + 1);
-
-    // this wave's 16 tokens: lane (c, g) gathers tokens 8g..8g+7 of channel 32*cb + c
-    const uint16_t *lp = reinterpret_cast<const uint16_t *>(buf) + (16 * wave + 8 * g) * PITCH + c;
+  auto compute_tile = [&](const unsigned char *buf) {
     bf16x8 op[4];
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb) {
-      union { uint32_t u[4]; bf16x8 v; } pk;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint32_t lo = lp[(2 * e) * PITCH + 32 * cb];
-        const uint32_t hi = lp[(2 * e + 1) * PITCH + 32 * cb];
-        pk.u[e] = lo | (hi << 16);
-      }
-      op[cb] = pk.v;
+      const bf16x4 lo = lds_read_tr(buf + tr_off + cb * 64);                    // tokens 8g .. 8g+3
+      const bf16x4 hi = lds_read_tr(buf + tr_off + cb * 64 + 4 * PITCH * 2);    // tokens 8g+4 .. 8g+7
+      op[cb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
 #pragma unroll
     for (int I = 0; I < 4; ++I)
@@ -86,6 +86,28 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(const SegTable T, int rows
         const int b = upper_block(I, J);
         acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[I], op[J], acc[b], 0, 0, 0);
       }
+  };
+  auto store_tile = [&](unsigned char *buf, const uint4 (&stage)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<uint4 *>(buf + ((ld_row + 16 * i) * PITCH + ld_chunk * 8) * 2) = stage[i];
+  };
+
+  // two tiles of global loads stay in flight while a third is being multiplied
+  uint4 stA[4], stB[4];
+  load_tile(0, stA);
+  load_tile(1, stB);
+  for (int t = 0; t < ntiles; t += 2) {
+    store_tile(smem, stA);
+    __syncthreads();
+    load_tile(t + 2, stA);
+    compute_tile(smem);
+    if (t + 1 < ntiles) {
+      store_tile(smem + TILE_BYTES, stB);
+      __syncthreads();
+      load_tile(t + 3, stB);
+      compute_tile(smem + TILE_BYTES);
+    }
   }
 
   // ---- sum the four waves' accumulators (fp32) through LDS, wave 0 collects -------------

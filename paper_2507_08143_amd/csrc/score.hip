@@ -6,6 +6,10 @@
 // bf16 planes) is staged once per workgroup in LDS and read as the A operand.  The output
 // tile D[sketch row][token] leaves every lane with 4 sketch rows of one token: squares are
 // summed in-lane and two cross-lane exchanges finish the row norm.
+//
+// W^T reaches the MFMA as a sum of bf16 planes (hi + lo = 16 mantissa bits with two planes):
+// bf16 x bf16 products are exact in the fp32 accumulator, so the only rounding besides the
+// accumulation itself is the 2^-17 relative error of the split.
 #include "common.h"
 
 namespace cmp {
@@ -15,36 +19,45 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int WPITCH = 136;   // bf16 per LDS row of W^T (272 B)
 
-template <int M, int NSUB>
+// A workgroup walks SCORE_TOKENS tokens of one head in steps of 256 (64 per wave, four 16-token
+// sub-tiles); the next step's key rows are loaded while the current step is multiplied.
+template <int M>
 __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
                                                        const uint16_t *__restrict__ wt,
                                                        float *__restrict__ scores,
                                                        int32_t *__restrict__ status) {
   __shared__ __attribute__((aligned(16))) uint16_t wl[W_TERMS * M * WPITCH];
-  constexpr int TOK_WG = 4 * 16 * NSUB;
+  constexpr int NSUB = 4, STEP = 4 * 16 * NSUB;
 
-  const Where w = locate_block(T, blockIdx.x, TOK_WG, false);
+  const Where w = locate_block(T, blockIdx.x, SCORE_TOKENS, false);
   const Seg &s = T.s[w.seg];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int t16 = lane & 15, g = lane >> 4;
   const int n = s.n;
-  const int tok0 = w.tile * TOK_WG + wave * (16 * NSUB);
+  const int tok_begin = w.tile * SCORE_TOKENS;
+  const int tok_end = min(n, tok_begin + SCORE_TOKENS);
+  const int nsteps = (tok_end - tok_begin + STEP - 1) / STEP;
+  const long long stride_t = s.stride_t;
+  const uint16_t *kp = head_ptr(s.k_score, s, w.head) + 8 * g;
 
-  // key rows -> B operands (issued first so that they fly while W^T is staged)
-  const uint16_t *kp = head_ptr(s.k_score, s, w.head);
-  uint4 kb[NSUB][4];
+  // key rows -> MFMA B operands: lane (t16, g) takes channels 32*kk + 8*g .. +7 of token t16
+  auto load_step = [&](int it, uint4 (&kb)[NSUB][4]) {
+    const int base = tok_begin + it * STEP + wave * (16 * NSUB) + t16;
 #pragma unroll
-  for (int st = 0; st < NSUB; ++st) {
-    const int tok = tok0 + 16 * st + t16;
-    const uint16_t *rp = kp + (long long)tok * s.stride_t + 8 * g;
+    for (int st = 0; st < NSUB; ++st) {
+      const int tok = base + 16 * st;
+      const uint16_t *rp = kp + (long long)tok * stride_t;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      kb[st][kk] = make_uint4(0, 0, 0, 0);
-      if (tok < n) kb[st][kk] = *reinterpret_cast<const uint4 *>(rp + 32 * kk);
+      for (int kk = 0; kk < 4; ++kk) {
+        kb[st][kk] = make_uint4(0, 0, 0, 0);
+        if (it < nsteps && tok < tok_end) kb[st][kk] = *reinterpret_cast<const uint4 *>(rp + 32 * kk);
+      }
     }
-  }
+  };
 
-  // W^T of this head -> LDS
+  uint4 kbA[NSUB][4], kbB[NSUB][4];
+  load_step(0, kbA);          // in flight while W^T is staged
+
   const uint16_t *wh = wt + (size_t)w.lhead * (W_TERMS * M * D);
   for (int cidx = tid; cidx < W_TERMS * M * 16; cidx += 256) {
     const int row = cidx >> 4, ch = cidx & 15;
@@ -53,47 +66,58 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
   }
   __syncthreads();
 
-  float sums[NSUB];
-#pragma unroll
-  for (int st = 0; st < NSUB; ++st) sums[st] = 0.f;
-
-#pragma unroll
-  for (int jb = 0; jb < M / 16; ++jb) {
-    f32x4 acc[NSUB];
-#pragma unroll
-    for (int st = 0; st < NSUB; ++st) acc[st] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-      for (int t = 0; t < W_TERMS; ++t) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
-            &wl[(t * M + jb * 16 + t16) * WPITCH + 32 * kk + 8 * g]);
-#pragma unroll
-        for (int st = 0; st < NSUB; ++st) {
-          union { uint4 u; bf16x8 v; } b;
-          b.u = kb[st][kk];
-          acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b.v, acc[st], 0, 0, 0);
-        }
-      }
-    }
-#pragma unroll
-    for (int st = 0; st < NSUB; ++st)
-      sums[st] += acc[st][0] * acc[st][0] + acc[st][1] * acc[st][1] + acc[st][2] * acc[st][2] +
-                  acc[st][3] * acc[st][3];
-  }
-
-  // lanes t16, t16+16, t16+32, t16+48 hold the four quarter-sums of token t16
   float *sp = scores + s.score_off + (long long)w.head * n;
   bool bad = false;
+
+  auto compute_step = [&](int it, const uint4 (&kb)[NSUB][4]) {
+    float sums[NSUB];
 #pragma unroll
-  for (int st = 0; st < NSUB; ++st) {
-    float x = sums[st];
-    x += __shfl_xor(x, 16);
-    x += __shfl_xor(x, 32);
-    const int tok = tok0 + 16 * st + t16;
-    if ((st & 3) == g && tok < n) {
+    for (int st = 0; st < NSUB; ++st) sums[st] = 0.f;
+#pragma unroll 1
+    for (int jb = 0; jb < M / 16; ++jb) {   // kept rolled: unrolling hoists every W^T operand
+      f32x4 acc[NSUB];
+#pragma unroll
+      for (int st = 0; st < NSUB; ++st) acc[st] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+        for (int t = 0; t < W_TERMS; ++t) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
+              &wl[(t * M + jb * 16 + t16) * WPITCH + 32 * kk + 8 * g]);
+#pragma unroll
+          for (int st = 0; st < NSUB; ++st) {
+            union { uint4 u; bf16x8 v; } b;
+            b.u = kb[st][kk];
+            acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b.v, acc[st], 0, 0, 0);
+          }
+        }
+      }
+#pragma unroll
+      for (int st = 0; st < NSUB; ++st)
+        sums[st] += acc[st][0] * acc[st][0] + acc[st][1] * acc[st][1] + acc[st][2] * acc[st][2] +
+                    acc[st][3] * acc[st][3];
+    }
+    // lanes (t16, g = 0..3) hold the four quarter-sums of token t16 of every sub-tile; a
+    // two-step exchange leaves lane (t16, g) with the full sum of sub-tile g
+    const bool up2 = g & 2, up1 = g & 1;
+    float k0 = up2 ? sums[2] : sums[0], k1 = up2 ? sums[3] : sums[1];
+    k0 += __shfl_xor(up2 ? sums[0] : sums[2], 32);
+    k1 += __shfl_xor(up2 ? sums[1] : sums[3], 32);
+    float x = up1 ? k1 : k0;
+    x += __shfl_xor(up1 ? k0 : k1, 16);
+    const int tok = tok_begin + it * STEP + wave * (16 * NSUB) + lane;   // = ... + 16*g + t16
+    if (tok < tok_end) {
       sp[tok] = x;
       bad |= !(fabsf(x) <= 3.0e38f);
+    }
+  };
+
+  for (int it = 0; it < nsteps; it += 2) {
+    load_step(it + 1, kbB);
+    compute_step(it, kbA);
+    if (it + 1 < nsteps) {
+      load_step(it + 2, kbA);
+      compute_step(it + 1, kbB);
     }
   }
   if (__any(bad)) {
@@ -106,8 +130,8 @@ static hipError_t launch_m(const SegTable &T, const uint16_t *wt, float *scores,
                            hipStream_t st) {
   const long long nb = total_blocks(T, SCORE_TOKENS, false);
   if (nb <= 0) return hipSuccess;
-  hipLaunchKernelGGL((score_kernel<M, SCORE_SUB>), dim3((unsigned)nb), dim3(256), 0, st, T, wt,
-                     scores, status);
+  hipLaunchKernelGGL((score_kernel<M>), dim3((unsigned)nb), dim3(256), 0, st, T, wt, scores,
+                     status);
   return hipGetLastError();
 }
 

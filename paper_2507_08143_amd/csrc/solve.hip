@@ -170,10 +170,167 @@ __global__ __launch_bounds__(256) void solve_kernel(const SegTable T, int m,
   if (tid == 0) status[sg.ghead0 + w.head] = flag;
 }
 
+// ---- sketched mode, compile-time order M (k_s): the fast path ------------------------------
+// Phases: T = G Phi (registers, Phi broadcast from LDS) -> S = Phi^T T (3x3 register blocks)
+// -> Cholesky with one barrier per step (columns stay unscaled until the end)
+// -> forward substitution L y = Phi[ch][:]^T with y in registers, one channel per thread.
+template <int M>
+__global__ __launch_bounds__(256) void solve_sketched_kernel(const SegTable T,
+                                                             const float *__restrict__ phi,
+                                                             float ridge_rel,
+                                                             const double *__restrict__ g64,
+                                                             uint16_t *__restrict__ wt,
+                                                             int32_t *__restrict__ status) {
+  constexpr int SP = M + 1, TP = M + 1, MB = M / 16, HB = M / 2;
+  __shared__ double S[M * SP];
+  __shared__ double TA[D * TP];
+  __shared__ __attribute__((aligned(16))) float PH[D * M];
+  __shared__ double piv_s[M];
+  __shared__ double d0[M];
+  __shared__ int flag;
+
+  const int lhead = blockIdx.x;
+  const Where w = locate_head(T, lhead);
+  const Seg &sg = T.s[w.seg];
+  const double *G = g64 + (size_t)lhead * (D * D);
+  const int tid = threadIdx.x;
+  if (tid == 0) flag = 0;
+  for (int idx = tid; idx < D * M / 4; idx += 256)
+    reinterpret_cast<float4 *>(PH)[idx] = reinterpret_cast<const float4 *>(phi)[idx];
+  __syncthreads();
+
+  {  // T = G Phi: thread (i, half) owns T[i][half*HB .. half*HB+HB)
+    const int i = tid & 127;
+    const int half = __builtin_amdgcn_readfirstlane(tid >> 7);
+    double acc[HB];
+#pragma unroll
+    for (int bb = 0; bb < HB; ++bb) acc[bb] = 0.0;
+    for (int j0 = 0; j0 < D; j0 += 8) {
+      double g[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) g[u] = G[(j0 + u) * D + i];   // symmetric: column i as row reads
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float4 *pr = reinterpret_cast<const float4 *>(&PH[(j0 + u) * M + half * HB]);
+#pragma unroll
+        for (int q = 0; q < HB / 4; ++q) {
+          const float4 f = pr[q];
+          acc[4 * q + 0] += g[u] * (double)f.x;
+          acc[4 * q + 1] += g[u] * (double)f.y;
+          acc[4 * q + 2] += g[u] * (double)f.z;
+          acc[4 * q + 3] += g[u] * (double)f.w;
+        }
+      }
+    }
+#pragma unroll
+    for (int bb = 0; bb < HB; ++bb) TA[i * TP + half * HB + bb] = acc[bb];
+  }
+  __syncthreads();
+
+  {  // S = Phi^T T, lower 16x16 block pairs; thread (ta, tb) owns an MB x MB register block
+    const int ta = tid >> 4, tb = tid & 15;
+    double acc[MB][MB];
+#pragma unroll
+    for (int x = 0; x < MB; ++x)
+#pragma unroll
+      for (int y = 0; y < MB; ++y) acc[x][y] = 0.0;
+    for (int i = 0; i < D; ++i) {
+      double pa[MB], tv[MB];
+#pragma unroll
+      for (int x = 0; x < MB; ++x) pa[x] = (double)PH[i * M + ta + 16 * x];
+#pragma unroll
+      for (int y = 0; y < MB; ++y) tv[y] = TA[i * TP + tb + 16 * y];
+#pragma unroll
+      for (int x = 0; x < MB; ++x)
+#pragma unroll
+        for (int y = 0; y <= x; ++y) acc[x][y] += pa[x] * tv[y];
+    }
+#pragma unroll
+    for (int x = 0; x < MB; ++x)
+#pragma unroll
+      for (int y = 0; y <= x; ++y) S[(ta + 16 * x) * SP + tb + 16 * y] = acc[x][y];
+  }
+  __syncthreads();
+
+  double tr = 0.0;
+  for (int a = 0; a < M; ++a) tr += S[a * SP + a];
+  const double rho = (double)ridge_rel * tr / (double)M;
+  __syncthreads();
+  if (tid < M) {
+    const double v = S[tid * SP + tid] + rho;
+    S[tid * SP + tid] = v;
+    d0[tid] = v;
+  }
+
+  // Cholesky, one barrier per step: column k keeps the values L[i][k] * L[k][k] until the end
+  const int tx = tid & 15, ty = tid >> 4;
+  for (int k = 0; k < M; ++k) {
+    __syncthreads();
+    const double piv = S[k * SP + k];
+    const bool ok = piv > PIVOT_REL * d0[k] && piv < 1.0e300;
+    if (tid == 0) {
+      piv_s[k] = ok ? piv : 0.0;
+      if (!ok) flag = COMPACTOR_STATUS_PIVOT;
+    }
+    if (ok) {
+      const double inv = 1.0 / piv;
+      for (int i = k + 1 + ty; i < M; i += 16) {
+        const double lik = S[i * SP + k] * inv;
+        for (int j = k + 1 + tx; j <= i; j += 16) S[i * SP + j] -= lik * S[j * SP + k];
+      }
+    }
+  }
+  __syncthreads();
+  // scale the columns: L[i][k] = S[i][k] / sqrt(piv_k); dropped columns become exact zeros
+  for (int idx = tid; idx < M * M; idx += 256) {
+    const int i = idx / M, k = idx - i * M;
+    if (k < i) {
+      const double pk = piv_s[k];
+      S[i * SP + k] = pk > 0.0 ? S[i * SP + k] / sqrt(pk) : 0.0;
+    }
+  }
+  __syncthreads();
+
+  // W^T[:, ch] = L^{-1} Phi[ch, :]^T by forward substitution, one channel per thread
+  if (tid < D) {
+    const int ch = tid;
+    double y[M];
+#pragma unroll
+    for (int j = 0; j < M; ++j) {
+      double v = (double)PH[ch * M + j];
+#pragma unroll
+      for (int q = 0; q < j; ++q) v -= S[j * SP + q] * y[q];
+      const double pj = piv_s[j];
+      y[j] = pj > 0.0 ? v / sqrt(pj) : 0.0;
+    }
+    uint16_t *wh = wt + (size_t)lhead * (W_TERMS * M * D);
+#pragma unroll
+    for (int j = 0; j < M; ++j) {
+      float x = (float)y[j];
+#pragma unroll
+      for (int t = 0; t < W_TERMS; ++t) {
+        const uint16_t b = bf16_rne(x);
+        wh[(t * M + j) * D + ch] = b;
+        x -= bf16_to_f32(b);
+      }
+    }
+  }
+  if (tid == 0) status[sg.ghead0 + w.head] = flag;
+}
+
 hipError_t launch_solve(const SegTable &T, int ks, const float *phi, float ridge_rel,
                         const double *g64, uint16_t *wt, int32_t *status, hipStream_t st) {
   if (T.nheads <= 0) return hipSuccess;
-  if (ks > 0) {
+  const dim3 grid((unsigned)T.nheads), block(256);
+  if (ks == 16) {
+    hipLaunchKernelGGL((solve_sketched_kernel<16>), grid, block, 0, st, T, phi, ridge_rel, g64, wt, status);
+  } else if (ks == 32) {
+    hipLaunchKernelGGL((solve_sketched_kernel<32>), grid, block, 0, st, T, phi, ridge_rel, g64, wt, status);
+  } else if (ks == 48) {
+    hipLaunchKernelGGL((solve_sketched_kernel<48>), grid, block, 0, st, T, phi, ridge_rel, g64, wt, status);
+  } else if (ks == 64) {
+    hipLaunchKernelGGL((solve_sketched_kernel<64>), grid, block, 0, st, T, phi, ridge_rel, g64, wt, status);
+  } else if (ks > 0) {
     hipLaunchKernelGGL((solve_kernel<64, true>), dim3((unsigned)T.nheads), dim3(256), 0, st, T, ks,
                        phi, ridge_rel, g64, wt, status);
   } else {
