@@ -53,7 +53,7 @@ int check_requests(const compactor_request_t *reqs, int32_t nreq, int need) {
   return COMPACTOR_OK;
 }
 
-// Rows of one Gram workgroup: large enough that the 64 KB partial it writes stays a small
+// Rows of one Gram workgroup: large enough that the 40 KB partial it writes stays a small
 // fraction of the keys it reads, small enough that the launch fills 256 compute units.
 int gram_rows_for(long long group_rows) {
   int rows = 4096;
@@ -71,7 +71,7 @@ GroupBytes group_bytes_needed(const SegTable &T, int ks, bool need_scores) {
   for (int i = 0; i < T.nseg; ++i) rows += (long long)T.s[i].n * T.s[i].head_count;
   const int m = ks > 0 ? ks : D;
   GroupBytes g;
-  g.partials = align_up((size_t)total_blocks(T, gram_rows_for(rows), false) * D * D * sizeof(float));
+  g.partials = align_up((size_t)total_blocks(T, gram_rows_for(rows), false) * GRAM_PARTIAL_FLOATS * sizeof(float));
   g.g64 = align_up((size_t)T.nheads * D * D * sizeof(double));
   g.wt = align_up((size_t)T.nheads * W_TERMS * m * D * sizeof(uint16_t));
   g.scores = need_scores ? align_up((size_t)rows * sizeof(float)) : 0;

