@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's own)")
     ap.add_argument("--group-mb", type=float, default=0.0, help="head-group size in MiB (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--allow-flagged", action="store_true",
+                    help="do not fail when a head reports a status flag (kernel experiments only)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
     return ap.parse_args()
 
@@ -144,7 +146,7 @@ def main():
     ms_per_step = dt / a.steps * 1e3
     tokens = w.tokens
     value = tokens / (dt / a.steps)
-    assert int(bufs["status"].max()) == 0, "a head was flagged during the benchmark"
+    assert a.allow_flagged or int(bufs["status"].max()) == 0, "a head was flagged during the benchmark"
 
     # the same steps again with per-stage HIP events on the launch stream
     stage_ms = {}

@@ -95,6 +95,14 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
         const bf16x4 hi = lds_read_tr(p + cb * 64 + 4 * PITCH * 2);    // tokens 8g+4 .. 8g+7
         op[cb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
+#if defined(GRAM_ABLATE) && GRAM_ABLATE >= 1
+      {  // experiment: keep the LDS reads alive without MFMA
+        union { bf16x8 v; float f[4]; } u0, u1, u2, u3;
+        u0.v = op[0]; u1.v = op[1]; u2.v = op[2]; u3.v = op[3];
+        acc[0][0] += u0.f[0] + u1.f[1] + u2.f[2] + u3.f[3];
+        continue;
+      }
+#endif
       switch (wave) {
         case 0: GRAM_MFMA(0, 0, 0); GRAM_MFMA(1, 0, 1); GRAM_MFMA(2, 0, 2); break;
         case 1: GRAM_MFMA(0, 0, 3); GRAM_MFMA(1, 1, 1); GRAM_MFMA(2, 1, 2); break;
@@ -114,6 +122,28 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
   uint4 stA[4], stB[4];
   load_tile(0, stA);
   load_tile(1, stB);
+#if defined(GRAM_ABLATE) && GRAM_ABLATE >= 3
+  for (int t = 0; t < ntiles; t += 2) {   // experiment: global loads only
+    acc[0][1] += __uint_as_float(stA[0].x ^ stA[1].y ^ stA[2].z ^ stA[3].w);
+    load_tile(t + 2, stA);
+    acc[0][2] += __uint_as_float(stB[0].x ^ stB[1].y ^ stB[2].z ^ stB[3].w);
+    load_tile(t + 3, stB);
+  }
+  if (false)
+#elif defined(GRAM_ABLATE) && GRAM_ABLATE == 2
+  for (int t = 0; t < ntiles; t += 2) {   // experiment: loads + LDS writes + barriers
+    store_tile(smem, stA);
+    __syncthreads();
+    load_tile(t + 2, stA);
+    if (t + 1 < ntiles) {
+      store_tile(smem + TILE_BYTES, stB);
+      __syncthreads();
+      load_tile(t + 3, stB);
+    }
+  }
+  acc[0][3] += smem[tid];
+  if (false)
+#endif
   for (int t = 0; t < ntiles; t += 2) {
     store_tile(smem, stA);
     __syncthreads();

@@ -1,9 +1,9 @@
 // Per-row quadratic form (paper Algorithm 1 lines 5-6): o_i = || W^T k_i ||^2, the squared row
 // norm of U~ = K_hat V~ Sigma~^{-1} written with the Cholesky factor instead of the SVD.
 //
-// The contraction runs over the channel axis, which is contiguous in memory, so key rows go
-// straight from global memory into MFMA B operands (16 B per lane); W^T (k_s x 128, three
-// bf16 planes) is staged once per workgroup in LDS and read as the A operand.  The output
+// The contraction runs over the channel axis, which is contiguous in memory, so a key row is an
+// MFMA B operand as it stands (16 B per lane); W^T (k_s x 128, as bf16 planes) is staged once
+// per workgroup in LDS and read as the A operand.  The output
 // tile D[sketch row][token] leaves every lane with 4 sketch rows of one token: squares are
 // summed in-lane and two cross-lane exchanges finish the row norm.
 //
@@ -17,17 +17,28 @@ namespace cmp {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int WPITCH = 136;   // bf16 per LDS row of W^T (272 B)
+constexpr int WPITCH = 136;   // bf16 per LDS row of W^T and of staged key rows (272 B)
 
-// A workgroup walks SCORE_TOKENS tokens of one head in steps of 256 (64 per wave, four 16-token
-// sub-tiles); the next step's key rows are loaded while the current step is multiplied.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// A workgroup walks SCORE_TOKENS tokens of one head in steps of 128 (32 per wave, two 16-token
+// sub-tiles).  Key rows arrive with fully coalesced streaming loads (a wave instruction covers
+// four whole 256-byte rows), pass through a wave-private LDS buffer, and are read back in the
+// MFMA B-operand arrangement; two steps of loads are in flight while a third is multiplied.
+// Nothing in the loop needs a workgroup barrier: a wave only reads what it wrote itself.
 template <int M>
 __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
                                                        const uint16_t *__restrict__ wt,
                                                        float *__restrict__ scores,
                                                        int32_t *__restrict__ status) {
+  constexpr int NSUB = 2, WTOK = 16 * NSUB, STEP = 4 * WTOK;     // tokens per wave / per WG step
+  constexpr int NLD = WTOK * 16 / 64;                            // 16-B loads per lane per step
   __shared__ __attribute__((aligned(16))) uint16_t wl[W_TERMS * M * WPITCH];
-  constexpr int NSUB = 4, STEP = 4 * 16 * NSUB;
+  __shared__ __attribute__((aligned(16))) uint16_t kl[4][WTOK * WPITCH];
 
   const Where w = locate_block(T, blockIdx.x, SCORE_TOKENS, false);
   const Seg &s = T.s[w.seg];
@@ -38,25 +49,23 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
   const int tok_end = min(n, tok_begin + SCORE_TOKENS);
   const int nsteps = (tok_end - tok_begin + STEP - 1) / STEP;
   const long long stride_t = s.stride_t;
-  const uint16_t *kp = head_ptr(s.k_score, s, w.head) + 8 * g;
+  const uint16_t *kp = head_ptr(s.k_score, s, w.head);
+  const int ld_row = lane >> 4, ld_chunk = lane & 15;            // loader: 16 lanes per row
 
-  // key rows -> MFMA B operands: lane (t16, g) takes channels 32*kk + 8*g .. +7 of token t16
-  auto load_step = [&](int it, uint4 (&kb)[NSUB][4]) {
-    const int base = tok_begin + it * STEP + wave * (16 * NSUB) + t16;
+  auto load_step = [&](int it, uint4 (&stg)[NLD]) {
+    const int base = tok_begin + it * STEP + wave * WTOK + ld_row;
 #pragma unroll
-    for (int st = 0; st < NSUB; ++st) {
-      const int tok = base + 16 * st;
-      const uint16_t *rp = kp + (long long)tok * stride_t;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        kb[st][kk] = make_uint4(0, 0, 0, 0);
-        if (it < nsteps && tok < tok_end) kb[st][kk] = load_stream16(rp + 32 * kk);
-      }
+    for (int i = 0; i < NLD; ++i) {
+      const int tok = base + 4 * i;
+      stg[i] = make_uint4(0, 0, 0, 0);
+      if (it < nsteps && tok < tok_end)
+        stg[i] = load_stream16(kp + (long long)tok * stride_t + ld_chunk * 8);
     }
   };
 
-  uint4 kbA[NSUB][4], kbB[NSUB][4];
-  load_step(0, kbA);          // in flight while W^T is staged
+  uint4 stA[NLD], stB[NLD];
+  load_step(0, stA);          // in flight while W^T is staged
+  load_step(1, stB);
 
   const uint16_t *wh = wt + (size_t)w.lhead * (W_TERMS * M * D);
   for (int cidx = tid; cidx < W_TERMS * M * 16; cidx += 256) {
@@ -67,12 +76,47 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
   __syncthreads();
 
   float *sp = scores + s.score_off + (long long)w.head * n;
+  uint16_t *kw = kl[wave];
   bool bad = false;
 
-  auto compute_step = [&](int it, const uint4 (&kb)[NSUB][4]) {
+  auto compute_step = [&](int it, const uint4 (&stg)[NLD]) {
+#if defined(SCORE_ABLATE) && SCORE_ABLATE == 3
+    {   // experiment: global loads only
+      float x = 0.f;
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) x += __uint_as_float(stg[i].x ^ stg[i].w);
+      const int tok = tok_begin + it * STEP + wave * WTOK + (lane & 31);
+      if (g < 2 && tok < tok_end) sp[tok] = x;
+      return;
+    }
+#endif
+    // redistribute through the wave's LDS buffer: rows in, B operands out.  Lanes exchange
+    // data here without a workgroup barrier (LDS operations of one wave execute in order), so
+    // wave-scope fences keep the compiler from moving the reads and writes across each other.
+    wave_lds_fence();
+#pragma unroll
+    for (int i = 0; i < NLD; ++i)
+      *reinterpret_cast<uint4 *>(&kw[(ld_row + 4 * i) * WPITCH + ld_chunk * 8]) = stg[i];
+    wave_lds_fence();
+    bf16x8 kb[NSUB][4];
+#pragma unroll
+    for (int st = 0; st < NSUB; ++st)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        kb[st][kk] = *reinterpret_cast<const bf16x8 *>(&kw[(16 * st + t16) * WPITCH + 32 * kk + 8 * g]);
+
     float sums[NSUB];
 #pragma unroll
     for (int st = 0; st < NSUB; ++st) sums[st] = 0.f;
+#if defined(SCORE_ABLATE) && SCORE_ABLATE == 2
+    {   // experiment: loads + LDS redistribution, no W^T reads, no MFMA
+#pragma unroll
+      for (int st = 0; st < NSUB; ++st)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) { union { bf16x8 v; float f[4]; } u; u.v = kb[st][kk]; sums[st] += u.f[0] + u.f[3]; }
+    }
+    if (false)
+#endif
 #pragma unroll 1
     for (int jb = 0; jb < M / 16; ++jb) {   // kept rolled: unrolling hoists every W^T operand
       f32x4 acc[NSUB];
@@ -85,11 +129,8 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
           const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
               &wl[(t * M + jb * 16 + t16) * WPITCH + 32 * kk + 8 * g]);
 #pragma unroll
-          for (int st = 0; st < NSUB; ++st) {
-            union { uint4 u; bf16x8 v; } b;
-            b.u = kb[st][kk];
-            acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b.v, acc[st], 0, 0, 0);
-          }
+          for (int st = 0; st < NSUB; ++st)
+            acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, kb[st][kk], acc[st], 0, 0, 0);
         }
       }
 #pragma unroll
@@ -97,27 +138,26 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
         sums[st] += acc[st][0] * acc[st][0] + acc[st][1] * acc[st][1] + acc[st][2] * acc[st][2] +
                     acc[st][3] * acc[st][3];
     }
-    // lanes (t16, g = 0..3) hold the four quarter-sums of token t16 of every sub-tile; a
-    // two-step exchange leaves lane (t16, g) with the full sum of sub-tile g
-    const bool up2 = g & 2, up1 = g & 1;
-    float k0 = up2 ? sums[2] : sums[0], k1 = up2 ? sums[3] : sums[1];
-    k0 += __shfl_xor(up2 ? sums[0] : sums[2], 32);
-    k1 += __shfl_xor(up2 ? sums[1] : sums[3], 32);
-    float x = up1 ? k1 : k0;
-    x += __shfl_xor(up1 ? k0 : k1, 16);
-    const int tok = tok_begin + it * STEP + wave * (16 * NSUB) + lane;   // = ... + 16*g + t16
-    if (tok < tok_end) {
+    // lanes (t16, g = 0..3) hold the four quarter-sums of token t16 of both sub-tiles; after
+    // the exchange lanes with g < 2 hold the full sum of sub-tile g
+    float x0 = sums[0] + __shfl_xor(sums[0], 32);
+    float x1 = sums[1] + __shfl_xor(sums[1], 32);
+    const bool up = g & 1;
+    float x = up ? x1 : x0;
+    x += __shfl_xor(up ? x0 : x1, 16);
+    const int tok = tok_begin + it * STEP + wave * WTOK + (lane & 31);   // 16*(g&1) + t16
+    if (g < 2 && tok < tok_end) {
       sp[tok] = x;
       bad |= !(fabsf(x) <= 3.0e38f);
     }
   };
 
   for (int it = 0; it < nsteps; it += 2) {
-    load_step(it + 1, kbB);
-    compute_step(it, kbA);
+    compute_step(it, stA);
+    load_step(it + 2, stA);
     if (it + 1 < nsteps) {
-      load_step(it + 2, kbA);
-      compute_step(it + 1, kbB);
+      compute_step(it + 1, stB);
+      load_step(it + 3, stB);
     }
   }
   if (__any(bad)) {
