@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's own)")
     ap.add_argument("--group-mb", type=float, default=0.0, help="head-group size in MiB (0 = library default)")
+    ap.add_argument("--gram-rows", type=int, default=0, help="tuning override (0 = library's choice)")
+    ap.add_argument("--score-tokens", type=int, default=0, help="tuning override (0 = library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--allow-flagged", action="store_true",
                     help="do not fail when a head reports a status flag (kernel experiments only)")
@@ -118,7 +120,8 @@ def main():
     ev = C.StageEvents()
     group_bytes = int(a.group_mb * 1024 * 1024)
     mk = lambda events: C.Params(w.layers, w.kv_heads, sketch_dim=w.sketch_dim, phi=phi,
-                                 ridge_rel=w.ridge_rel, group_bytes=group_bytes, stage_events=events)
+                                 ridge_rel=w.ridge_rel, group_bytes=group_bytes, stage_events=events,
+                                 gram_rows=a.gram_rows, score_tokens=a.score_tokens)
     params, params_ev = mk(None), mk(ev)
     reqs = [C.Request(k_score=r.k, v_cache=r.v, ratio=r.ratio) for r in w.requests]
     so, ko, kk = C.compactor_layout(params, reqs)

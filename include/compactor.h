@@ -89,6 +89,8 @@ typedef struct compactor_params {
   int64_t group_bytes;    /* tuning: heads are processed in groups whose keys total about this
                              many bytes so that the second pass over a group's keys hits the
                              last-level cache; 0 = library default */
+  int32_t gram_rows;      /* tuning: target key rows per workgroup of the Gram kernel and target */
+  int32_t score_tokens;   /* tokens per workgroup of the score kernel; 0 = chosen by the library */
   void  **stage_events;   /* profiling aid, normally NULL.  host array of COMPACTOR_NUM_STAGES+1
                              hipEvent_t created by the caller: event[0] is recorded on the stream
                              before the first kernel of a group and event[i+1] after stage i's

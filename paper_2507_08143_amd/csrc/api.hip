@@ -30,7 +30,7 @@ int check_params(const compactor_params_t *p, bool scoring) {
     if (!(p->ridge_rel >= 0.f) || !isfinite(p->ridge_rel)) return COMPACTOR_EINVAL;
     if (!isfinite(p->lambda_blend)) return COMPACTOR_EINVAL;
   }
-  if (p->group_bytes < 0) return COMPACTOR_EINVAL;
+  if (p->group_bytes < 0 || p->gram_rows < 0 || p->score_tokens < 0) return COMPACTOR_EINVAL;
   return COMPACTOR_OK;
 }
 
@@ -53,12 +53,41 @@ int check_requests(const compactor_request_t *reqs, int32_t nreq, int need) {
   return COMPACTOR_OK;
 }
 
-// Rows of one Gram workgroup: large enough that the 40 KB partial it writes stays a small
-// fraction of the keys it reads, small enough that the launch fills 256 compute units.
-int gram_rows_for(long long group_rows) {
-  int rows = 4096;
-  while (rows > 512 && group_rows / rows < 1024) rows >>= 1;
-  return rows;
+// Work per workgroup of a streaming kernel.  Workgroups of one launch are equal in size and the
+// device runs `slots` of them at a time, so a launch of W workgroups takes ceil(W / slots)
+// rounds; the chunk is chosen to keep the last round full and the per-workgroup fixed cost
+// (fixed_bytes of extra traffic against chunk * 256 bytes of keys) small.
+int pick_chunk(const SegTable &T, int lo, int hi, int step, int slots, double fixed_bytes) {
+  int best = hi;
+  double best_score = -1.0;
+  for (int c = hi; c >= lo; c -= step) {
+    const double w = (double)total_blocks(T, c, step, false);
+    const double rounds = ceil(w / slots);
+    const double fill = w / (rounds * slots);
+    const double score = fill * (c * 256.0) / (c * 256.0 + fixed_bytes);
+    if (score > best_score + 1e-9) { best_score = score; best = c; }
+  }
+  return best;
+}
+
+int compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+    n = 256;
+  return n;
+}
+
+// Gram: 3 workgroups per compute unit; a workgroup writes a 40 KB partial that is read back once.
+int gram_rows_for(const compactor_params_t *p, const SegTable &T, int cus) {
+  if (p->gram_rows > 0) return (p->gram_rows + GRAM_TILE - 1) / GRAM_TILE * GRAM_TILE;
+  return pick_chunk(T, 512, 4096, GRAM_TILE, 3 * cus, 2.0 * GRAM_PARTIAL_FLOATS * sizeof(float));
+}
+
+// Score: 2 workgroups per compute unit; a workgroup stages W^T (about 26 KB) once.
+int score_tokens_for(const compactor_params_t *p, const SegTable &T, int cus) {
+  if (p->score_tokens > 0) return (p->score_tokens + SCORE_STEP - 1) / SCORE_STEP * SCORE_STEP;
+  return pick_chunk(T, 1024, 4096, SCORE_STEP, 2 * cus, 32768.0);
 }
 
 struct GroupBytes {
@@ -66,12 +95,14 @@ struct GroupBytes {
   size_t total() const { return partials + g64 + wt + scores; }
 };
 
-GroupBytes group_bytes_needed(const SegTable &T, int ks, bool need_scores) {
+GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bool need_scores) {
+  const int ks = p->sketch_dim;
   long long rows = 0;
   for (int i = 0; i < T.nseg; ++i) rows += (long long)T.s[i].n * T.s[i].head_count;
   const int m = ks > 0 ? ks : D;
   GroupBytes g;
-  g.partials = align_up((size_t)total_blocks(T, gram_rows_for(rows), false) * GRAM_PARTIAL_FLOATS * sizeof(float));
+  g.partials = align_up((size_t)total_blocks(T, gram_rows_for(p, T, compute_units()), GRAM_TILE, false) *
+                        GRAM_PARTIAL_FLOATS * sizeof(float));
   g.g64 = align_up((size_t)T.nheads * D * D * sizeof(double));
   g.wt = align_up((size_t)T.nheads * W_TERMS * m * D * sizeof(uint16_t));
   g.scores = need_scores ? align_up((size_t)rows * sizeof(float)) : 0;
@@ -136,7 +167,7 @@ int workspace_need(const compactor_params_t *p, const compactor_request_t *reqs,
   size_t need = 0;
   const int rc = for_each_group(p, reqs, nreq, group_rows_of(p), local_scores,
                                 [&](const SegTable &T, long long) {
-                                  const size_t t = group_bytes_needed(T, p->sketch_dim, local_scores).total();
+                                  const size_t t = group_bytes_needed(p, T, local_scores).total();
                                   if (t > need) need = t;
                                   return COMPACTOR_OK;
                                 });
@@ -168,11 +199,12 @@ struct Marks {
 // score (+ blend) of one group
 int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows, float *scores,
                   int32_t *status, unsigned char *ws, hipStream_t st) {
-  const GroupBytes gb = group_bytes_needed(T, p->sketch_dim, false);
+  const GroupBytes gb = group_bytes_needed(p, T, false);
   float *partials = reinterpret_cast<float *>(ws);
   double *g64 = reinterpret_cast<double *>(ws + gb.partials);
   uint16_t *wt = reinterpret_cast<uint16_t *>(ws + gb.partials + gb.g64);
-  const int rpw = gram_rows_for(rows);
+  const int cus = compute_units();
+  const int rpw = gram_rows_for(p, T, cus);
   const Marks m{p->stage_events, st};
   MARK(m, 0);
   HIP_TRY(launch_gram(T, rpw, partials, st));
@@ -181,7 +213,7 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   MARK(m, COMPACTOR_STAGE_REDUCE + 1);
   HIP_TRY(launch_solve(T, p->sketch_dim, p->phi, p->ridge_rel, g64, wt, status, st));
   MARK(m, COMPACTOR_STAGE_SOLVE + 1);
-  HIP_TRY(launch_score(T, p->sketch_dim, wt, scores, status, st));
+  HIP_TRY(launch_score(T, p->sketch_dim, score_tokens_for(p, T, cus), wt, scores, status, st));
   MARK(m, COMPACTOR_STAGE_SCORE + 1);
   HIP_TRY(launch_blend(T, p->lambda_blend, scores, st));
   MARK(m, COMPACTOR_STAGE_BLEND + 1);
@@ -204,6 +236,8 @@ void compactor_default_params(compactor_params_t *p, int32_t layers, int32_t kv_
   p->ridge_rel = 0.f;
   p->lambda_blend = 0.3f;
   p->group_bytes = 0;
+  p->gram_rows = 0;
+  p->score_tokens = 0;
   p->stage_events = nullptr;
 }
 
@@ -322,7 +356,7 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
                         [&](const SegTable &T, long long rows) {
     float *sc = scores;
     if (local_scores) {
-      const GroupBytes gb = group_bytes_needed(T, p->sketch_dim, true);
+      const GroupBytes gb = group_bytes_needed(p, T, true);
       sc = reinterpret_cast<float *>(ws + gb.partials + gb.g64 + gb.wt);
     }
     const int rc2 = enqueue_score(p, T, rows, sc, status, ws, st);

@@ -22,7 +22,7 @@ constexpr int W_TERMS = CMP_W_TERMS;  // W^T is carried as a sum of this many bf
 // Launch-time tile sizes.
 constexpr int GRAM_PARTIAL_FLOATS = 10 * 32 * 32;   // upper blocks of one partial Gram matrix
 constexpr int GRAM_TILE = 64;         // rows staged in LDS per step of the Gram kernel
-constexpr int SCORE_TOKENS = 2048;    // tokens per score workgroup (walked 256 at a time)
+constexpr int SCORE_STEP = 128;       // tokens a score workgroup multiplies per step
 constexpr int SELECT_THREADS = 1024;
 constexpr int GATHER_ROWS = 64;       // kept rows per gather workgroup
 
@@ -56,27 +56,40 @@ struct Where {
   int seg;
   int head;      // l*H + h inside the request
   int lhead;     // launch-local head index
-  int tile;
+  int tile;      // block index inside the head
+  int chunk;     // units per block of this head: the block covers [tile*chunk, (tile+1)*chunk)
 };
 
-// blocks-per-head is ceil(units(seg) / per_block), units = n or k_keep;
-// per_block <= 0 means one block per head.
-__host__ __device__ __forceinline__ int blocks_per_head(int units, int per_block) {
-  return per_block <= 0 ? 1 : (int)(((long long)units + per_block - 1) / per_block);
+// Work of a head (n tokens, or k_keep kept rows) is cut into equal chunks: the caller names a
+// target chunk size `per_block`; the head gets ceil(units / per_block) blocks and every block
+// takes chunk_of(units, per_block, step) units (a multiple of `step`), so that the blocks of a
+// head are as even as the step allows.  per_block <= 0 means one block per head.
+__host__ __device__ __forceinline__ int chunk_of(int units, int per_block, int step) {
+  if (per_block <= 0) return units > 0 ? units : 1;
+  const long long splits = ((long long)units + per_block - 1) / per_block;
+  const long long even = (units + splits - 1) / (splits > 0 ? splits : 1);
+  const long long c = (even + step - 1) / step * step;
+  return (int)(c > 0 ? c : step);
+}
+__host__ __device__ __forceinline__ int blocks_per_head(int units, int per_block, int step) {
+  if (per_block <= 0) return 1;
+  const int c = chunk_of(units, per_block, step);
+  return (int)(((long long)units + c - 1) / c);
 }
 
-__device__ __forceinline__ Where locate_block(const SegTable &T, int blk, int per_block,
+__device__ __forceinline__ Where locate_block(const SegTable &T, int blk, int per_block, int step,
                                               bool by_keep) {
-  Where w{0, 0, 0, 0};
+  Where w{0, 0, 0, 0, 0};
   int base = 0;
   for (int i = 0; i < T.nseg; ++i) {
     const int units = by_keep ? T.s[i].k_keep : T.s[i].n;
-    const int bph = blocks_per_head(units, per_block);
+    const int bph = blocks_per_head(units, per_block, step);
     const int nb = bph * T.s[i].head_count;
     if (blk < base + nb || i == T.nseg - 1) {
       const int local = blk - base;
       const int hh = local / bph;
       w.seg = i;
+      w.chunk = chunk_of(units, per_block, step);
       w.head = T.s[i].head_begin + hh;
       w.lhead = T.s[i].lhead0 + hh;
       w.tile = local - hh * bph;
@@ -122,8 +135,8 @@ hipError_t launch_solve(const SegTable &T, int ks, const float *phi, float ridge
                         const double *g64, uint16_t *wt, int32_t *status, hipStream_t st);
 
 // scores[i] = || W^T k_i ||^2
-hipError_t launch_score(const SegTable &T, int ks, const uint16_t *wt, float *scores,
-                        int32_t *status, hipStream_t st);
+hipError_t launch_score(const SegTable &T, int ks, int tokens_per_wg, const uint16_t *wt,
+                        float *scores, int32_t *status, hipStream_t st);
 
 // s = z(a) + lambda z(o) in place over the scores of heads whose request has attn
 hipError_t launch_blend(const SegTable &T, float lambda, float *scores, hipStream_t st);
@@ -135,10 +148,10 @@ hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, uint16_t *k
                          uint16_t *v_packed, hipStream_t st);
 
 // Total workgroups of a launch whose blocks-per-head rule is (per_block, by_keep).
-inline long long total_blocks(const SegTable &T, int per_block, bool by_keep) {
+inline long long total_blocks(const SegTable &T, int per_block, int step, bool by_keep) {
   long long nb = 0;
   for (int i = 0; i < T.nseg; ++i)
-    nb += (long long)blocks_per_head(by_keep ? T.s[i].k_keep : T.s[i].n, per_block) *
+    nb += (long long)blocks_per_head(by_keep ? T.s[i].k_keep : T.s[i].n, per_block, step) *
           T.s[i].head_count;
   return nb;
 }

@@ -10,7 +10,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
                                                      const int32_t *__restrict__ kept_idx,
                                                      uint16_t *__restrict__ k_packed,
                                                      uint16_t *__restrict__ v_packed) {
-  const Where w = locate_block(T, blockIdx.x, GATHER_ROWS, true);
+  const Where w = locate_block(T, blockIdx.x, GATHER_ROWS, GATHER_ROWS, true);
   const Seg &s = T.s[w.seg];
   const int k = s.k_keep;
   const long long row0 = s.kept_off + (long long)w.head * k;      // first packed row of the head
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
 
 hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, uint16_t *k_packed,
                          uint16_t *v_packed, hipStream_t st) {
-  const long long nb = total_blocks(T, GATHER_ROWS, true);
+  const long long nb = total_blocks(T, GATHER_ROWS, GATHER_ROWS, true);
   if (nb <= 0) return hipSuccess;
   hipLaunchKernelGGL(gather_kernel, dim3((unsigned)nb), dim3(256), 0, st, T, kept_idx, k_packed,
                      v_packed);

@@ -49,12 +49,12 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
                                                       float *__restrict__ partials) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TILE_BYTES];
 
-  const Where w = locate_block(T, blockIdx.x, rows_per_wg, false);
+  const Where w = locate_block(T, blockIdx.x, rows_per_wg, GRAM_TILE, false);
   const Seg &s = T.s[w.seg];
   const uint16_t *kp = head_ptr(s.k_score, s, w.head);
   const long long stride_t = s.stride_t;
-  const int r0 = w.tile * rows_per_wg;
-  const int r1 = min(s.n, r0 + rows_per_wg);
+  const int r0 = w.tile * w.chunk;
+  const int r1 = min(s.n, r0 + w.chunk);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -183,7 +183,7 @@ __device__ __forceinline__ long long partial_base(const SegTable &T, int lhead, 
                                                   int &nsplit) {
   long long base = 0;
   for (int i = 0; i < T.nseg; ++i) {
-    const int bph = blocks_per_head(T.s[i].n, rows_per_wg);
+    const int bph = blocks_per_head(T.s[i].n, rows_per_wg, GRAM_TILE);
     const int hh = lhead - T.s[i].lhead0;
     if (hh < T.s[i].head_count || i == T.nseg - 1) {
       nsplit = bph;
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const SegTable T, int 
 }
 
 hipError_t launch_gram(const SegTable &T, int rows_per_wg, float *partials, hipStream_t st) {
-  const long long nb = total_blocks(T, rows_per_wg, false);
+  const long long nb = total_blocks(T, rows_per_wg, GRAM_TILE, false);
   if (nb <= 0) return hipSuccess;
   hipLaunchKernelGGL(gram_kernel, dim3((unsigned)nb), dim3(256), 0, st, T, rows_per_wg, partials);
   return hipGetLastError();

@@ -25,13 +25,13 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// A workgroup walks SCORE_TOKENS tokens of one head in steps of 128 (32 per wave, two 16-token
+// A workgroup walks tokens_per_wg tokens of one head in steps of 128 (32 per wave, two 16-token
 // sub-tiles).  Key rows arrive with fully coalesced streaming loads (a wave instruction covers
 // four whole 256-byte rows), pass through a wave-private LDS buffer, and are read back in the
 // MFMA B-operand arrangement; two steps of loads are in flight while a third is multiplied.
 // Nothing in the loop needs a workgroup barrier: a wave only reads what it wrote itself.
 template <int M>
-__global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
+__global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tokens_per_wg,
                                                        const uint16_t *__restrict__ wt,
                                                        float *__restrict__ scores,
                                                        int32_t *__restrict__ status) {
@@ -40,13 +40,13 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
   __shared__ __attribute__((aligned(16))) uint16_t wl[W_TERMS * M * WPITCH];
   __shared__ __attribute__((aligned(16))) uint16_t kl[4][WTOK * WPITCH];
 
-  const Where w = locate_block(T, blockIdx.x, SCORE_TOKENS, false);
+  const Where w = locate_block(T, blockIdx.x, tokens_per_wg, SCORE_STEP, false);
   const Seg &s = T.s[w.seg];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int t16 = lane & 15, g = lane >> 4;
   const int n = s.n;
-  const int tok_begin = w.tile * SCORE_TOKENS;
-  const int tok_end = min(n, tok_begin + SCORE_TOKENS);
+  const int tok_begin = w.tile * w.chunk;
+  const int tok_end = min(n, tok_begin + w.chunk);
   const int nsteps = (tok_end - tok_begin + STEP - 1) / STEP;
   const long long stride_t = s.stride_t;
   const uint16_t *kp = head_ptr(s.k_score, s, w.head);
@@ -166,23 +166,23 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T,
 }
 
 template <int M>
-static hipError_t launch_m(const SegTable &T, const uint16_t *wt, float *scores, int32_t *status,
-                           hipStream_t st) {
-  const long long nb = total_blocks(T, SCORE_TOKENS, false);
+static hipError_t launch_m(const SegTable &T, int tokens_per_wg, const uint16_t *wt,
+                           float *scores, int32_t *status, hipStream_t st) {
+  const long long nb = total_blocks(T, tokens_per_wg, SCORE_STEP, false);
   if (nb <= 0) return hipSuccess;
-  hipLaunchKernelGGL((score_kernel<M>), dim3((unsigned)nb), dim3(256), 0, st, T, wt, scores,
-                     status);
+  hipLaunchKernelGGL((score_kernel<M>), dim3((unsigned)nb), dim3(256), 0, st, T, tokens_per_wg, wt,
+                     scores, status);
   return hipGetLastError();
 }
 
-hipError_t launch_score(const SegTable &T, int ks, const uint16_t *wt, float *scores,
-                        int32_t *status, hipStream_t st) {
+hipError_t launch_score(const SegTable &T, int ks, int tokens_per_wg, const uint16_t *wt,
+                        float *scores, int32_t *status, hipStream_t st) {
   switch (ks) {
-    case 16: return launch_m<16>(T, wt, scores, status, st);
-    case 32: return launch_m<32>(T, wt, scores, status, st);
-    case 48: return launch_m<48>(T, wt, scores, status, st);
-    case 64: return launch_m<64>(T, wt, scores, status, st);
-    case 0:  return launch_m<128>(T, wt, scores, status, st);
+    case 16: return launch_m<16>(T, tokens_per_wg, wt, scores, status, st);
+    case 32: return launch_m<32>(T, tokens_per_wg, wt, scores, status, st);
+    case 48: return launch_m<48>(T, tokens_per_wg, wt, scores, status, st);
+    case 64: return launch_m<64>(T, tokens_per_wg, wt, scores, status, st);
+    case 0:  return launch_m<128>(T, tokens_per_wg, wt, scores, status, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -92,7 +92,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T
   __shared__ int wsum[SELECT_THREADS / 64];
   __shared__ int found[2];
 
-  const Where w = locate_block(T, blockIdx.x, 0, false);
+  const Where w = locate_block(T, blockIdx.x, 0, 1, false);
   const Seg &s = T.s[w.seg];
   const int n = s.n, k = s.k_keep;
   const float *sp = scores + s.score_off + (long long)w.head * n;
@@ -160,7 +160,7 @@ __device__ __forceinline__ double block_sum(double v, double *wd) {
 __global__ __launch_bounds__(SELECT_THREADS) void blend_kernel(const SegTable T, float lambda,
                                                                float *__restrict__ scores) {
   __shared__ double wd[SELECT_THREADS / 64];
-  const Where w = locate_block(T, blockIdx.x, 0, false);
+  const Where w = locate_block(T, blockIdx.x, 0, 1, false);
   const Seg &s = T.s[w.seg];
   if (s.attn == nullptr) return;
   const int n = s.n, tid = threadIdx.x;
