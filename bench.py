@@ -33,6 +33,7 @@ def parse():
     ap.add_argument("--group-mb", type=float, default=0.0, help="head-group size in MiB (0 = library default)")
     ap.add_argument("--gram-rows", type=int, default=0, help="tuning override (0 = library's choice)")
     ap.add_argument("--score-tokens", type=int, default=0, help="tuning override (0 = library's choice)")
+    ap.add_argument("--streams", type=int, default=0, help="stream lanes (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--allow-flagged", action="store_true",
                     help="do not fail when a head reports a status flag (kernel experiments only)")
@@ -121,14 +122,16 @@ def main():
     group_bytes = int(a.group_mb * 1024 * 1024)
     mk = lambda events: C.Params(w.layers, w.kv_heads, sketch_dim=w.sketch_dim, phi=phi,
                                  ridge_rel=w.ridge_rel, group_bytes=group_bytes, stage_events=events,
-                                 gram_rows=a.gram_rows, score_tokens=a.score_tokens)
+                                 gram_rows=a.gram_rows, score_tokens=a.score_tokens,
+                                 streams=(1 if events is not None else a.streams))
     params, params_ev = mk(None), mk(ev)
     reqs = [C.Request(k_score=r.k, v_cache=r.v, ratio=r.ratio) for r in w.requests]
     so, ko, kk = C.compactor_layout(params, reqs)
     nh = len(reqs) * w.layers * w.kv_heads
 
     # every output and the workspace are allocated once, outside the timed region
-    ws = torch.empty(max(256, C.compactor_workspace_size(params, reqs)), dtype=torch.uint8, device=dev)
+    ws_bytes = max(256, C.compactor_workspace_size(params, reqs), C.compactor_workspace_size(params_ev, reqs))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     bufs = dict(kept_idx=torch.empty(ko[-1], dtype=torch.int32, device=dev),
                 kept_cnt=torch.empty(nh, dtype=torch.int32, device=dev),
                 k_packed=torch.empty(ko[-1], 128, dtype=torch.bfloat16, device=dev),

@@ -20,7 +20,9 @@
  *     pointer marked "host" is ordinary host memory owned by the caller.  The
  *     library never allocates, frees or synchronises: all work is enqueued on
  *     the stream that is passed in (a hipStream_t cast to void*, NULL = the
- *     default stream) and outputs are valid once that stream has drained.
+ *     default stream), or on helper streams ordered after and before it (see
+ *     compactor_params_t.streams), and outputs are valid once that stream has
+ *     drained.
  *   - Keys and values are bfloat16 (raw 16-bit patterns), head_dim contiguous.
  *   - Heads are numbered request-major: head g = (sum of L*H of earlier
  *     requests) + layer*H + kv_head.  All per-head outputs use this order and
@@ -29,8 +31,10 @@
  *     detected on the host before anything is enqueued; a failing call leaves
  *     the outputs untouched.  Numerical trouble inside a head never aborts: it
  *     is reported in that head's status word (see COMPACTOR_STATUS_*).
- *   - Thread safety: no global mutable state; concurrent calls are safe when
- *     they use distinct workspaces and output buffers.
+ *   - Thread safety: concurrent calls are safe when they use distinct workspaces
+ *     and output buffers.  The only process-wide state is the per-device set of
+ *     helper streams used when params.streams > 1; calls that use it are
+ *     serialised while they enqueue.
  */
 #ifndef COMPACTOR_H
 #define COMPACTOR_H
@@ -91,6 +95,12 @@ typedef struct compactor_params {
                              last-level cache; 0 = library default */
   int32_t gram_rows;      /* tuning: target key rows per workgroup of the Gram kernel and target */
   int32_t score_tokens;   /* tokens per workgroup of the score kernel; 0 = chosen by the library */
+  int32_t streams;        /* concurrency: 0 or 1 = every kernel on the caller's stream.  2..4 = head
+                             groups are spread over that many lanes (the caller's stream plus
+                             helper streams that the library creates once per device and keeps),
+                             forked from and joined back into the caller's stream by events, so
+                             that latency-bound kernels of one group run beside streaming kernels
+                             of another.  The workspace grows to one slice per lane. */
   void  **stage_events;   /* profiling aid, normally NULL.  host array of COMPACTOR_NUM_STAGES+1
                              hipEvent_t created by the caller: event[0] is recorded on the stream
                              before the first kernel of a group and event[i+1] after stage i's

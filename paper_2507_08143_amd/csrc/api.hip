@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "common.h"
 
 using namespace cmp;
@@ -30,7 +32,8 @@ int check_params(const compactor_params_t *p, bool scoring) {
     if (!(p->ridge_rel >= 0.f) || !isfinite(p->ridge_rel)) return COMPACTOR_EINVAL;
     if (!isfinite(p->lambda_blend)) return COMPACTOR_EINVAL;
   }
-  if (p->group_bytes < 0 || p->gram_rows < 0 || p->score_tokens < 0) return COMPACTOR_EINVAL;
+  if (p->group_bytes < 0 || p->gram_rows < 0 || p->score_tokens < 0 || p->streams < 0)
+    return COMPACTOR_EINVAL;
   return COMPACTOR_OK;
 }
 
@@ -156,22 +159,70 @@ int for_each_group(const compactor_params_t *p, const compactor_request_t *reqs,
   return COMPACTOR_OK;
 }
 
-long long group_rows_of(const compactor_params_t *p) {
-  const long long gb = p->group_bytes > 0 ? p->group_bytes : DEFAULT_GROUP_BYTES;
-  long long r = gb / (D * 2);
+constexpr int MAX_LANES = 4;          // concurrent stream lanes (the caller's stream + 3 helpers)
+constexpr int GROUPS_PER_LANE = 2;    // default pipeline depth when the caller names no group size
+
+int lanes_of(const compactor_params_t *p) {
+  const int l = p->streams > 0 ? p->streams : 1;
+  return l > MAX_LANES ? MAX_LANES : l;
+}
+
+// Key rows per head group.  An explicit group_bytes wins; otherwise a single-lane call is one
+// group and a multi-lane call gets GROUPS_PER_LANE groups per lane, so that the latency-bound
+// kernels of one group (factorisation, selection) run beside the streaming kernels of others.
+long long group_rows_of(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq) {
+  if (p->group_bytes > 0) {
+    const long long r = p->group_bytes / (D * 2);
+    return r < 1 ? 1 : r;
+  }
+  const int lanes = lanes_of(p);
+  if (lanes <= 1) return DEFAULT_GROUP_BYTES / (D * 2);
+  long long total = 0;
+  for (int b = 0; b < nreq; ++b) total += (long long)reqs[b].n * p->layers * p->kv_heads;
+  const long long r = (total + lanes * GROUPS_PER_LANE - 1) / (lanes * GROUPS_PER_LANE);
   return r < 1 ? 1 : r;
 }
 
+// Helper streams and fork/join events, one set per device, created on first use and kept for
+// the life of the process.  Enqueueing through the pool is serialised by its mutex.
+struct LanePool {
+  std::mutex mu;
+  bool ready = false;
+  hipStream_t helper[MAX_LANES - 1];
+  hipEvent_t fork;
+  hipEvent_t join[MAX_LANES - 1];
+};
+constexpr int MAX_DEVICES = 16;
+LanePool g_pools[MAX_DEVICES];
+
+LanePool *lane_pool() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  LanePool *lp = &g_pools[dev];
+  std::lock_guard<std::mutex> lock(lp->mu);
+  if (!lp->ready) {
+    for (int i = 0; i < MAX_LANES - 1; ++i) {
+      if (hipStreamCreateWithFlags(&lp->helper[i], hipStreamNonBlocking) != hipSuccess) return nullptr;
+      if (hipEventCreateWithFlags(&lp->join[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+    }
+    if (hipEventCreateWithFlags(&lp->fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+    lp->ready = true;
+  }
+  return lp;
+}
+
+// Bytes one lane needs (the largest group); a call needs lanes_of(p) such slices.
 int workspace_need(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
-                   bool local_scores, size_t *bytes) {
+                   bool local_scores, size_t *slice, size_t *bytes) {
   size_t need = 0;
-  const int rc = for_each_group(p, reqs, nreq, group_rows_of(p), local_scores,
+  const int rc = for_each_group(p, reqs, nreq, group_rows_of(p, reqs, nreq), local_scores,
                                 [&](const SegTable &T, long long) {
                                   const size_t t = group_bytes_needed(p, T, local_scores).total();
                                   if (t > need) need = t;
                                   return COMPACTOR_OK;
                                 });
-  *bytes = need;
+  if (slice) *slice = need;
+  *bytes = need * lanes_of(p);
   return rc;
 }
 
@@ -209,15 +260,54 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   MARK(m, 0);
   HIP_TRY(launch_gram(T, rpw, partials, st));
   MARK(m, COMPACTOR_STAGE_GRAM + 1);
-  HIP_TRY(launch_gram_reduce(T, rpw, partials, g64, st));
-  MARK(m, COMPACTOR_STAGE_REDUCE + 1);
-  HIP_TRY(launch_solve(T, p->sketch_dim, p->phi, p->ridge_rel, g64, wt, status, st));
+  if (p->sketch_dim > 0) {
+    hipEvent_t mid = m.ev ? static_cast<hipEvent_t>(m.ev[COMPACTOR_STAGE_REDUCE + 1]) : nullptr;
+    HIP_TRY(launch_sketch_solve(T, p->sketch_dim, rpw, partials, p->phi, p->ridge_rel, g64, wt,
+                                status, st, mid));
+  } else {
+    HIP_TRY(launch_gram_reduce(T, rpw, partials, g64, st));
+    MARK(m, COMPACTOR_STAGE_REDUCE + 1);
+    HIP_TRY(launch_solve(T, p->ridge_rel, g64, wt, status, st));
+  }
   MARK(m, COMPACTOR_STAGE_SOLVE + 1);
   HIP_TRY(launch_score(T, p->sketch_dim, score_tokens_for(p, T, cus), wt, scores, status, st));
   MARK(m, COMPACTOR_STAGE_SCORE + 1);
   HIP_TRY(launch_blend(T, p->lambda_blend, scores, st));
   MARK(m, COMPACTOR_STAGE_BLEND + 1);
   return COMPACTOR_OK;
+}
+
+// Runs fn(T, rows, stream, workspace slice) for every head group.  With one lane everything is
+// enqueued on the caller's stream.  With several lanes group g goes to lane g % lanes: lane 0
+// is the caller's stream, the others are the pool's helper streams, forked from the caller's
+// stream by an event before the first group and joined back into it after the last, so that
+// for the caller the call still behaves as work enqueued on its own stream.
+template <class F>
+int run_groups(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+               bool local_scores, unsigned char *ws, size_t slice, hipStream_t user, F &&fn) {
+  const int lanes = lanes_of(p);
+  const long long grows = group_rows_of(p, reqs, nreq);
+  if (lanes <= 1)
+    return for_each_group(p, reqs, nreq, grows, local_scores,
+                          [&](const SegTable &T, long long rows) { return fn(T, rows, user, ws); });
+  LanePool *lp = lane_pool();
+  if (!lp) return COMPACTOR_EHIP;
+  std::lock_guard<std::mutex> lock(lp->mu);
+  HIP_TRY(hipEventRecord(lp->fork, user));
+  for (int i = 0; i < lanes - 1; ++i) HIP_TRY(hipStreamWaitEvent(lp->helper[i], lp->fork, 0));
+  int g = 0;
+  const int rc = for_each_group(p, reqs, nreq, grows, local_scores,
+                                [&](const SegTable &T, long long rows) {
+    const int lane = g++ % lanes;
+    hipStream_t st = lane == 0 ? user : lp->helper[lane - 1];
+    return fn(T, rows, st, ws + (size_t)lane * slice);
+  });
+  // join even after a failed enqueue, so that the helpers never outlive the call unobserved
+  for (int i = 0; i < lanes - 1; ++i) {
+    if (hipEventRecord(lp->join[i], lp->helper[i]) != hipSuccess) return COMPACTOR_EHIP;
+    if (hipStreamWaitEvent(user, lp->join[i], 0) != hipSuccess) return COMPACTOR_EHIP;
+  }
+  return rc;
 }
 
 }  // namespace
@@ -238,6 +328,7 @@ void compactor_default_params(compactor_params_t *p, int32_t layers, int32_t kv_
   p->group_bytes = 0;
   p->gram_rows = 0;
   p->score_tokens = 0;
+  p->streams = 0;
   p->stage_events = nullptr;
 }
 
@@ -279,7 +370,7 @@ int compactor_workspace_size(const compactor_params_t *p, const compactor_reques
   rc = check_requests(reqs, nreq, 0);
   if (rc) return rc;
   // sized for the fused call that keeps its scores in the workspace, the largest user
-  return workspace_need(p, reqs, nreq, true, bytes);
+  return workspace_need(p, reqs, nreq, true, nullptr, bytes);
 }
 
 int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
@@ -290,16 +381,16 @@ int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs
   rc = check_requests(reqs, nreq, NEED_SCORE);
   if (rc) return rc;
   if (!scores || !status) return COMPACTOR_EINVAL;
-  size_t need;
-  rc = workspace_need(p, reqs, nreq, false, &need);
+  size_t need, slice;
+  rc = workspace_need(p, reqs, nreq, false, &slice, &need);
   if (rc) return rc;
   if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  unsigned char *ws = static_cast<unsigned char *>(workspace);
-  return for_each_group(p, reqs, nreq, group_rows_of(p), false, [&](const SegTable &T, long long rows) {
-    return enqueue_score(p, T, rows, scores, status, ws, st);
-  });
+  return run_groups(p, reqs, nreq, false, static_cast<unsigned char *>(workspace), slice,
+                    static_cast<hipStream_t>(stream),
+                    [&](const SegTable &T, long long rows, hipStream_t st, unsigned char *ws) {
+                      return enqueue_score(p, T, rows, scores, status, ws, st);
+                    });
 }
 
 int compactor_select(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
@@ -345,15 +436,14 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
   if (!kept_idx || !kept_cnt || !k_packed || !v_packed || !status) return COMPACTOR_EINVAL;
   if (!aligned16(k_packed) || !aligned16(v_packed)) return COMPACTOR_EALIGN;
   const bool local_scores = scores == nullptr;
-  size_t need;
-  rc = workspace_need(p, reqs, nreq, local_scores, &need);
+  size_t need, slice;
+  rc = workspace_need(p, reqs, nreq, local_scores, &slice, &need);
   if (rc) return rc;
   if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  unsigned char *ws = static_cast<unsigned char *>(workspace);
-  return for_each_group(p, reqs, nreq, group_rows_of(p), local_scores,
-                        [&](const SegTable &T, long long rows) {
+  return run_groups(p, reqs, nreq, local_scores, static_cast<unsigned char *>(workspace), slice,
+                    static_cast<hipStream_t>(stream),
+                    [&](const SegTable &T, long long rows, hipStream_t st, unsigned char *ws) {
     float *sc = scores;
     if (local_scores) {
       const GroupBytes gb = group_bytes_needed(p, T, true);

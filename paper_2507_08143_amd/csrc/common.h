@@ -119,6 +119,29 @@ __device__ __forceinline__ const uint16_t *head_ptr(const uint16_t *base, const 
   return base + (long long)l * s.stride_l + (long long)h * s.stride_h;
 }
 
+// Stored order of the 10 upper 32x32 blocks of a partial Gram matrix.
+__host__ __device__ __forceinline__ int upper_block(int I, int J) {
+  return I * 4 - (I * (I - 1)) / 2 + (J - I);
+}
+
+// First partial and number of row splits of launch-local head `lhead` (Gram workgroups are
+// numbered segment by segment, head by head, split by split).
+__device__ __forceinline__ long long partial_base(const SegTable &T, int lhead, int rows_per_wg,
+                                                  int &nsplit) {
+  long long base = 0;
+  for (int i = 0; i < T.nseg; ++i) {
+    const int bph = blocks_per_head(T.s[i].n, rows_per_wg, GRAM_TILE);
+    const int hh = lhead - T.s[i].lhead0;
+    if (hh < T.s[i].head_count || i == T.nseg - 1) {
+      nsplit = bph;
+      return base + (long long)hh * bph;
+    }
+    base += (long long)bph * T.s[i].head_count;
+  }
+  nsplit = 0;
+  return 0;
+}
+
 // ---- host-side launchers (one per translation unit) -------------------------------------
 // All of them enqueue on `st` and return the hipGetLastError() of their launches.
 
@@ -130,9 +153,17 @@ hipError_t launch_gram(const SegTable &T, int rows_per_wg, float *partials, hipS
 hipError_t launch_gram_reduce(const SegTable &T, int rows_per_wg, const float *partials,
                               double *g64, hipStream_t st);
 
-// Factor and emit W^T (as W_TERMS bf16 planes, [term][ks_pad][128] per head) and status.
-hipError_t launch_solve(const SegTable &T, int ks, const float *phi, float ridge_rel,
-                        const double *g64, uint16_t *wt, int32_t *status, hipStream_t st);
+// Exact mode: factor G + rho I and emit W^T (as W_TERMS bf16 planes, [term][128][128] per head)
+// and the status word.
+hipError_t launch_solve(const SegTable &T, float ridge_rel, const double *g64, uint16_t *wt,
+                        int32_t *status, hipStream_t st);
+
+// Sketched mode: partial Gram blocks -> S = Phi^T G Phi (4 contributions per head in s_parts)
+// -> W^T ([term][k_s][128] per head) and status.  `mid`, if not null, is recorded between the
+// two kernels.
+hipError_t launch_sketch_solve(const SegTable &T, int ks, int rows_per_wg, const float *partials,
+                               const float *phi, float ridge_rel, double *s_parts, uint16_t *wt,
+                               int32_t *status, hipStream_t st, hipEvent_t mid);
 
 // scores[i] = || W^T k_i ||^2
 hipError_t launch_score(const SegTable &T, int ks, int tokens_per_wg, const uint16_t *wt,

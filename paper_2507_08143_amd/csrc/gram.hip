@@ -23,10 +23,6 @@ constexpr int PITCH = 144;                 // bf16 per LDS row: 288 B keeps 16-B
 constexpr int TILE_BYTES = GRAM_TILE * PITCH * 2;
 constexpr int GBLK = 32 * 32;              // one 32x32 block of G
 
-__host__ __device__ __forceinline__ int upper_block(int I, int J) {
-  return I * 4 - (I * (I - 1)) / 2 + (J - I);
-}
-
 // LDS transpose read (ds_read_b64_tr_b16): within each group of 16 lanes, lane j receives
 // element (j & 3) of the 8-byte words addressed by lanes (j >> 2), 4 + (j >> 2), 8 + (j >> 2),
 // 12 + (j >> 2).  With lane i pointing at row (i >> 2), columns 4*(i & 3).. of a row-major
@@ -177,23 +173,6 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
 // Order in which the waves own the upper blocks, as (I, J) per stored block number.
 __device__ __constant__ int kBlockI[10] = {0, 0, 0, 0, 1, 1, 1, 2, 2, 3};
 __device__ __constant__ int kBlockJ[10] = {0, 1, 2, 3, 1, 2, 3, 2, 3, 3};
-
-// First partial and number of row splits of launch-local head `lhead`.
-__device__ __forceinline__ long long partial_base(const SegTable &T, int lhead, int rows_per_wg,
-                                                  int &nsplit) {
-  long long base = 0;
-  for (int i = 0; i < T.nseg; ++i) {
-    const int bph = blocks_per_head(T.s[i].n, rows_per_wg, GRAM_TILE);
-    const int hh = lhead - T.s[i].lhead0;
-    if (hh < T.s[i].head_count || i == T.nseg - 1) {
-      nsplit = bph;
-      return base + (long long)hh * bph;
-    }
-    base += (long long)bph * T.s[i].head_count;
-  }
-  nsplit = 0;
-  return 0;
-}
 
 // G64 = sum of a head's partials in fp64, in split order (deterministic), written as the full
 // symmetric 128 x 128 matrix: one workgroup per (head, upper block), the mirror image goes

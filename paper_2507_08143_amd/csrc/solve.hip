@@ -2,13 +2,11 @@
 // notes that routes other than the SVD give the same scores).
 //
 //   sketched:  S = Phi^T G Phi + rho I  (k_s x k_s),   exact:  S = G + rho I  (d x d)
-//   S = L L^T,  X = L^{-1},  W^T = X Phi^T  (k_s x d)   [exact: W^T = X]
+//   S = L L^T,   W^T = L^{-1} Phi^T  (k_s x d)   [exact: W^T = L^{-1}]
 //
 // so that the score of a token is o_i = || W^T k_i ||^2 = k^_i^T S^{-1} k^_i, which equals
 // diag(U~ U~^T) of Algorithm 1 lines 5-6 when rho = 0.  All arithmetic here is fp64; W^T leaves
-// as the sum of three bf16 planes (an exact split of its fp32 value) for the MFMA score pass.
-//
-// One workgroup per head; everything lives in LDS (up to 134 KB of the CU's 160 KB).
+// as a sum of bf16 planes for the MFMA score pass.
 #include "common.h"
 
 namespace cmp {
@@ -38,18 +36,15 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_floa
 // accumulated Gram matrix resolves: the direction is dropped and the head flagged.
 constexpr double PIVOT_REL = 1.4901161193847656e-08;   // 2^-26
 
-template <int M_MAX, bool SKETCHED>
-__global__ __launch_bounds__(256) void solve_kernel(const SegTable T, int m,
-                                                    const float *__restrict__ phi, float ridge_rel,
-                                                    const double *__restrict__ g64,
-                                                    uint16_t *__restrict__ wt,
-                                                    int32_t *__restrict__ status) {
-  constexpr int SP = M_MAX + 1;                        // pitch of S (doubles)
-  constexpr int TP = M_MAX + 1;                        // pitch of the T / Phi staging area
-  __shared__ double S[M_MAX * SP];
-  __shared__ double TA[SKETCHED ? D * TP : 1];
-  __shared__ double dinv[M_MAX];
-  __shared__ double d0[M_MAX];
+// ---- exact mode: S = G + rho I (128 x 128), one workgroup per head, everything in LDS -------
+__global__ __launch_bounds__(256) void solve_exact_kernel(const SegTable T, float ridge_rel,
+                                                          const double *__restrict__ g64,
+                                                          uint16_t *__restrict__ wt,
+                                                          int32_t *__restrict__ status) {
+  constexpr int m = D, SP = D + 1;
+  __shared__ double S[m * SP];
+  __shared__ double dinv[m];
+  __shared__ double d0[m];
   __shared__ int flag;
 
   const int lhead = blockIdx.x;
@@ -58,48 +53,9 @@ __global__ __launch_bounds__(256) void solve_kernel(const SegTable T, int m,
   const double *G = g64 + (size_t)lhead * (D * D);
   const int tid = threadIdx.x;
   if (tid == 0) flag = 0;
-
-  if (SKETCHED) {
-    // T = G Phi.  Thread (i, half) owns T[i][half + 2*bb]; G is symmetric so column i is read
-    // as row-major G[j][i], contiguous across threads.
-    const int i = tid & 127, half = tid >> 7;
-    double acc[M_MAX / 2];
-#pragma unroll
-    for (int bb = 0; bb < M_MAX / 2; ++bb) acc[bb] = 0.0;
-    for (int j = 0; j < D; ++j) {
-      const double gji = G[j * D + i];
-      const float *ph = phi + j * m;
-#pragma unroll
-      for (int bb = 0; bb < M_MAX / 2; ++bb) {
-        const int b = half + 2 * bb;
-        if (b < m) acc[bb] += gji * (double)ph[b];
-      }
-    }
-#pragma unroll
-    for (int bb = 0; bb < M_MAX / 2; ++bb) {
-      const int b = half + 2 * bb;
-      if (b < m) TA[i * TP + b] = acc[bb];
-    }
-    __syncthreads();
-    // S = Phi^T T, lower triangle
-    for (int idx = tid; idx < m * m; idx += 256) {
-      const int a = idx / m, b = idx - a * m;
-      if (b > a) continue;
-      double sum = 0.0;
-      for (int i2 = 0; i2 < D; ++i2) sum += (double)phi[i2 * m + a] * TA[i2 * TP + b];
-      S[a * SP + b] = sum;
-    }
-    __syncthreads();
-    // the staging area now holds Phi in fp64 for the last step
-    for (int idx = tid; idx < D * m; idx += 256) {
-      const int i2 = idx / m, b = idx - i2 * m;
-      TA[i2 * TP + b] = (double)phi[idx];
-    }
-  } else {
-    for (int idx = tid; idx < m * m; idx += 256) {
-      const int a = idx / m, b = idx - a * m;
-      if (b <= a) S[a * SP + b] = G[a * D + b];
-    }
+  for (int idx = tid; idx < m * m; idx += 256) {
+    const int a = idx / m, b = idx - a * m;
+    if (b <= a) S[a * SP + b] = G[a * D + b];
   }
   __syncthreads();
 
@@ -148,17 +104,11 @@ __global__ __launch_bounds__(256) void solve_kernel(const SegTable T, int m,
   }
   __syncthreads();
 
-  // W^T[j][ch] = sum_{q <= j} X[j][q] Phi[ch][q]; exact mode: W^T = X (lower triangular)
+  // W^T = X (lower triangular), split into bf16 planes
   uint16_t *wh = wt + (size_t)lhead * (W_TERMS * m * D);
   const int ch = tid & 127;
   for (int j = tid >> 7; j < m; j += 2) {
-    double wv;
-    if (SKETCHED) {
-      wv = dinv[j] * TA[ch * TP + j];
-      for (int q = 0; q < j; ++q) wv += S[q * SP + j] * TA[ch * TP + q];
-    } else {
-      wv = ch < j ? S[ch * SP + j] : (ch == j ? dinv[j] : 0.0);
-    }
+    const double wv = ch < j ? S[ch * SP + j] : (ch == j ? dinv[j] : 0.0);
     float x = (float)wv;
 #pragma unroll
     for (int t = 0; t < W_TERMS; ++t) {
@@ -170,173 +120,256 @@ __global__ __launch_bounds__(256) void solve_kernel(const SegTable T, int m,
   if (tid == 0) status[sg.ghead0 + w.head] = flag;
 }
 
-// ---- sketched mode, compile-time order M (k_s): the fast path ------------------------------
-// Phases: T = G Phi (registers, Phi broadcast from LDS) -> S = Phi^T T (3x3 register blocks)
-// -> Cholesky with one barrier per step (columns stay unscaled until the end)
-// -> forward substitution L y = Phi[ch][:]^T with y in registers, one channel per thread.
+// ---- sketched mode -------------------------------------------------------------------------
+// Step 1, sketch_kernel: one workgroup per (head, 32-row block I of G).  It sums the head's
+// partial Gram blocks in fp64 (split order, deterministic), forms the rows G_I (32 x 128),
+// T_I = G_I Phi (32 x k_s) and the contribution S_I = Phi_I^T T_I (k_s x k_s) to
+// S = Phi^T G Phi = sum_I S_I.  All the O(d^2 k_s) work of the factorisation step is here,
+// spread over 4 x heads workgroups.
 template <int M>
-__global__ __launch_bounds__(256) void solve_sketched_kernel(const SegTable T,
-                                                             const float *__restrict__ phi,
-                                                             float ridge_rel,
-                                                             const double *__restrict__ g64,
-                                                             uint16_t *__restrict__ wt,
-                                                             int32_t *__restrict__ status) {
-  constexpr int SP = M + 1, TP = M + 1, MB = M / 16, HB = M / 2;
-  __shared__ double S[M * SP];
-  __shared__ double TA[D * TP];
+__global__ __launch_bounds__(256) void sketch_kernel(const SegTable T, int rows_per_wg,
+                                                     const float *__restrict__ partials,
+                                                     const float *__restrict__ phi,
+                                                     double *__restrict__ s_parts) {
+  constexpr int GP = D + 1, TP = M + 1, CPT = M / 8;     // CPT: T columns per thread
+  __shared__ double Gs[32 * GP];
+  __shared__ double Ts[32 * TP];
   __shared__ __attribute__((aligned(16))) float PH[D * M];
-  __shared__ double piv_s[M];
-  __shared__ double d0[M];
-  __shared__ int flag;
 
-  const int lhead = blockIdx.x;
-  const Where w = locate_head(T, lhead);
-  const Seg &sg = T.s[w.seg];
-  const double *G = g64 + (size_t)lhead * (D * D);
+  const int lhead = blockIdx.x >> 2, I = blockIdx.x & 3;
   const int tid = threadIdx.x;
-  if (tid == 0) flag = 0;
   for (int idx = tid; idx < D * M / 4; idx += 256)
     reinterpret_cast<float4 *>(PH)[idx] = reinterpret_cast<const float4 *>(phi)[idx];
-  __syncthreads();
 
-  {  // T = G Phi: thread (i, half) owns T[i][half*HB .. half*HB+HB)
-    const int i = tid & 127;
-    const int half = __builtin_amdgcn_readfirstlane(tid >> 7);
-    double acc[HB];
+  // rows 32I .. 32I+31 of G from the stored upper blocks (mirror blocks read transposed)
+  int nsplit;
+  const long long pb = partial_base(T, lhead, rows_per_wg, nsplit);
+  const int e = tid * 4, ii = e >> 5, jj = e & 31;
 #pragma unroll
-    for (int bb = 0; bb < HB; ++bb) acc[bb] = 0.0;
-    for (int j0 = 0; j0 < D; j0 += 8) {
-      double g[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) g[u] = G[(j0 + u) * D + i];   // symmetric: column i as row reads
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const float4 *pr = reinterpret_cast<const float4 *>(&PH[(j0 + u) * M + half * HB]);
-#pragma unroll
-        for (int q = 0; q < HB / 4; ++q) {
-          const float4 f = pr[q];
-          acc[4 * q + 0] += g[u] * (double)f.x;
-          acc[4 * q + 1] += g[u] * (double)f.y;
-          acc[4 * q + 2] += g[u] * (double)f.z;
-          acc[4 * q + 3] += g[u] * (double)f.w;
-        }
-      }
+  for (int J = 0; J < 4; ++J) {
+    const int blk = J >= I ? upper_block(I, J) : upper_block(J, I);
+    const float *src = partials + pb * GRAM_PARTIAL_FLOATS + blk * 1024 + e;
+    double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    for (int sidx = 0; sidx < nsplit; ++sidx) {
+      const float4 v = *reinterpret_cast<const float4 *>(src + (long long)sidx * GRAM_PARTIAL_FLOATS);
+      a0 += v.x; a1 += v.y; a2 += v.z; a3 += v.w;
     }
-#pragma unroll
-    for (int bb = 0; bb < HB; ++bb) TA[i * TP + half * HB + bb] = acc[bb];
-  }
-  __syncthreads();
-
-  {  // S = Phi^T T, lower 16x16 block pairs; thread (ta, tb) owns an MB x MB register block
-    const int ta = tid >> 4, tb = tid & 15;
-    double acc[MB][MB];
-#pragma unroll
-    for (int x = 0; x < MB; ++x)
-#pragma unroll
-      for (int y = 0; y < MB; ++y) acc[x][y] = 0.0;
-    for (int i = 0; i < D; ++i) {
-      double pa[MB], tv[MB];
-#pragma unroll
-      for (int x = 0; x < MB; ++x) pa[x] = (double)PH[i * M + ta + 16 * x];
-#pragma unroll
-      for (int y = 0; y < MB; ++y) tv[y] = TA[i * TP + tb + 16 * y];
-#pragma unroll
-      for (int x = 0; x < MB; ++x)
-#pragma unroll
-        for (int y = 0; y <= x; ++y) acc[x][y] += pa[x] * tv[y];
-    }
-#pragma unroll
-    for (int x = 0; x < MB; ++x)
-#pragma unroll
-      for (int y = 0; y <= x; ++y) S[(ta + 16 * x) * SP + tb + 16 * y] = acc[x][y];
-  }
-  __syncthreads();
-
-  double tr = 0.0;
-  for (int a = 0; a < M; ++a) tr += S[a * SP + a];
-  const double rho = (double)ridge_rel * tr / (double)M;
-  __syncthreads();
-  if (tid < M) {
-    const double v = S[tid * SP + tid] + rho;
-    S[tid * SP + tid] = v;
-    d0[tid] = v;
-  }
-
-  // Cholesky, one barrier per step: column k keeps the values L[i][k] * L[k][k] until the end
-  const int tx = tid & 15, ty = tid >> 4;
-  for (int k = 0; k < M; ++k) {
-    __syncthreads();
-    const double piv = S[k * SP + k];
-    const bool ok = piv > PIVOT_REL * d0[k] && piv < 1.0e300;
-    if (tid == 0) {
-      piv_s[k] = ok ? piv : 0.0;
-      if (!ok) flag = COMPACTOR_STATUS_PIVOT;
-    }
-    if (ok) {
-      const double inv = 1.0 / piv;
-      for (int i = k + 1 + ty; i < M; i += 16) {
-        const double lik = S[i * SP + k] * inv;
-        for (int j = k + 1 + tx; j <= i; j += 16) S[i * SP + j] -= lik * S[j * SP + k];
-      }
+    if (J >= I) {           // stored as (I,J): element (ii, jj+q) is G[32I+ii][32J+jj+q]
+      double *d = &Gs[ii * GP + 32 * J + jj];
+      d[0] = a0; d[1] = a1; d[2] = a2; d[3] = a3;
+    } else {                // stored as (J,I): element (ii, jj+q) is G[32J+ii][32I+jj+q]
+      Gs[(jj + 0) * GP + 32 * J + ii] = a0;
+      Gs[(jj + 1) * GP + 32 * J + ii] = a1;
+      Gs[(jj + 2) * GP + 32 * J + ii] = a2;
+      Gs[(jj + 3) * GP + 32 * J + ii] = a3;
     }
   }
   __syncthreads();
-  // scale the columns: L[i][k] = S[i][k] / sqrt(piv_k); dropped columns become exact zeros
+
+  {  // T_I = G_I Phi: thread (r, cg) owns T[r][cg*CPT .. +CPT)
+    const int r = tid >> 3, cg = tid & 7;
+    double acc[CPT];
+#pragma unroll
+    for (int q = 0; q < CPT; ++q) acc[q] = 0.0;
+    for (int c = 0; c < D; ++c) {
+      const double g = Gs[r * GP + c];
+#pragma unroll
+      for (int q = 0; q < CPT; ++q) acc[q] += g * (double)PH[c * M + cg * CPT + q];
+    }
+#pragma unroll
+    for (int q = 0; q < CPT; ++q) Ts[r * TP + cg * CPT + q] = acc[q];
+  }
+  __syncthreads();
+
+  // S_I = Phi_I^T T_I
+  double *out = s_parts + ((size_t)lhead * 4 + I) * (M * M);
   for (int idx = tid; idx < M * M; idx += 256) {
-    const int i = idx / M, k = idx - i * M;
-    if (k < i) {
-      const double pk = piv_s[k];
-      S[i * SP + k] = pk > 0.0 ? S[i * SP + k] / sqrt(pk) : 0.0;
-    }
+    const int a = idx / M, b = idx - a * M;
+    double sum = 0.0;
+#pragma unroll 8
+    for (int r = 0; r < 32; ++r) sum += (double)PH[(32 * I + r) * M + a] * Ts[r * TP + b];
+    out[idx] = sum;
   }
-  __syncthreads();
-
-  // W^T[:, ch] = L^{-1} Phi[ch, :]^T by forward substitution, one channel per thread
-  if (tid < D) {
-    const int ch = tid;
-    double y[M];
-#pragma unroll
-    for (int j = 0; j < M; ++j) {
-      double v = (double)PH[ch * M + j];
-#pragma unroll
-      for (int q = 0; q < j; ++q) v -= S[j * SP + q] * y[q];
-      const double pj = piv_s[j];
-      y[j] = pj > 0.0 ? v / sqrt(pj) : 0.0;
-    }
-    uint16_t *wh = wt + (size_t)lhead * (W_TERMS * M * D);
-#pragma unroll
-    for (int j = 0; j < M; ++j) {
-      float x = (float)y[j];
-#pragma unroll
-      for (int t = 0; t < W_TERMS; ++t) {
-        const uint16_t b = bf16_rne(x);
-        wh[(t * M + j) * D + ch] = b;
-        x -= bf16_to_f32(b);
-      }
-    }
-  }
-  if (tid == 0) status[sg.ghead0 + w.head] = flag;
 }
 
-hipError_t launch_solve(const SegTable &T, int ks, const float *phi, float ridge_rel,
-                        const double *g64, uint16_t *wt, int32_t *status, hipStream_t st) {
-  if (T.nheads <= 0) return hipSuccess;
-  const dim3 grid((unsigned)T.nheads), block(256);
-  if (ks == 16) {
-    hipLaunchKernelGGL((solve_sketched_kernel<16>), grid, block, 0, st, T, phi, ridge_rel, g64, wt, status);
-  } else if (ks == 32) {
-    hipLaunchKernelGGL((solve_sketched_kernel<32>), grid, block, 0, st, T, phi, ridge_rel, g64, wt, status);
-  } else if (ks == 48) {
-    hipLaunchKernelGGL((solve_sketched_kernel<48>), grid, block, 0, st, T, phi, ridge_rel, g64, wt, status);
-  } else if (ks == 64) {
-    hipLaunchKernelGGL((solve_sketched_kernel<64>), grid, block, 0, st, T, phi, ridge_rel, g64, wt, status);
-  } else if (ks > 0) {
-    hipLaunchKernelGGL((solve_kernel<64, true>), dim3((unsigned)T.nheads), dim3(256), 0, st, T, ks,
-                       phi, ridge_rel, g64, wt, status);
-  } else {
-    hipLaunchKernelGGL((solve_kernel<128, false>), dim3((unsigned)T.nheads), dim3(256), 0, st, T,
-                       D, phi, ridge_rel, g64, wt, status);
+__device__ __forceinline__ double readlane_f64(double x, int lane) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(x), lane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(x), lane);
+  return __hiloint2double(hi, lo);
+}
+
+// Step 2, solve_wave_kernel: Cholesky and forward substitution in the registers of one wave,
+// with no barrier.  Lane i holds row i of S; a pivot or a column entry needed by every lane is
+// read with v_readlane.  The register file is walked with a sliding window so that the loops
+// over the pivot index stay rolled (small code): after step k the window has moved one column
+// to the right, register 0 always holds the pivot column.  Column k of L is parked in LDS for
+// the substitution.  Two waves per head factor the same S redundantly and each produces 64 of
+// the 128 columns of W^T = L^{-1} Phi^T (lane = channel).
+//
+// PANEL steps with a window of WIN registers: one 16-column panel of the factorisation.
+template <int WIN>
+__device__ __forceinline__ void chol_panel(double (&row)[64], double d0, int k0, int lane,
+                                           double *__restrict__ Ls, int LP, double &rsv, int &flag) {
+#pragma unroll 1
+  for (int k = k0; k < k0 + 16; ++k) {
+    const double piv = readlane_f64(row[0], k);
+    const double d0k = readlane_f64(d0, k);
+    const bool ok = piv > PIVOT_REL * d0k && piv < 1.0e300;      // false for NaN too
+    const double rs = ok ? rsqrt(piv) : 0.0;
+    rsv = (lane == k) ? rs : rsv;
+    if (!ok) flag = COMPACTOR_STATUS_PIVOT;
+    const double lk = ok ? row[0] * rs : 0.0;                    // L[lane][k] (lanes > k)
+    Ls[k * LP + lane] = lk;
+    // the column just parked is read back at wave-uniform addresses (an LDS broadcast costs a
+    // third of a pair of v_readlane here); LDS operations of one wave execute in order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const double *lc = Ls + k * LP + k;                          // lc[j] = L[k + j][k]
+#pragma unroll
+    for (int j = 1; j < WIN; ++j) row[j - 1] = row[j] - lk * lc[j];
   }
+}
+
+template <int WIN>
+__device__ __forceinline__ void fwd_panel(double (&v)[64], int j0, const double *__restrict__ Ls,
+                                          int LP, double rsv, uint16_t *__restrict__ wh, int M,
+                                          int ch) {
+#pragma unroll 1
+  for (int j = j0; j < j0 + 16; ++j) {
+    const double y = v[0] * readlane_f64(rsv, j);
+    float x = (float)y;
+#pragma unroll
+    for (int t = 0; t < W_TERMS; ++t) {
+      const uint16_t b = bf16_rne(x);
+      wh[(t * M + j) * D + ch] = b;
+      x -= bf16_to_f32(b);
+    }
+    const double *lc = Ls + j * LP + j;          // L[j + i][j], i = 1.. (same address in all lanes)
+#pragma unroll
+    for (int i = 1; i < WIN; ++i) v[i - 1] = v[i] - lc[i] * y;
+  }
+}
+
+template <int M>
+__global__ __launch_bounds__(64) void solve_wave_kernel(const SegTable T,
+                                                        const float *__restrict__ phi,
+                                                        float ridge_rel,
+                                                        const double *__restrict__ s_parts,
+                                                        uint16_t *__restrict__ wt,
+                                                        int32_t *__restrict__ status) {
+  constexpr int LP = 64 + 16;                    // row pitch of the parked L (doubles); the pad
+  __shared__ double Ls[M * LP];                  // absorbs the reads past column M-1 below
+  const int lhead = blockIdx.x >> 1, half = blockIdx.x & 1;
+  const int lane = threadIdx.x;
+  const bool rowlane = lane < M;
+  const double *sp = s_parts + (size_t)lhead * 4 * (M * M);
+
+#ifdef SOLVE_PROFILE
+  long long tp0 = clock64(), tp1, tp2, tp3;
+#endif
+  // S is symmetric: lane i reads S[j][i], contiguous across lanes, as its row entry (i, j)
+  double row[64];
+#pragma unroll
+  for (int j = 0; j < 64; ++j) row[j] = 0.0;
+#pragma unroll 1
+  for (int part = 0; part < 4; ++part) {       // one contribution at a time: M loads in flight
+    double tmp[M];
+#pragma unroll
+    for (int j = 0; j < M; ++j) tmp[j] = rowlane ? sp[part * M * M + j * M + lane] : 0.0;
+#pragma unroll
+    for (int j = 0; j < M; ++j) row[j] += tmp[j];
+  }
+  double diag = 0.0;
+#pragma unroll
+  for (int j = 0; j < M; ++j) diag = (lane == j) ? row[j] : diag;
+  double tr = diag;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) tr += __shfl_xor(tr, d);
+  const double rho = (double)ridge_rel * tr / (double)M;
+  const double d0 = diag + rho;
+#pragma unroll
+  for (int j = 0; j < M; ++j) row[j] += (lane == j) ? rho : 0.0;
+  for (int idx = lane; idx < M * LP; idx += 64) Ls[idx] = 0.0;
+
+#ifdef SOLVE_PROFILE
+  tp1 = clock64();
+#endif
+  // right-looking Cholesky in 16-column panels; the window shrinks by 16 per panel
+  double rsv = 0.0;                              // lane k: 1 / L[k][k] (0 for a dropped pivot)
+  int flag = 0;
+  if constexpr (M >= 64) chol_panel<64>(row, d0, M - 64, lane, Ls, LP, rsv, flag);
+  if constexpr (M >= 48) chol_panel<48>(row, d0, M - 48, lane, Ls, LP, rsv, flag);
+  if constexpr (M >= 32) chol_panel<32>(row, d0, M - 32, lane, Ls, LP, rsv, flag);
+  chol_panel<16>(row, d0, M - 16, lane, Ls, LP, rsv, flag);
+  // the substitution below reads what other lanes parked in LDS: keep the order
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+#ifdef SOLVE_PROFILE
+  tp2 = clock64();
+#endif
+  // forward substitution, column oriented, same sliding window: v -= L[:, j] * y_j
+  const int ch = 64 * half + lane;
+  double v[64];
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (4 * q < M) f = *reinterpret_cast<const float4 *>(phi + ch * M + 4 * q);
+    v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+  }
+  uint16_t *wh = wt + (size_t)lhead * (W_TERMS * M * D);
+  if constexpr (M >= 64) fwd_panel<64>(v, M - 64, Ls, LP, rsv, wh, M, ch);
+  if constexpr (M >= 48) fwd_panel<48>(v, M - 48, Ls, LP, rsv, wh, M, ch);
+  if constexpr (M >= 32) fwd_panel<32>(v, M - 32, Ls, LP, rsv, wh, M, ch);
+  fwd_panel<16>(v, M - 16, Ls, LP, rsv, wh, M, ch);
+
+#ifdef SOLVE_PROFILE
+  tp3 = clock64();
+  if (lane == 0 && blockIdx.x == 6)
+    printf("solve_wave phases (cycles): load %lld  chol %lld  fwd %lld\n", tp1 - tp0, tp2 - tp1, tp3 - tp2);
+#endif
+  if (half == 0 && lane == 0) {
+    const Where w = locate_head(T, lhead);
+    status[T.s[w.seg].ghead0 + w.head] = flag;
+  }
+}
+
+template <int M>
+static hipError_t launch_sketched(const SegTable &T, int rows_per_wg, const float *partials,
+                                  const float *phi, float ridge_rel, double *s_parts,
+                                  uint16_t *wt, int32_t *status, hipStream_t st, hipEvent_t mid) {
+  hipLaunchKernelGGL((sketch_kernel<M>), dim3((unsigned)T.nheads * 4), dim3(256), 0, st, T,
+                     rows_per_wg, partials, phi, s_parts);
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  if (mid && hipEventRecord(mid, st) != hipSuccess) return hipErrorLaunchFailure;
+  hipLaunchKernelGGL((solve_wave_kernel<M>), dim3((unsigned)T.nheads * 2), dim3(64), 0, st, T, phi,
+                     ridge_rel, s_parts, wt, status);
+  return hipGetLastError();
+}
+
+// Sketched mode: partial Gram blocks -> W^T in two kernels (see above).  `mid`, if not null, is
+// recorded between them (profiling).
+hipError_t launch_sketch_solve(const SegTable &T, int ks, int rows_per_wg, const float *partials,
+                               const float *phi, float ridge_rel, double *s_parts, uint16_t *wt,
+                               int32_t *status, hipStream_t st, hipEvent_t mid) {
+  if (T.nheads <= 0) return hipSuccess;
+  switch (ks) {
+    case 16: return launch_sketched<16>(T, rows_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
+    case 32: return launch_sketched<32>(T, rows_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
+    case 48: return launch_sketched<48>(T, rows_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
+    case 64: return launch_sketched<64>(T, rows_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// Exact mode: full G (fp64, from gram_reduce) -> Cholesky of G + rho I -> W^T = L^{-1}.
+hipError_t launch_solve(const SegTable &T, float ridge_rel, const double *g64, uint16_t *wt,
+                        int32_t *status, hipStream_t st) {
+  if (T.nheads <= 0) return hipSuccess;
+  hipLaunchKernelGGL(solve_exact_kernel, dim3((unsigned)T.nheads), dim3(256), 0, st, T, ridge_rel,
+                     g64, wt, status);
   return hipGetLastError();
 }
 

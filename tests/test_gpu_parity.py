@@ -210,6 +210,17 @@ def test_separate_calls_equal_fused_call(C):
     assert torch.equal(fused["kept_idx"], kept) and torch.equal(fused["kept_cnt"], cnt)
     assert torch.equal(fused["k_packed"].view(torch.int16), kp.view(torch.int16))
     assert torch.equal(fused["v_packed"].view(torch.int16), vp.view(torch.int16))
+    # spreading the head groups over helper streams changes nothing either
+    for lanes in (2, 4):
+        params_s, _ = U.make_call(C, w, DEV)
+        params_s.streams = lanes
+        multi = C.compactor_compress(params_s, reqs, want_scores=True)
+        torch.cuda.synchronize()
+        assert torch.equal(fused["scores"].view(torch.int32), multi["scores"].view(torch.int32))
+        assert torch.equal(fused["kept_idx"], multi["kept_idx"])
+        assert torch.equal(fused["k_packed"].view(torch.int16), multi["k_packed"].view(torch.int16))
+        assert torch.equal(fused["v_packed"].view(torch.int16), multi["v_packed"].view(torch.int16))
+        assert torch.equal(fused["status"], multi["status"])
     # run-to-run determinism
     again = C.compactor_compress(params, reqs, want_scores=True)
     torch.cuda.synchronize()
