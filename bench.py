@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's own)")
     ap.add_argument("--group-mb", type=float, default=0.0, help="head-group size in MiB (0 = library default)")
-    ap.add_argument("--gram-rows", type=int, default=0, help="tuning override (0 = library's choice)")
+    ap.add_argument("--gram-wgs", type=int, default=0, help="tuning override (0 = library's choice)")
     ap.add_argument("--score-tokens", type=int, default=0, help="tuning override (0 = library's choice)")
     ap.add_argument("--streams", type=int, default=0, help="stream lanes (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -122,7 +122,7 @@ def main():
     group_bytes = int(a.group_mb * 1024 * 1024)
     mk = lambda events: C.Params(w.layers, w.kv_heads, sketch_dim=w.sketch_dim, phi=phi,
                                  ridge_rel=w.ridge_rel, group_bytes=group_bytes, stage_events=events,
-                                 gram_rows=a.gram_rows, score_tokens=a.score_tokens,
+                                 gram_wgs=a.gram_wgs, score_tokens=a.score_tokens,
                                  streams=(1 if events is not None else a.streams))
     params, params_ev = mk(None), mk(ev)
     reqs = [C.Request(k_score=r.k, v_cache=r.v, ratio=r.ratio) for r in w.requests]

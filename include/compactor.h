@@ -93,8 +93,8 @@ typedef struct compactor_params {
   int64_t group_bytes;    /* tuning: heads are processed in groups whose keys total about this
                              many bytes so that the second pass over a group's keys hits the
                              last-level cache; 0 = library default */
-  int32_t gram_rows;      /* tuning: target key rows per workgroup of the Gram kernel and target */
-  int32_t score_tokens;   /* tokens per workgroup of the score kernel; 0 = chosen by the library */
+  int32_t gram_wgs;       /* tuning: workgroups of the persistent Gram kernel and target tokens */
+  int32_t score_tokens;   /* per workgroup of the score kernel; 0 = chosen by the library */
   int32_t streams;        /* concurrency: 0 or 1 = every kernel on the caller's stream.  2..4 = head
                              groups are spread over that many lanes (the caller's stream plus
                              helper streams that the library creates once per device and keeps),

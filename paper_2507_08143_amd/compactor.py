@@ -39,7 +39,7 @@ class _Params(C.Structure):
     _fields_ = [("layers", C.c_int32), ("kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("sketch_dim", C.c_int32), ("phi", C.c_void_p), ("ridge_rel", C.c_float),
                 ("lambda_blend", C.c_float), ("group_bytes", C.c_int64),
-                ("gram_rows", C.c_int32), ("score_tokens", C.c_int32), ("streams", C.c_int32),
+                ("gram_wgs", C.c_int32), ("score_tokens", C.c_int32), ("streams", C.c_int32),
                 ("stage_events", C.c_void_p)]
 
 
@@ -131,7 +131,7 @@ class Params:
     group_bytes: int = 0
     head_dim: int = 128
     stage_events: Optional["StageEvents"] = None   # profiling aid (see the header)
-    gram_rows: int = 0                              # tuning knobs, 0 = library's choice
+    gram_wgs: int = 0                              # tuning knobs, 0 = library's choice
     score_tokens: int = 0
     streams: int = 0                                # 2..4 = spread head groups over helper streams
 
@@ -142,7 +142,7 @@ class Params:
             phi = self.phi.data_ptr()
         ev = C.cast(self.stage_events.array, C.c_void_p) if self.stage_events is not None else None
         return _Params(self.layers, self.kv_heads, self.head_dim, self.sketch_dim, phi,
-                       self.ridge_rel, self.lambda_blend, self.group_bytes, self.gram_rows,
+                       self.ridge_rel, self.lambda_blend, self.group_bytes, self.gram_wgs,
                        self.score_tokens, self.streams, ev)
 
 

@@ -32,7 +32,7 @@ int check_params(const compactor_params_t *p, bool scoring) {
     if (!(p->ridge_rel >= 0.f) || !isfinite(p->ridge_rel)) return COMPACTOR_EINVAL;
     if (!isfinite(p->lambda_blend)) return COMPACTOR_EINVAL;
   }
-  if (p->group_bytes < 0 || p->gram_rows < 0 || p->score_tokens < 0 || p->streams < 0)
+  if (p->group_bytes < 0 || p->gram_wgs < 0 || p->score_tokens < 0 || p->streams < 0)
     return COMPACTOR_EINVAL;
   return COMPACTOR_OK;
 }
@@ -81,10 +81,19 @@ int compute_units() {
   return n;
 }
 
-// Gram: 3 workgroups per compute unit; a workgroup writes a 40 KB partial that is read back once.
-int gram_rows_for(const compactor_params_t *p, const SegTable &T, int cus) {
-  if (p->gram_rows > 0) return (p->gram_rows + GRAM_TILE - 1) / GRAM_TILE * GRAM_TILE;
-  return pick_chunk(T, 512, 4096, GRAM_TILE, 3 * cus, 2.0 * GRAM_PARTIAL_FLOATS * sizeof(float));
+// Gram: a persistent launch of 2 workgroups per compute unit (or as many as there are tiles),
+// each taking an equal run of 64-row tiles.
+struct GramPlan { int nwg, tiles_per_wg; };
+GramPlan gram_plan(const compactor_params_t *p, const SegTable &T, int cus) {
+  const long long total = total_tiles(T);
+  long long want = p->gram_wgs > 0 ? p->gram_wgs : 2ll * cus;
+  if (want > total) want = total;
+  if (want < 1) want = 1;
+  GramPlan g;
+  g.tiles_per_wg = (int)((total + want - 1) / want);
+  if (g.tiles_per_wg < 1) g.tiles_per_wg = 1;
+  g.nwg = (int)((total + g.tiles_per_wg - 1) / g.tiles_per_wg);
+  return g;
 }
 
 // Score: 2 workgroups per compute unit; a workgroup stages W^T (about 26 KB) once.
@@ -104,7 +113,7 @@ GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bo
   for (int i = 0; i < T.nseg; ++i) rows += (long long)T.s[i].n * T.s[i].head_count;
   const int m = ks > 0 ? ks : D;
   GroupBytes g;
-  g.partials = align_up((size_t)total_blocks(T, gram_rows_for(p, T, compute_units()), GRAM_TILE, false) *
+  g.partials = align_up(((size_t)gram_plan(p, T, compute_units()).nwg + T.nheads) *
                         GRAM_PARTIAL_FLOATS * sizeof(float));
   g.g64 = align_up((size_t)T.nheads * D * D * sizeof(double));
   g.wt = align_up((size_t)T.nheads * W_TERMS * m * D * sizeof(uint16_t));
@@ -255,10 +264,11 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   double *g64 = reinterpret_cast<double *>(ws + gb.partials);
   uint16_t *wt = reinterpret_cast<uint16_t *>(ws + gb.partials + gb.g64);
   const int cus = compute_units();
-  const int rpw = gram_rows_for(p, T, cus);
+  const GramPlan gp = gram_plan(p, T, cus);
+  const int rpw = gp.tiles_per_wg;
   const Marks m{p->stage_events, st};
   MARK(m, 0);
-  HIP_TRY(launch_gram(T, rpw, partials, st));
+  HIP_TRY(launch_gram(T, gp.nwg, gp.tiles_per_wg, partials, st));
   MARK(m, COMPACTOR_STAGE_GRAM + 1);
   if (p->sketch_dim > 0) {
     hipEvent_t mid = m.ev ? static_cast<hipEvent_t>(m.ev[COMPACTOR_STAGE_REDUCE + 1]) : nullptr;
@@ -326,7 +336,7 @@ void compactor_default_params(compactor_params_t *p, int32_t layers, int32_t kv_
   p->ridge_rel = 0.f;
   p->lambda_blend = 0.3f;
   p->group_bytes = 0;
-  p->gram_rows = 0;
+  p->gram_wgs = 0;
   p->score_tokens = 0;
   p->streams = 0;
   p->stage_events = nullptr;

@@ -124,19 +124,31 @@ __host__ __device__ __forceinline__ int upper_block(int I, int J) {
   return I * 4 - (I * (I - 1)) / 2 + (J - I);
 }
 
-// First partial and number of row splits of launch-local head `lhead` (Gram workgroups are
-// numbered segment by segment, head by head, split by split).
-__device__ __forceinline__ long long partial_base(const SegTable &T, int lhead, int rows_per_wg,
+// The Gram kernel numbers the launch's 64-row tiles head after head and deals them out evenly,
+// tiles_per_wg to a workgroup; the partial of (workgroup i, head h) lives in slot i + h.
+__host__ __device__ __forceinline__ int tiles_of(int n) { return (n + GRAM_TILE - 1) / GRAM_TILE; }
+
+inline long long total_tiles(const SegTable &T) {
+  long long t = 0;
+  for (int i = 0; i < T.nseg; ++i) t += (long long)tiles_of(T.s[i].n) * T.s[i].head_count;
+  return t;
+}
+
+// First partial slot of launch-local head `lhead` and the number of consecutive slots (one per
+// workgroup that touched the head).
+__device__ __forceinline__ long long partial_base(const SegTable &T, int lhead, int tiles_per_wg,
                                                   int &nsplit) {
   long long base = 0;
   for (int i = 0; i < T.nseg; ++i) {
-    const int bph = blocks_per_head(T.s[i].n, rows_per_wg, GRAM_TILE);
+    const int tph = tiles_of(T.s[i].n);
     const int hh = lhead - T.s[i].lhead0;
     if (hh < T.s[i].head_count || i == T.nseg - 1) {
-      nsplit = bph;
-      return base + (long long)hh * bph;
+      const long long t0 = base + (long long)hh * tph;        // first tile of the head
+      const long long first = t0 / tiles_per_wg, last = (t0 + tph - 1) / tiles_per_wg;
+      nsplit = (int)(last - first + 1);
+      return first + lhead;
     }
-    base += (long long)bph * T.s[i].head_count;
+    base += (long long)tph * T.s[i].head_count;
   }
   nsplit = 0;
   return 0;
@@ -145,12 +157,13 @@ __device__ __forceinline__ long long partial_base(const SegTable &T, int lhead, 
 // ---- host-side launchers (one per translation unit) -------------------------------------
 // All of them enqueue on `st` and return the hipGetLastError() of their launches.
 
-// Partial Gram matrices: the 10 upper 32x32 blocks (fp32) per (head, row split), split-major
-// inside a head.
-hipError_t launch_gram(const SegTable &T, int rows_per_wg, float *partials, hipStream_t st);
+// Partial Gram matrices: the 10 upper 32x32 blocks (fp32) per (workgroup, head) intersection,
+// nwg + nheads slots.
+hipError_t launch_gram(const SegTable &T, int nwg, int tiles_per_wg, float *partials,
+                       hipStream_t st);
 
 // G64[lhead] = sum over splits of the head's partials, in fp64.
-hipError_t launch_gram_reduce(const SegTable &T, int rows_per_wg, const float *partials,
+hipError_t launch_gram_reduce(const SegTable &T, int tiles_per_wg, const float *partials,
                               double *g64, hipStream_t st);
 
 // Exact mode: factor G + rho I and emit W^T (as W_TERMS bf16 planes, [term][128][128] per head)
@@ -161,7 +174,7 @@ hipError_t launch_solve(const SegTable &T, float ridge_rel, const double *g64, u
 // Sketched mode: partial Gram blocks -> S = Phi^T G Phi (4 contributions per head in s_parts)
 // -> W^T ([term][k_s][128] per head) and status.  `mid`, if not null, is recorded between the
 // two kernels.
-hipError_t launch_sketch_solve(const SegTable &T, int ks, int rows_per_wg, const float *partials,
+hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, const float *partials,
                                const float *phi, float ridge_rel, double *s_parts, uint16_t *wt,
                                int32_t *status, hipStream_t st, hipEvent_t mid);
 

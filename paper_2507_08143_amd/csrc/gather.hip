@@ -10,7 +10,11 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
                                                      const int32_t *__restrict__ kept_idx,
                                                      uint16_t *__restrict__ k_packed,
                                                      uint16_t *__restrict__ v_packed) {
+#ifdef GATHER_REVERSE
+  const Where w = locate_block(T, gridDim.x - 1 - blockIdx.x, GATHER_ROWS, GATHER_ROWS, true);
+#else
   const Where w = locate_block(T, blockIdx.x, GATHER_ROWS, GATHER_ROWS, true);
+#endif
   const Seg &s = T.s[w.seg];
   const int k = s.k_keep;
   const long long row0 = s.kept_off + (long long)w.head * k;      // first packed row of the head

@@ -31,26 +31,77 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char *p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p));
 }
 
+// Position in the launch's tile sequence: tiles of 64 key rows, head after head.
+struct TileCursor {
+  int seg, hh, tile, tph, n;        // segment, head inside the segment, tile inside the head
+  long long stride_t;
+  const uint16_t *kp;               // first row of the head
+};
+
+__device__ __forceinline__ void cursor_head(const SegTable &T, TileCursor &c) {
+  const Seg &s = T.s[c.seg];
+  c.n = s.n;
+  c.tph = tiles_of(s.n);
+  c.stride_t = s.stride_t;
+  c.kp = head_ptr(s.k_score, s, s.head_begin + c.hh);
+}
+
+__device__ __forceinline__ void cursor_seek(const SegTable &T, long long g, TileCursor &c) {
+  long long base = 0;
+  c.seg = 0; c.hh = 0; c.tile = 0;
+  for (int i = 0; i < T.nseg; ++i) {
+    const int tph = tiles_of(T.s[i].n);
+    const long long cnt = (long long)tph * T.s[i].head_count;
+    if (g < base + cnt || i == T.nseg - 1) {
+      const long long local = g - base;
+      c.seg = i;
+      c.hh = (int)(local / tph);
+      c.tile = (int)(local - (long long)c.hh * tph);
+      break;
+    }
+    base += cnt;
+  }
+  cursor_head(T, c);
+}
+
+// Moves to the next tile.  Past the last tile of the launch the cursor wraps inside the last
+// segment; such positions are never loaded (the callers mask by tile count).
+__device__ __forceinline__ void cursor_next(const SegTable &T, TileCursor &c) {
+  if (++c.tile == c.tph) {
+    c.tile = 0;
+    if (++c.hh == T.s[c.seg].head_count) {
+      c.hh = 0;
+      if (c.seg + 1 < T.nseg) ++c.seg;
+    }
+    cursor_head(T, c);
+  }
+}
+
+// Persistent kernel: the launch's tiles are dealt out evenly, workgroup i takes tiles
+// [i * tiles_per_wg, (i+1) * tiles_per_wg), crossing head boundaries where they fall.  Each
+// (workgroup, head) intersection yields one partial Gram matrix, stored in slot
+// workgroup + head (unique, because along the tile sequence workgroup and head only grow).
+// All workgroups are resident at once and do the same amount of streaming, so there is no
+// tail, and the partials are written when a head ends, spread over the run of the kernel.
+//
 // The 10 upper blocks are split over the 4 waves of a workgroup (3, 3, 2, 2): every wave sees
 // all tokens of the tile but owns its blocks outright, so no cross-wave reduction is needed and
 // a wave carries at most 48 accumulator registers.
 //   wave 0: (0,0) (0,1) (0,2)   wave 1: (0,3) (1,1) (1,2)   wave 2: (1,3) (2,2)   wave 3: (2,3) (3,3)
 #ifndef GRAM_OCC
-#define GRAM_OCC 3          // waves per SIMD the register budget is set for
+#define GRAM_OCC 2          // waves per SIMD the register budget is set for
 #endif
 #ifndef GRAM_TG_UNROLL
 #define GRAM_TG_UNROLL 4    // 16-token steps unrolled together (more = more operands in flight)
 #endif
-__global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, int rows_per_wg,
-                                                      float *__restrict__ partials) {
+__global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, int tiles_per_wg,
+                                                             long long total,
+                                                             float *__restrict__ partials) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TILE_BYTES];
 
-  const Where w = locate_block(T, blockIdx.x, rows_per_wg, GRAM_TILE, false);
-  const Seg &s = T.s[w.seg];
-  const uint16_t *kp = head_ptr(s.k_score, s, w.head);
-  const long long stride_t = s.stride_t;
-  const int r0 = w.tile * w.chunk;
-  const int r1 = min(s.n, r0 + w.chunk);
+  const long long g0 = (long long)blockIdx.x * tiles_per_wg;
+  const int count = (int)min((long long)tiles_per_wg, total - g0);
+  if (count <= 0) return;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -62,16 +113,19 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
 
-  const int ntiles = (r1 - r0 + GRAM_TILE - 1) / GRAM_TILE;
-  const uint16_t *lp0 = kp + (long long)(r0 + ld_row) * stride_t + ld_chunk * 8;
-  auto load_tile = [&](int t, uint4 (&stage)[4]) {
+  TileCursor L, C;                 // load cursor runs two tiles ahead of the compute cursor
+  cursor_seek(T, g0, L);
+  C = L;
+
+  auto load_tile = [&](int t, uint4 (&stage)[4]) {   // t: tile number inside this workgroup
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int roff = t * GRAM_TILE + 16 * i;
+      const int row = L.tile * GRAM_TILE + 16 * i + ld_row;
       stage[i] = make_uint4(0, 0, 0, 0);
-      if (t < ntiles && r0 + roff + ld_row < r1)
-        stage[i] = load_stream16(lp0 + (long long)roff * stride_t);
+      if (t < count && row < L.n)
+        stage[i] = load_stream16(L.kp + (long long)row * L.stride_t + ld_chunk * 8);
     }
+    cursor_next(T, L);
   };
 
   // transpose-read addressing of this lane (see lds_read_tr): 16-lane group = (channel half,
@@ -91,14 +145,6 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
         const bf16x4 hi = lds_read_tr(p + cb * 64 + 4 * PITCH * 2);    // tokens 8g+4 .. 8g+7
         op[cb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
-#if defined(GRAM_ABLATE) && GRAM_ABLATE >= 1
-      {  // experiment: keep the LDS reads alive without MFMA
-        union { bf16x8 v; float f[4]; } u0, u1, u2, u3;
-        u0.v = op[0]; u1.v = op[1]; u2.v = op[2]; u3.v = op[3];
-        acc[0][0] += u0.f[0] + u1.f[1] + u2.f[2] + u3.f[3];
-        continue;
-      }
-#endif
       switch (wave) {
         case 0: GRAM_MFMA(0, 0, 0); GRAM_MFMA(1, 0, 1); GRAM_MFMA(2, 0, 2); break;
         case 1: GRAM_MFMA(0, 0, 3); GRAM_MFMA(1, 1, 1); GRAM_MFMA(2, 1, 2); break;
@@ -114,60 +160,54 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
       *reinterpret_cast<uint4 *>(buf + ((ld_row + 16 * i) * PITCH + ld_chunk * 8) * 2) = stage[i];
   };
 
+  // Each wave writes the blocks it owns: a partial is the 10 upper blocks, each [32][32].
+  // 32x32 accumulator layout: register v of lane l is element (8*(v>>2) + 4*(l>>5) + (v&3), l&31).
+  const int nblk = wave < 2 ? 3 : 2;
+  const int first = wave == 0 ? 0 : (wave == 1 ? 3 : (wave == 2 ? 6 : 8));
+  const int col = lane & 31, rsub = 4 * (lane >> 5);
+  auto flush = [&](int lhead) {
+    float *out = partials + ((size_t)blockIdx.x + lhead) * GRAM_PARTIAL_FLOATS;
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+      if (b < nblk) {
+        float *ob = out + (first + b) * GBLK;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          ob[(8 * (v >> 2) + rsub + (v & 3)) * 32 + col] = acc[b][v];
+          acc[b][v] = 0.f;
+        }
+      }
+    }
+  };
+  bool dirty = false;
+  auto finish_tile = [&]() {       // after a tile has been multiplied
+    dirty = true;
+    if (C.tile + 1 == C.tph) {
+      flush(T.s[C.seg].lhead0 + C.hh);
+      dirty = false;
+    }
+    cursor_next(T, C);
+  };
+
   // two tiles of global loads stay in flight while a third is being multiplied
   uint4 stA[4], stB[4];
   load_tile(0, stA);
   load_tile(1, stB);
-#if defined(GRAM_ABLATE) && GRAM_ABLATE >= 3
-  for (int t = 0; t < ntiles; t += 2) {   // experiment: global loads only
-    acc[0][1] += __uint_as_float(stA[0].x ^ stA[1].y ^ stA[2].z ^ stA[3].w);
-    load_tile(t + 2, stA);
-    acc[0][2] += __uint_as_float(stB[0].x ^ stB[1].y ^ stB[2].z ^ stB[3].w);
-    load_tile(t + 3, stB);
-  }
-  if (false)
-#elif defined(GRAM_ABLATE) && GRAM_ABLATE == 2
-  for (int t = 0; t < ntiles; t += 2) {   // experiment: loads + LDS writes + barriers
-    store_tile(smem, stA);
-    __syncthreads();
-    load_tile(t + 2, stA);
-    if (t + 1 < ntiles) {
-      store_tile(smem + TILE_BYTES, stB);
-      __syncthreads();
-      load_tile(t + 3, stB);
-    }
-  }
-  acc[0][3] += smem[tid];
-  if (false)
-#endif
-  for (int t = 0; t < ntiles; t += 2) {
+  for (int t = 0; t < count; t += 2) {
     store_tile(smem, stA);
     __syncthreads();
     load_tile(t + 2, stA);
     compute_tile(smem);
-    if (t + 1 < ntiles) {
+    finish_tile();
+    if (t + 1 < count) {
       store_tile(smem + TILE_BYTES, stB);
       __syncthreads();
       load_tile(t + 3, stB);
       compute_tile(smem + TILE_BYTES);
+      finish_tile();
     }
   }
-
-  // ---- each wave writes the blocks it owns: partial = 10 upper blocks, each [32][32] --------
-  // 32x32 accumulator layout: register v of lane l is element (8*(v>>2) + 4*(l>>5) + (v&3), l&31).
-  float *out = partials + (size_t)blockIdx.x * (10 * GBLK);
-  const int nblk = wave < 2 ? 3 : 2;
-  const int first = wave == 0 ? 0 : (wave == 1 ? 3 : (wave == 2 ? 6 : 8));
-  // wave-local block b is upper block number first + b in the order listed above
-  const int col = lane & 31, rsub = 4 * (lane >> 5);
-#pragma unroll
-  for (int b = 0; b < 3; ++b) {
-    if (b < nblk) {
-      float *ob = out + (first + b) * GBLK;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) ob[(8 * (v >> 2) + rsub + (v & 3)) * 32 + col] = acc[b][v];
-    }
-  }
+  if (dirty) flush(T.s[C.seg].lhead0 + C.hh);
 }
 
 // Order in which the waves own the upper blocks, as (I, J) per stored block number.
@@ -177,14 +217,14 @@ __device__ __constant__ int kBlockJ[10] = {0, 1, 2, 3, 1, 2, 3, 2, 3, 3};
 // G64 = sum of a head's partials in fp64, in split order (deterministic), written as the full
 // symmetric 128 x 128 matrix: one workgroup per (head, upper block), the mirror image goes
 // through an LDS transpose so that both stores are coalesced.
-__global__ __launch_bounds__(256) void gram_reduce_kernel(const SegTable T, int rows_per_wg,
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const SegTable T, int tiles_per_wg,
                                                           const float *__restrict__ partials,
                                                           double *__restrict__ g64) {
   __shared__ double tile[32][33];
   const int lhead = blockIdx.x / 10;
   const int blk = blockIdx.x - lhead * 10;
   int nsplit;
-  const long long pb = partial_base(T, lhead, rows_per_wg, nsplit);
+  const long long pb = partial_base(T, lhead, tiles_per_wg, nsplit);
   const int e = threadIdx.x * 4;                 // 4 consecutive elements of the block
   const int ii = e >> 5, jj = e & 31;
   double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
@@ -205,18 +245,20 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const SegTable T, int 
   }
 }
 
-hipError_t launch_gram(const SegTable &T, int rows_per_wg, float *partials, hipStream_t st) {
-  const long long nb = total_blocks(T, rows_per_wg, GRAM_TILE, false);
-  if (nb <= 0) return hipSuccess;
-  hipLaunchKernelGGL(gram_kernel, dim3((unsigned)nb), dim3(256), 0, st, T, rows_per_wg, partials);
+hipError_t launch_gram(const SegTable &T, int nwg, int tiles_per_wg, float *partials,
+                       hipStream_t st) {
+  const long long total = total_tiles(T);
+  if (total <= 0 || nwg <= 0) return hipSuccess;
+  hipLaunchKernelGGL(gram_kernel, dim3((unsigned)nwg), dim3(256), 0, st, T, tiles_per_wg, total,
+                     partials);
   return hipGetLastError();
 }
 
-hipError_t launch_gram_reduce(const SegTable &T, int rows_per_wg, const float *partials,
+hipError_t launch_gram_reduce(const SegTable &T, int tiles_per_wg, const float *partials,
                               double *g64, hipStream_t st) {
   if (T.nheads <= 0) return hipSuccess;
   hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)T.nheads * 10), dim3(256), 0, st, T,
-                     rows_per_wg, partials, g64);
+                     tiles_per_wg, partials, g64);
   return hipGetLastError();
 }
 

@@ -40,7 +40,11 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
   __shared__ __attribute__((aligned(16))) uint16_t wl[W_TERMS * M * WPITCH];
   __shared__ __attribute__((aligned(16))) uint16_t kl[4][WTOK * WPITCH];
 
+#ifdef SCORE_REVERSE
+  const Where w = locate_block(T, gridDim.x - 1 - blockIdx.x, tokens_per_wg, SCORE_STEP, false);
+#else
   const Where w = locate_block(T, blockIdx.x, tokens_per_wg, SCORE_STEP, false);
+#endif
   const Seg &s = T.s[w.seg];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int t16 = lane & 15, g = lane >> 4;

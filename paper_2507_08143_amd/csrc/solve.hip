@@ -127,7 +127,7 @@ __global__ __launch_bounds__(256) void solve_exact_kernel(const SegTable T, floa
 // S = Phi^T G Phi = sum_I S_I.  All the O(d^2 k_s) work of the factorisation step is here,
 // spread over 4 x heads workgroups.
 template <int M>
-__global__ __launch_bounds__(256) void sketch_kernel(const SegTable T, int rows_per_wg,
+__global__ __launch_bounds__(256) void sketch_kernel(const SegTable T, int tiles_per_wg,
                                                      const float *__restrict__ partials,
                                                      const float *__restrict__ phi,
                                                      double *__restrict__ s_parts) {
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void sketch_kernel(const SegTable T, int rows_
 
   // rows 32I .. 32I+31 of G from the stored upper blocks (mirror blocks read transposed)
   int nsplit;
-  const long long pb = partial_base(T, lhead, rows_per_wg, nsplit);
+  const long long pb = partial_base(T, lhead, tiles_per_wg, nsplit);
   const int e = tid * 4, ii = e >> 5, jj = e & 31;
 #pragma unroll
   for (int J = 0; J < 4; ++J) {
@@ -337,11 +337,11 @@ __global__ __launch_bounds__(64) void solve_wave_kernel(const SegTable T,
 }
 
 template <int M>
-static hipError_t launch_sketched(const SegTable &T, int rows_per_wg, const float *partials,
+static hipError_t launch_sketched(const SegTable &T, int tiles_per_wg, const float *partials,
                                   const float *phi, float ridge_rel, double *s_parts,
                                   uint16_t *wt, int32_t *status, hipStream_t st, hipEvent_t mid) {
   hipLaunchKernelGGL((sketch_kernel<M>), dim3((unsigned)T.nheads * 4), dim3(256), 0, st, T,
-                     rows_per_wg, partials, phi, s_parts);
+                     tiles_per_wg, partials, phi, s_parts);
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   if (mid && hipEventRecord(mid, st) != hipSuccess) return hipErrorLaunchFailure;
   hipLaunchKernelGGL((solve_wave_kernel<M>), dim3((unsigned)T.nheads * 2), dim3(64), 0, st, T, phi,
@@ -351,15 +351,15 @@ static hipError_t launch_sketched(const SegTable &T, int rows_per_wg, const floa
 
 // Sketched mode: partial Gram blocks -> W^T in two kernels (see above).  `mid`, if not null, is
 // recorded between them (profiling).
-hipError_t launch_sketch_solve(const SegTable &T, int ks, int rows_per_wg, const float *partials,
+hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, const float *partials,
                                const float *phi, float ridge_rel, double *s_parts, uint16_t *wt,
                                int32_t *status, hipStream_t st, hipEvent_t mid) {
   if (T.nheads <= 0) return hipSuccess;
   switch (ks) {
-    case 16: return launch_sketched<16>(T, rows_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
-    case 32: return launch_sketched<32>(T, rows_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
-    case 48: return launch_sketched<48>(T, rows_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
-    case 64: return launch_sketched<64>(T, rows_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
+    case 16: return launch_sketched<16>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
+    case 32: return launch_sketched<32>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
+    case 48: return launch_sketched<48>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
+    case 64: return launch_sketched<64>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, st, mid);
     default: return hipErrorInvalidValue;
   }
 }

@@ -188,8 +188,29 @@ def test_blend_with_attention_scores(C):
     st, _ = U.run_and_check(C, w, DEV, kept_tol_scale=50.0)
 
 
+def _same_up_to_rounding(C, w, params, reqs, ref, other, what):
+    """A different launch partition changes the fp32 summation order of the Gram matrix, so
+    scores may move in their last bits: they must agree to 1e-5 relative, and the selections
+    may differ only between tokens whose scores are that close to the threshold."""
+    so, ko, kk = C.compactor_layout(params, reqs)
+    a, b = ref["scores"].double(), other["scores"].double()
+    assert torch.all((a - b).abs() <= 1e-5 * a.abs() + 1e-9), what
+    LH = w.layers * w.kv_heads
+    sa, ia, ib = ref["scores"].cpu().numpy(), ref["kept_idx"].cpu().numpy(), other["kept_idx"].cpu().numpy()
+    kp, vp = other["k_packed"].view(torch.int16).cpu().numpy(), other["v_packed"].view(torch.int16).cpu().numpy()
+    for bq, r in enumerate(w.requests):
+        for g in range(LH):
+            n, k = r.n, kk[bq]
+            s = sa[so[bq] + g * n: so[bq] + (g + 1) * n].astype(np.float64)
+            rows = slice(ko[bq] + g * k, ko[bq] + (g + 1) * k)
+            U.check_kept(ib[rows], ia[rows], s, what, tol_scale=0.01)
+            l, h = divmod(g, w.kv_heads)
+            assert np.array_equal(kp[rows].view(np.uint16), W.bf16_bits(r.k[l, h])[ib[rows]]), what
+            assert np.array_equal(vp[rows].view(np.uint16), W.bf16_bits(r.v[l, h])[ib[rows]]), what
+
+
 def test_separate_calls_equal_fused_call(C):
-    _say("score + select + compact == compress, bit for bit; grouping does not change results")
+    _say("score + select + compact == compress, bit for bit; regrouping only moves last bits")
     w = W.config4(device=DEV, L=2, H=3, n_req=4, n_lo=500, n_hi=3000)
     params, reqs = U.make_call(C, w, DEV)
     fused = C.compactor_compress(params, reqs, want_scores=True)
@@ -197,34 +218,34 @@ def test_separate_calls_equal_fused_call(C):
     kept, cnt = C.compactor_select(params, reqs, scores)
     kp, vp = C.compactor_compact(params, reqs, kept, cnt)
     nosc = C.compactor_compress(params, reqs, want_scores=False)
+    torch.cuda.synchronize()
+    assert torch.equal(fused["kept_idx"], nosc["kept_idx"])
+    assert torch.equal(fused["k_packed"].view(torch.int16), nosc["k_packed"].view(torch.int16))
+    assert torch.equal(fused["v_packed"].view(torch.int16), nosc["v_packed"].view(torch.int16))
+    assert torch.equal(fused["scores"].view(torch.int32), scores.view(torch.int32))
+    assert torch.equal(fused["kept_idx"], kept) and torch.equal(fused["kept_cnt"], cnt)
+    assert torch.equal(fused["k_packed"].view(torch.int16), kp.view(torch.int16))
+    assert torch.equal(fused["v_packed"].view(torch.int16), vp.view(torch.int16))
+    # run-to-run determinism
+    again = C.compactor_compress(params, reqs, want_scores=True)
+    torch.cuda.synchronize()
+    assert torch.equal(fused["scores"].view(torch.int32), again["scores"].view(torch.int32))
+    assert torch.equal(fused["kept_idx"], again["kept_idx"])
+    # head groups (one launch sequence per group) and helper-stream lanes
     params_g, _ = U.make_call(C, w, DEV, group_bytes=2 * 1024 * 1024)
     grouped = C.compactor_compress(params_g, reqs, want_scores=True)
     grouped_nosc = C.compactor_compress(params_g, reqs, want_scores=False)
     torch.cuda.synchronize()
-    for other in (nosc, grouped, grouped_nosc):
-        assert torch.equal(fused["kept_idx"], other["kept_idx"])
-        assert torch.equal(fused["k_packed"].view(torch.int16), other["k_packed"].view(torch.int16))
-        assert torch.equal(fused["v_packed"].view(torch.int16), other["v_packed"].view(torch.int16))
-    assert torch.equal(fused["scores"].view(torch.int32), scores.view(torch.int32))
-    assert torch.equal(fused["scores"].view(torch.int32), grouped["scores"].view(torch.int32))
-    assert torch.equal(fused["kept_idx"], kept) and torch.equal(fused["kept_cnt"], cnt)
-    assert torch.equal(fused["k_packed"].view(torch.int16), kp.view(torch.int16))
-    assert torch.equal(fused["v_packed"].view(torch.int16), vp.view(torch.int16))
-    # spreading the head groups over helper streams changes nothing either
+    _same_up_to_rounding(C, w, params, reqs, fused, grouped, "grouped")
+    assert torch.equal(grouped["kept_idx"], grouped_nosc["kept_idx"])
+    assert torch.equal(grouped["k_packed"].view(torch.int16), grouped_nosc["k_packed"].view(torch.int16))
     for lanes in (2, 4):
         params_s, _ = U.make_call(C, w, DEV)
         params_s.streams = lanes
         multi = C.compactor_compress(params_s, reqs, want_scores=True)
         torch.cuda.synchronize()
-        assert torch.equal(fused["scores"].view(torch.int32), multi["scores"].view(torch.int32))
-        assert torch.equal(fused["kept_idx"], multi["kept_idx"])
-        assert torch.equal(fused["k_packed"].view(torch.int16), multi["k_packed"].view(torch.int16))
-        assert torch.equal(fused["v_packed"].view(torch.int16), multi["v_packed"].view(torch.int16))
+        _same_up_to_rounding(C, w, params, reqs, fused, multi, "%d lanes" % lanes)
         assert torch.equal(fused["status"], multi["status"])
-    # run-to-run determinism
-    again = C.compactor_compress(params, reqs, want_scores=True)
-    torch.cuda.synchronize()
-    assert torch.equal(fused["scores"].view(torch.int32), again["scores"].view(torch.int32))
 
 
 def test_degenerate_inputs_are_flagged_not_fatal(C):
