@@ -56,23 +56,6 @@ int check_requests(const compactor_request_t *reqs, int32_t nreq, int need) {
   return COMPACTOR_OK;
 }
 
-// Work per workgroup of a streaming kernel.  Workgroups of one launch are equal in size and the
-// device runs `slots` of them at a time, so a launch of W workgroups takes ceil(W / slots)
-// rounds; the chunk is chosen to keep the last round full and the per-workgroup fixed cost
-// (fixed_bytes of extra traffic against chunk * 256 bytes of keys) small.
-int pick_chunk(const SegTable &T, int lo, int hi, int step, int slots, double fixed_bytes) {
-  int best = hi;
-  double best_score = -1.0;
-  for (int c = hi; c >= lo; c -= step) {
-    const double w = (double)total_blocks(T, c, step, false);
-    const double rounds = ceil(w / slots);
-    const double fill = w / (rounds * slots);
-    const double score = fill * (c * 256.0) / (c * 256.0 + fixed_bytes);
-    if (score > best_score + 1e-9) { best_score = score; best = c; }
-  }
-  return best;
-}
-
 int compute_units() {
   int dev = 0, n = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
@@ -96,10 +79,21 @@ GramPlan gram_plan(const compactor_params_t *p, const SegTable &T, int cus) {
   return g;
 }
 
-// Score: 2 workgroups per compute unit; a workgroup stages W^T (about 26 KB) once.
+// Score: workgroups of equal token runs inside a head, 2 per compute unit at a time.  A launch
+// of W workgroups takes ceil(W / slots) rounds; the run length is chosen to keep the last
+// round full and the per-workgroup fixed cost (staging W^T, about 32 KB) small.
 int score_tokens_for(const compactor_params_t *p, const SegTable &T, int cus) {
   if (p->score_tokens > 0) return (p->score_tokens + SCORE_STEP - 1) / SCORE_STEP * SCORE_STEP;
-  return pick_chunk(T, 1024, 4096, SCORE_STEP, 2 * cus, 32768.0);
+  const int slots = 2 * cus;
+  int best = 4096;
+  double best_score = -1.0;
+  for (int c = 4096; c >= 1024; c -= SCORE_STEP) {
+    const double w = (double)total_blocks(T, c, SCORE_STEP, false);
+    const double rounds = ceil(w / slots);
+    const double score = w / (rounds * slots) * (c * 256.0) / (c * 256.0 + 32768.0);
+    if (score > best_score + 1e-9) { best_score = score; best = c; }
+  }
+  return best;
 }
 
 struct GroupBytes {

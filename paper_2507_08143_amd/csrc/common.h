@@ -124,6 +124,68 @@ __host__ __device__ __forceinline__ int upper_block(int I, int J) {
   return I * 4 - (I * (I - 1)) / 2 + (J - I);
 }
 
+// ---- persistent streaming kernels: tile cursors ----------------------------------------------
+// The key rows of a launch form one sequence of TILE-row tiles, head after head (a head of n
+// rows has ceil(n / TILE) tiles, the last one ragged).  A persistent kernel deals the sequence
+// out evenly; a cursor tracks where in it a workgroup is.
+struct TileCursor {
+  int seg, hh, tile, tph, n;        // segment, head inside the segment, tile inside the head,
+  long long stride_t;               // tiles per head, rows of the head
+  const uint16_t *kp;               // first row of the head
+};
+
+template <int TILE>
+__host__ __device__ __forceinline__ int tiles_in(int n) { return (n + TILE - 1) / TILE; }
+
+template <int TILE>
+inline long long total_tiles_of(const SegTable &T) {
+  long long t = 0;
+  for (int i = 0; i < T.nseg; ++i) t += (long long)tiles_in<TILE>(T.s[i].n) * T.s[i].head_count;
+  return t;
+}
+
+template <int TILE>
+__device__ __forceinline__ void cursor_head(const SegTable &T, TileCursor &c) {
+  const Seg &s = T.s[c.seg];
+  c.n = s.n;
+  c.tph = tiles_in<TILE>(s.n);
+  c.stride_t = s.stride_t;
+  c.kp = head_ptr(s.k_score, s, s.head_begin + c.hh);
+}
+
+template <int TILE>
+__device__ __forceinline__ void cursor_seek(const SegTable &T, long long g, TileCursor &c) {
+  long long base = 0;
+  c.seg = 0; c.hh = 0; c.tile = 0;
+  for (int i = 0; i < T.nseg; ++i) {
+    const int tph = tiles_in<TILE>(T.s[i].n);
+    const long long cnt = (long long)tph * T.s[i].head_count;
+    if (g < base + cnt || i == T.nseg - 1) {
+      const long long local = g - base;
+      c.seg = i;
+      c.hh = (int)(local / tph);
+      c.tile = (int)(local - (long long)c.hh * tph);
+      break;
+    }
+    base += cnt;
+  }
+  cursor_head<TILE>(T, c);
+}
+
+// Moves to the next tile.  Past the last tile of the launch the cursor wraps inside the last
+// segment; such positions are never loaded (the callers mask by tile count).
+template <int TILE>
+__device__ __forceinline__ void cursor_next(const SegTable &T, TileCursor &c) {
+  if (++c.tile == c.tph) {
+    c.tile = 0;
+    if (++c.hh == T.s[c.seg].head_count) {
+      c.hh = 0;
+      if (c.seg + 1 < T.nseg) ++c.seg;
+    }
+    cursor_head<TILE>(T, c);
+  }
+}
+
 // The Gram kernel numbers the launch's 64-row tiles head after head and deals them out evenly,
 // tiles_per_wg to a workgroup; the partial of (workgroup i, head h) lives in slot i + h.
 __host__ __device__ __forceinline__ int tiles_of(int n) { return (n + GRAM_TILE - 1) / GRAM_TILE; }

@@ -31,52 +31,6 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char *p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p));
 }
 
-// Position in the launch's tile sequence: tiles of 64 key rows, head after head.
-struct TileCursor {
-  int seg, hh, tile, tph, n;        // segment, head inside the segment, tile inside the head
-  long long stride_t;
-  const uint16_t *kp;               // first row of the head
-};
-
-__device__ __forceinline__ void cursor_head(const SegTable &T, TileCursor &c) {
-  const Seg &s = T.s[c.seg];
-  c.n = s.n;
-  c.tph = tiles_of(s.n);
-  c.stride_t = s.stride_t;
-  c.kp = head_ptr(s.k_score, s, s.head_begin + c.hh);
-}
-
-__device__ __forceinline__ void cursor_seek(const SegTable &T, long long g, TileCursor &c) {
-  long long base = 0;
-  c.seg = 0; c.hh = 0; c.tile = 0;
-  for (int i = 0; i < T.nseg; ++i) {
-    const int tph = tiles_of(T.s[i].n);
-    const long long cnt = (long long)tph * T.s[i].head_count;
-    if (g < base + cnt || i == T.nseg - 1) {
-      const long long local = g - base;
-      c.seg = i;
-      c.hh = (int)(local / tph);
-      c.tile = (int)(local - (long long)c.hh * tph);
-      break;
-    }
-    base += cnt;
-  }
-  cursor_head(T, c);
-}
-
-// Moves to the next tile.  Past the last tile of the launch the cursor wraps inside the last
-// segment; such positions are never loaded (the callers mask by tile count).
-__device__ __forceinline__ void cursor_next(const SegTable &T, TileCursor &c) {
-  if (++c.tile == c.tph) {
-    c.tile = 0;
-    if (++c.hh == T.s[c.seg].head_count) {
-      c.hh = 0;
-      if (c.seg + 1 < T.nseg) ++c.seg;
-    }
-    cursor_head(T, c);
-  }
-}
-
 // Persistent kernel: the launch's tiles are dealt out evenly, workgroup i takes tiles
 // [i * tiles_per_wg, (i+1) * tiles_per_wg), crossing head boundaries where they fall.  Each
 // (workgroup, head) intersection yields one partial Gram matrix, stored in slot
@@ -114,7 +68,7 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
     for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
 
   TileCursor L, C;                 // load cursor runs two tiles ahead of the compute cursor
-  cursor_seek(T, g0, L);
+  cursor_seek<GRAM_TILE>(T, g0, L);
   C = L;
 
   auto load_tile = [&](int t, uint4 (&stage)[4]) {   // t: tile number inside this workgroup
@@ -125,7 +79,7 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
       if (t < count && row < L.n)
         stage[i] = load_stream16(L.kp + (long long)row * L.stride_t + ld_chunk * 8);
     }
-    cursor_next(T, L);
+    cursor_next<GRAM_TILE>(T, L);
   };
 
   // transpose-read addressing of this lane (see lds_read_tr): 16-lane group = (channel half,
@@ -186,7 +140,7 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
       flush(T.s[C.seg].lhead0 + C.hh);
       dirty = false;
     }
-    cursor_next(T, C);
+    cursor_next<GRAM_TILE>(T, C);
   };
 
   // two tiles of global loads stay in flight while a third is being multiplied
