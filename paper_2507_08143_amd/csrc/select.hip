@@ -5,7 +5,8 @@
 // (12 + 12 + 8 bits, LDS histograms), followed by an ordered emit: tokens above the threshold
 // key, plus the lowest-indexed tokens equal to it until k_keep is reached, written in
 // ascending token order.  Ties therefore go to the lower index, deterministically.
-// One workgroup of 1024 threads per head; wave ballots and popcounts give the prefix sums.
+// One workgroup of 1024 threads per head; heads of up to 32768 tokens read their scores once
+// and keep the keys in LDS (128 KB) for the later passes.
 #include "common.h"
 
 namespace cmp {
@@ -43,21 +44,12 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *wsum, int *total
   return base + inc - v;
 }
 
-// One radix pass: histogram `bits` bits at `shift` of the keys whose higher bits equal
-// `prefix` (hi_shift = 32 means no prefix), then find the digit where the descending
-// cumulative count reaches `need`.  Returns the digit; *need becomes the count still wanted
-// inside that digit.
-__device__ int radix_pass(const float *__restrict__ sp, int n, int shift, int bits, int hi_shift,
-                          uint32_t prefix, int *need, int *hist, int *wsum, int *found) {
-  const int nb = 1 << bits;
+constexpr int LDS_KEYS = 32768;    // heads up to this many tokens keep their keys in LDS
+
+// Finds, in a histogram of `nb` digits, the digit where the descending cumulative count reaches
+// `need`; returns the digit and leaves in *need the count still wanted inside that digit.
+__device__ __forceinline__ int find_digit(const int *hist, int nb, int *need, int *wsum, int *found) {
   const int tid = threadIdx.x;
-  for (int i = tid; i < 4096; i += SELECT_THREADS) hist[i] = 0;
-  __syncthreads();
-  for (int i = tid; i < n; i += SELECT_THREADS) {
-    const uint32_t k = score_key(sp[i]);
-    if (hi_shift >= 32 || (k >> hi_shift) == prefix) atomicAdd(&hist[(k >> shift) & (nb - 1)], 1);
-  }
-  __syncthreads();
   // thread t owns the 4 digits nb-1-4t .. nb-4-4t (descending), so that an ascending scan over
   // threads is a descending scan over digits
   int c[4], sum = 0;
@@ -70,7 +62,6 @@ __device__ int radix_pass(const float *__restrict__ sp, int n, int shift, int bi
   int total;
   int before = block_exclusive_scan(sum, wsum, &total);   // keys in higher digits
   const int want = *need;
-  __syncthreads();                                         // everyone has read *need
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     if (before < want && want <= before + c[q]) {          // exactly one (thread, q) matches
@@ -84,45 +75,51 @@ __device__ int radix_pass(const float *__restrict__ sp, int n, int shift, int bi
   return found[0];
 }
 
-__global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T,
-                                                                const float *__restrict__ scores,
-                                                                int32_t *__restrict__ kept_idx,
-                                                                int32_t *__restrict__ kept_cnt) {
-  __shared__ int hist[4096];
-  __shared__ int wsum[SELECT_THREADS / 64];
-  __shared__ int found[2];
-
-  const Where w = locate_block(T, blockIdx.x, 0, 1, false);
-  const Seg &s = T.s[w.seg];
-  const int n = s.n, k = s.k_keep;
-  const float *sp = scores + s.score_off + (long long)w.head * n;
-  int32_t *out = kept_idx + (s.kept_off + (long long)w.head * k);
+// One radix pass: histogram `bits` bits at `shift` of the keys whose higher bits equal `prefix`
+// (hi_shift = 32 means no prefix), then find_digit.  Keys come from LDS (FROM_LDS) or are
+// recomputed from the scores in global memory; with STORE the keys are also parked in LDS.
+template <bool FROM_LDS, bool STORE>
+__device__ int radix_pass(const float *__restrict__ sp, uint32_t *keys, int n, int shift, int bits,
+                          int hi_shift, uint32_t prefix, int *need, int *hist, int *wsum,
+                          int *found) {
+  const int nb = 1 << bits;
   const int tid = threadIdx.x;
-  if (tid == 0) kept_cnt[s.ghead0 + w.head] = k;
+  for (int i = tid; i < 4096; i += SELECT_THREADS) hist[i] = 0;
+  __syncthreads();
+#pragma unroll 8
+  for (int i = tid; i < n; i += SELECT_THREADS) {
+    const uint32_t k = FROM_LDS ? keys[i] : score_key(sp[i]);
+    if (STORE) keys[i] = k;
+    if (hi_shift >= 32 || (k >> hi_shift) == prefix) atomicAdd(&hist[(k >> shift) & (nb - 1)], 1);
+  }
+  __syncthreads();
+  return find_digit(hist, nb, need, wsum, found);
+}
 
-  // threshold key: the k-th largest
-  int need = k;
-  const uint32_t d1 = radix_pass(sp, n, 20, 12, 32, 0u, &need, hist, wsum, found);
-  const uint32_t d2 = radix_pass(sp, n, 8, 12, 20, d1, &need, hist, wsum, found);
-  const uint32_t d3 = radix_pass(sp, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
-  const uint32_t thr = (d1 << 20) | (d2 << 8) | d3;
-  const int need_eq = need;             // how many keys equal to thr are kept (lowest indices)
-
-  // ordered emit, 4 consecutive tokens per thread per round
+// Ordered emit: tokens above the threshold key, plus the first need_eq tokens equal to it, in
+// ascending token order; 4 consecutive tokens per thread per round.
+template <bool FROM_LDS>
+__device__ void emit_kept(const float *__restrict__ sp, const uint32_t *keys, int n, int k,
+                          uint32_t thr, int need_eq, int32_t *__restrict__ out, int *wsum) {
+  const int tid = threadIdx.x;
   int carry_gt = 0, carry_eq = 0;
   for (int base = 0; base < n; base += 4 * SELECT_THREADS) {
     const int i0 = base + 4 * tid;
     uint32_t key[4];
     int gt = 0, eq = 0;
+    if (FROM_LDS && i0 + 3 < n) {
+      const uint4 kv = *reinterpret_cast<const uint4 *>(keys + i0);
+      key[0] = kv.x; key[1] = kv.y; key[2] = kv.z; key[3] = kv.w;
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        key[q] = i0 + q < n ? (FROM_LDS ? keys[i0 + q] : score_key(sp[i0 + q])) : 0u;
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      key[q] = 0;
       if (i0 + q < n) {
-        key[q] = score_key(sp[i0 + q]);
         gt += key[q] > thr;
         eq += key[q] == thr;
-      } else {
-        key[q] = 0xffffffffu;           // marks "past the end" below
       }
     }
     int total;
@@ -140,6 +137,38 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T
     }
     carry_gt += total & 0xffff;
     carry_eq += total >> 16;
+  }
+}
+
+__global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T,
+                                                                const float *__restrict__ scores,
+                                                                int32_t *__restrict__ kept_idx,
+                                                                int32_t *__restrict__ kept_cnt) {
+  __shared__ __attribute__((aligned(16))) uint32_t keys[LDS_KEYS];
+  __shared__ int hist[4096];
+  __shared__ int wsum[SELECT_THREADS / 64];
+  __shared__ int found[2];
+
+  const Where w = locate_block(T, blockIdx.x, 0, 1, false);
+  const Seg &s = T.s[w.seg];
+  const int n = s.n, k = s.k_keep;
+  const float *sp = scores + s.score_off + (long long)w.head * n;
+  int32_t *out = kept_idx + (s.kept_off + (long long)w.head * k);
+  const int tid = threadIdx.x;
+  if (tid == 0) kept_cnt[s.ghead0 + w.head] = k;
+
+  // threshold key = the k-th largest, by three radix passes (12 + 12 + 8 bits)
+  int need = k;
+  if (n <= LDS_KEYS) {       // one read of the scores; everything else runs out of LDS
+    const uint32_t d1 = radix_pass<false, true>(sp, keys, n, 20, 12, 32, 0u, &need, hist, wsum, found);
+    const uint32_t d2 = radix_pass<true, false>(sp, keys, n, 8, 12, 20, d1, &need, hist, wsum, found);
+    const uint32_t d3 = radix_pass<true, false>(sp, keys, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
+    emit_kept<true>(sp, keys, n, k, (d1 << 20) | (d2 << 8) | d3, need, out, wsum);
+  } else {
+    const uint32_t d1 = radix_pass<false, false>(sp, keys, n, 20, 12, 32, 0u, &need, hist, wsum, found);
+    const uint32_t d2 = radix_pass<false, false>(sp, keys, n, 8, 12, 20, d1, &need, hist, wsum, found);
+    const uint32_t d3 = radix_pass<false, false>(sp, keys, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
+    emit_kept<false>(sp, keys, n, k, (d1 << 20) | (d2 << 8) | d3, need, out, wsum);
   }
 }
 
