@@ -11,6 +11,8 @@
 
 namespace cmp {
 
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ Where locate_head(const SegTable &T, int lhead) {
   Where w{0, 0, lhead, 0};
   for (int i = 0; i < T.nseg; ++i) {
@@ -124,14 +126,14 @@ __global__ __launch_bounds__(256) void solve_exact_kernel(const SegTable T, floa
 // Step 1, sketch_kernel: one workgroup per (head, 32-row block I of G).  It sums the head's
 // partial Gram blocks in fp64 (split order, deterministic), forms the rows G_I (32 x 128),
 // T_I = G_I Phi (32 x k_s) and the contribution S_I = Phi_I^T T_I (k_s x k_s) to
-// S = Phi^T G Phi = sum_I S_I.  All the O(d^2 k_s) work of the factorisation step is here,
-// spread over 4 x heads workgroups.
+// S = Phi^T G Phi = sum_I S_I, both on the fp64 matrix cores.  All the O(d^2 k_s) work of the
+// factorisation step is here, spread over 4 x heads workgroups.
 template <int M>
 __global__ __launch_bounds__(256) void sketch_kernel(const SegTable T, int tiles_per_wg,
                                                      const float *__restrict__ partials,
                                                      const float *__restrict__ phi,
                                                      double *__restrict__ s_parts) {
-  constexpr int GP = D + 1, TP = M + 1, CPT = M / 8;     // CPT: T columns per thread
+  constexpr int GP = D + 1, TP = M + 1;
   __shared__ double Gs[32 * GP];
   __shared__ double Ts[32 * TP];
   __shared__ __attribute__((aligned(16))) float PH[D * M];
@@ -166,29 +168,38 @@ __global__ __launch_bounds__(256) void sketch_kernel(const SegTable T, int tiles
   }
   __syncthreads();
 
-  {  // T_I = G_I Phi: thread (r, cg) owns T[r][cg*CPT .. +CPT)
-    const int r = tid >> 3, cg = tid & 7;
-    double acc[CPT];
-#pragma unroll
-    for (int q = 0; q < CPT; ++q) acc[q] = 0.0;
-    for (int c = 0; c < D; ++c) {
-      const double g = Gs[r * GP + c];
-#pragma unroll
-      for (int q = 0; q < CPT; ++q) acc[q] += g * (double)PH[c * M + cg * CPT + q];
+  // fp64 MFMA 16x16x4: A[i][k] sits in lane (i = l & 15, k = l >> 4), B[k][j] in lane
+  // (j = l & 15, k = l >> 4); register v of lane l of the result is D[4*v + (l >> 4)][l & 15].
+  const int wave = tid >> 6, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
+  constexpr int CT = M / 16;
+  // T_I = G_I Phi (32 x M): 2 x CT tiles, K = 128
+  for (int tile = wave; tile < 2 * CT; tile += 4) {
+    const int rt = tile / CT, ct = tile - rt * CT;
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll 8
+    for (int ks = 0; ks < D / 4; ++ks) {
+      const double a = Gs[(16 * rt + l16) * GP + 4 * ks + lq];
+      const double b = (double)PH[(4 * ks + lq) * M + 16 * ct + l16];
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
     }
 #pragma unroll
-    for (int q = 0; q < CPT; ++q) Ts[r * TP + cg * CPT + q] = acc[q];
+    for (int v = 0; v < 4; ++v) Ts[(16 * rt + 4 * v + lq) * TP + 16 * ct + l16] = acc[v];
   }
   __syncthreads();
 
-  // S_I = Phi_I^T T_I
+  // S_I = Phi_I^T T_I (M x M): CT x CT tiles, K = 32
   double *out = s_parts + ((size_t)lhead * 4 + I) * (M * M);
-  for (int idx = tid; idx < M * M; idx += 256) {
-    const int a = idx / M, b = idx - a * M;
-    double sum = 0.0;
-#pragma unroll 8
-    for (int r = 0; r < 32; ++r) sum += (double)PH[(32 * I + r) * M + a] * Ts[r * TP + b];
-    out[idx] = sum;
+  for (int tile = wave; tile < CT * CT; tile += 4) {
+    const int at = tile / CT, bt = tile - at * CT;
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const double a = (double)PH[(32 * I + 4 * ks + lq) * M + 16 * at + l16];
+      const double b = Ts[(4 * ks + lq) * TP + 16 * bt + l16];
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) out[(16 * at + 4 * v + lq) * M + 16 * bt + l16] = acc[v];
   }
 }
 
