@@ -67,9 +67,15 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
     }
   };
 
-  uint4 stA[NLD], stB[NLD];
+#ifndef SCORE_DEPTH
+#define SCORE_DEPTH 2
+#endif
+  uint4 stA[NLD];
   load_step(0, stA);          // in flight while W^T is staged
+#if SCORE_DEPTH != 1
+  uint4 stB[NLD];
   load_step(1, stB);
+#endif
 
   const uint16_t *wh = wt + (size_t)w.lhead * (W_TERMS * M * D);
   for (int cidx = tid; cidx < W_TERMS * M * 16; cidx += 256) {
@@ -83,17 +89,8 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
   uint16_t *kw = kl[wave];
   bool bad = false;
 
-  auto compute_step = [&](int it, const uint4 (&stg)[NLD]) {
-#if defined(SCORE_ABLATE) && SCORE_ABLATE == 3
-    {   // experiment: global loads only
-      float x = 0.f;
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) x += __uint_as_float(stg[i].x ^ stg[i].w);
-      const int tok = tok_begin + it * STEP + wave * WTOK + (lane & 31);
-      if (g < 2 && tok < tok_end) sp[tok] = x;
-      return;
-    }
-#endif
+  bf16x8 kb[NSUB][4];
+  auto redistribute = [&](const uint4 (&stg)[NLD]) {
     // redistribute through the wave's LDS buffer: rows in, B operands out.  Lanes exchange
     // data here without a workgroup barrier (LDS operations of one wave execute in order), so
     // wave-scope fences keep the compiler from moving the reads and writes across each other.
@@ -102,25 +99,16 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
     for (int i = 0; i < NLD; ++i)
       *reinterpret_cast<uint4 *>(&kw[(ld_row + 4 * i) * WPITCH + ld_chunk * 8]) = stg[i];
     wave_lds_fence();
-    bf16x8 kb[NSUB][4];
 #pragma unroll
     for (int st = 0; st < NSUB; ++st)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
         kb[st][kk] = *reinterpret_cast<const bf16x8 *>(&kw[(16 * st + t16) * WPITCH + 32 * kk + 8 * g]);
-
+  };
+  auto multiply = [&](int it) {
     float sums[NSUB];
 #pragma unroll
     for (int st = 0; st < NSUB; ++st) sums[st] = 0.f;
-#if defined(SCORE_ABLATE) && SCORE_ABLATE == 2
-    {   // experiment: loads + LDS redistribution, no W^T reads, no MFMA
-#pragma unroll
-      for (int st = 0; st < NSUB; ++st)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) { union { bf16x8 v; float f[4]; } u; u.v = kb[st][kk]; sums[st] += u.f[0] + u.f[3]; }
-    }
-    if (false)
-#endif
 #pragma unroll 1
     for (int jb = 0; jb < M / 16; ++jb) {   // kept rolled: unrolling hoists every W^T operand
       f32x4 acc[NSUB];
@@ -156,14 +144,24 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
     }
   };
 
+#if SCORE_DEPTH == 1
+  for (int it = 0; it < nsteps; ++it) {     // one step of loads in flight behind the MFMAs
+    redistribute(stA);
+    load_step(it + 1, stA);
+    multiply(it);
+  }
+#else
   for (int it = 0; it < nsteps; it += 2) {
-    compute_step(it, stA);
+    redistribute(stA);
     load_step(it + 2, stA);
+    multiply(it);
     if (it + 1 < nsteps) {
-      compute_step(it + 1, stB);
+      redistribute(stB);
       load_step(it + 3, stB);
+      multiply(it + 1);
     }
   }
+#endif
   if (__any(bad)) {
     if (lane == 0) atomicOr(&status[s.ghead0 + w.head], COMPACTOR_STATUS_NONFINITE);
   }
