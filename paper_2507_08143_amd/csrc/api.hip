@@ -74,7 +74,8 @@ GramPlan gram_plan(const compactor_params_t *p, const SegTable &T, int cus) {
   if (want < 1) want = 1;
   GramPlan g;
   g.tiles_per_wg = (int)((total + want - 1) / want);
-  if (g.tiles_per_wg < 1) g.tiles_per_wg = 1;
+  // not below 8 tiles (512 rows) a workgroup: every partial costs a 40 KB round trip
+  if (g.tiles_per_wg < 8 && p->gram_wgs <= 0) g.tiles_per_wg = 8;
   g.nwg = (int)((total + g.tiles_per_wg - 1) / g.tiles_per_wg);
   return g;
 }

@@ -86,11 +86,29 @@ __device__ int radix_pass(const float *__restrict__ sp, uint32_t *keys, int n, i
   const int tid = threadIdx.x;
   for (int i = tid; i < 4096; i += SELECT_THREADS) hist[i] = 0;
   __syncthreads();
-#pragma unroll 8
-  for (int i = tid; i < n; i += SELECT_THREADS) {
+  auto tally = [&](uint32_t k) {
+    if (hi_shift >= 32 || (k >> hi_shift) == prefix) atomicAdd(&hist[(k >> shift) & (nb - 1)], 1);
+  };
+  // 16-byte accesses where the head's scores (or the LDS keys) allow it, scalars for the rest
+  const bool vec = FROM_LDS || (reinterpret_cast<uintptr_t>(sp) & 15u) == 0;
+  const int nv = vec ? n >> 2 : 0;
+#pragma unroll 4
+  for (int i = tid; i < nv; i += SELECT_THREADS) {
+    uint4 k4;
+    if (FROM_LDS) {
+      k4 = reinterpret_cast<const uint4 *>(keys)[i];
+    } else {
+      const float4 f = reinterpret_cast<const float4 *>(sp)[i];
+      k4 = make_uint4(score_key(f.x), score_key(f.y), score_key(f.z), score_key(f.w));
+      if (STORE) reinterpret_cast<uint4 *>(keys)[i] = k4;
+    }
+    tally(k4.x); tally(k4.y); tally(k4.z); tally(k4.w);
+  }
+#pragma unroll 4
+  for (int i = 4 * nv + tid; i < n; i += SELECT_THREADS) {
     const uint32_t k = FROM_LDS ? keys[i] : score_key(sp[i]);
     if (STORE) keys[i] = k;
-    if (hi_shift >= 32 || (k >> hi_shift) == prefix) atomicAdd(&hist[(k >> shift) & (nb - 1)], 1);
+    tally(k);
   }
   __syncthreads();
   return find_digit(hist, nb, need, wsum, found);
@@ -110,6 +128,9 @@ __device__ void emit_kept(const float *__restrict__ sp, const uint32_t *keys, in
     if (FROM_LDS && i0 + 3 < n) {
       const uint4 kv = *reinterpret_cast<const uint4 *>(keys + i0);
       key[0] = kv.x; key[1] = kv.y; key[2] = kv.z; key[3] = kv.w;
+    } else if (!FROM_LDS && i0 + 3 < n && (reinterpret_cast<uintptr_t>(sp) & 15u) == 0) {
+      const float4 f = *reinterpret_cast<const float4 *>(sp + i0);
+      key[0] = score_key(f.x); key[1] = score_key(f.y); key[2] = score_key(f.z); key[3] = score_key(f.w);
     } else {
 #pragma unroll
       for (int q = 0; q < 4; ++q)
