@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--gram-wgs", type=int, default=0, help="tuning override (0 = library's choice)")
     ap.add_argument("--score-tokens", type=int, default=0, help="tuning override (0 = library's choice)")
     ap.add_argument("--streams", type=int, default=0, help="stream lanes (0 = library default)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (a dispatch of known size against "
+                         "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--allow-flagged", action="store_true",
                     help="do not fail when a head reports a status flag (kernel experiments only)")
@@ -140,6 +143,13 @@ def main():
 
     def step(p):
         C.compactor_compress(p, reqs, want_scores=False, **bufs)
+
+    if a.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                    # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(a.warmup):
         step(params)

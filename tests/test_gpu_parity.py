@@ -273,3 +273,76 @@ def test_error_codes_reach_python(C):
     with pytest.raises(C.CompactorError) as e:
         C.compactor_compress(params, reqs, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
     assert e.value.code == C.EWORKSPACE
+
+
+# ------------------------------------------------------------------ full sizes (sampled heads)
+def _sample_heads(w, per_request=4, seed=11):
+    rng = np.random.default_rng(seed)
+    heads = []
+    for b in range(len(w.requests)):
+        picks = rng.choice(w.layers * w.kv_heads, size=min(per_request, w.layers * w.kv_heads), replace=False)
+        heads += [(b, int(g) // w.kv_heads, int(g) % w.kv_heads) for g in picks]
+    return heads
+
+
+def _structure_checks(C, w, out):
+    """Properties that hold at any size, on every head (no oracle): status clear, scores in
+    [0, 1] summing to k_s per head, selections valid on the library's own scores."""
+    params, reqs = U.make_call(C, w, DEV)
+    so, ko, kk = C.compactor_layout(params, reqs)
+    assert int(out["status"].max()) == 0
+    LH = w.layers * w.kv_heads
+    for b, r in enumerate(w.requests):
+        s = out["scores"][so[b]:so[b + 1]].view(LH, r.n)
+        assert float(s.min()) >= 0.0 and float(s.max()) <= 1.0 + 1e-5
+        if w.ridge_rel == 0.0 and w.sketch_dim > 0:
+            assert torch.all((s.double().sum(dim=1) - w.sketch_dim).abs() < 2e-2)
+        idx = out["kept_idx"][ko[b]:ko[b + 1]].view(LH, kk[b]).long()
+        assert torch.all(idx[:, 1:] > idx[:, :-1])
+        kept_min = torch.gather(s, 1, idx).min(dim=1).values
+        mask = torch.ones_like(s, dtype=torch.bool).scatter_(1, idx, False)
+        ev_max = torch.where(mask, s, torch.full_like(s, -1.0)).max(dim=1).values
+        assert torch.all(kept_min >= ev_max)
+        # packed rows are bit copies of the selected rows
+        src_k = r.k.reshape(LH, r.n, 128).view(torch.int16)
+        got_k = out["k_packed"][ko[b]:ko[b + 1]].view(LH, kk[b], 128).view(torch.int16)
+        assert torch.equal(got_k, torch.gather(src_k, 1, idx.unsqueeze(-1).expand(-1, -1, 128)))
+        src_v = r.v.reshape(LH, r.n, 128).view(torch.int16)
+        got_v = out["v_packed"][ko[b]:ko[b + 1]].view(LH, kk[b], 128).view(torch.int16)
+        assert torch.equal(got_v, torch.gather(src_v, 1, idx.unsqueeze(-1).expand(-1, -1, 128)))
+
+
+def test_config2_full_size_as_benchmarked(C):
+    _say("config 2 at full size (32 x 8 heads, n = 32768), the launch configuration bench.py times")
+    w = W.config2(device=DEV)
+    st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 6))
+    _say("  %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
+    _structure_checks(C, w, out)
+
+
+def test_config3_full_length(C):
+    _say("config 3 at full length (n = 131072), 4 of 28 layers")
+    w = W.config3(device=DEV, L=4)
+    st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 3))
+    _say("  %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
+    _structure_checks(C, w, out)
+
+
+def test_config5_full_length_sketched_and_exact(C):
+    _say("config 5 at full length (n = 100000), 2 of 64 layers")
+    w = W.config5(device=DEV, L=2)
+    st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 3))
+    _say("  sketched, %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
+    _structure_checks(C, w, out)
+    w.sketch_dim, w.ridge_rel = 0, 1e-4
+    st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 2))
+    _say("  exact ridge 1e-4, %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
+    _structure_checks(C, w, out)
+
+
+def test_config4_ragged_batch_full_lengths(C):
+    _say("config 4: 16 requests with n in [8192, 65536], 2 of 32 layers")
+    w = W.config4(device=DEV, L=2)
+    st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 1))
+    _say("  %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
+    _structure_checks(C, w, out)
