@@ -19,6 +19,14 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per launch measured with rocprofv3 (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
+# scale factors read off a 1 GiB copy kernel): profiles/compress_config2_hbm_traffic.txt.
+# Only the default workload has been profiled; other workloads report null.
+MEASURED_TRAFFIC_BYTES = {
+    ("config2_llama31_8b_n32768", "gather"): 2.592e9,
+    ("config2_llama31_8b_n32768", "gram"): 2.169e9,
+    ("config2_llama31_8b_n32768", "score"): 2.232e9,
+}
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 
@@ -199,7 +207,9 @@ def main():
                    "kept_head_rows": kept, "sketch_dim": w.sketch_dim,
                    "group_mb": a.group_mb},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "algorithmic_bytes": sbytes[dominant],
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant)) if not a.layers else None},
         "path_hbm": {"algorithmic_bytes": total_bytes,
                      "achieved_GB/s": total_bytes / (ms_per_step * 1e-3) / 1e9,
                      "frac_of_8TB/s": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},

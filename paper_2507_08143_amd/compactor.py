@@ -208,7 +208,7 @@ def compactor_default_params(layers: int, kv_heads: int) -> Params:
     p = _Params()
     _lib.compactor_default_params(C.byref(p), layers, kv_heads)
     return Params(p.layers, p.kv_heads, p.sketch_dim, None, p.ridge_rel, p.lambda_blend,
-                  p.group_bytes, p.head_dim)
+                  p.group_bytes, p.head_dim, None, p.gram_wgs, p.score_tokens, p.streams)
 
 
 def compactor_layout(params: Params, reqs: Sequence[Request]):

@@ -1,0 +1,119 @@
+"""Host-side checks of the C boundary that need no GPU: the library loads, exports every
+symbol the header declares, its host helpers agree with the oracle, and argument errors are
+reported before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import compactor_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "compactor.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2507_08143_amd import compactor
+    return compactor
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(compactor_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(B):
+    names = _declared_functions()
+    assert {"compactor_score", "compactor_select", "compactor_compact", "compactor_compress"} <= set(names)
+    for n in names:
+        assert hasattr(B._lib, n), "libcompactor.so does not export %s" % n
+    assert set(B.EXPORTS) == set(names)
+
+
+def test_struct_layouts_match_the_header(B):
+    # sizes the C compiler gives for the two structs of the header (x86-64 ABI)
+    assert C.sizeof(B._Request) == 4 * 8 + 3 * 8 + 4 + 4
+    assert C.sizeof(B._Params) == 4 * 4 + 8 + 4 + 4 + 8 + 4 + 4 + 4 + 4 + 8
+
+
+def test_keep_count_matches_oracle(B):
+    rng = np.random.default_rng(0)
+    for n, r in [(4096, 0.5), (32768, 0.3), (131072, 0.2), (100000, 0.32), (1000, 0.001), (3, 1 / 3),
+                 (1, 0.01), (10, 1.0), (0, 0.5)]:
+        assert B.compactor_keep_count(n, r) == O.keep_count(n, r)
+    for _ in range(2000):
+        n = int(rng.integers(1, 200000))
+        r = float(np.float32(rng.uniform(1e-4, 1.0)))
+        assert B.compactor_keep_count(n, r) == O.keep_count(n, r)
+
+
+def test_calibrated_ratio_matches_oracle(B):
+    for nll, a, b, tau in [(1.0, np.log(2.0), 0.0, 0.5), (2.3, 0.7, 0.2, 0.95), (0.4, 3.0, 1.0, 0.9),
+                           (1.0, 0.0, 0.0, 0.8), (5.0, 2.0, 0.0, 1.0)]:
+        assert abs(B.compactor_calibrated_ratio(nll, a, b, tau) - O.calibrated_ratio(nll, a, b, tau)) < 1e-14
+    assert abs(B.compactor_calibrated_ratio(1.0, np.log(2.0), 0.0, 0.5) - np.log2(1.5)) < 1e-14
+
+
+def _req(n=100, ratio=0.5, ptr=0x1000, stride_t=128):
+    return B_mod._Request(ptr, 0, ptr, 0, 8 * n * stride_t, n * stride_t, stride_t, n, ratio)
+
+
+def test_layout_offsets(B):
+    global B_mod
+    B_mod = B
+    p = B._Params(3, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, None)
+    reqs = (B._Request * 3)(_req(100, 0.5), _req(7, 1.0), _req(1000, 0.25))
+    so, ko, kk = (C.c_int64 * 4)(), (C.c_int64 * 4)(), (C.c_int32 * 3)()
+    assert B._lib.compactor_layout(C.byref(p), reqs, 3, so, ko, kk) == 0
+    assert list(kk) == [50, 7, 250]
+    assert list(so) == [0, 600, 642, 6642]
+    assert list(ko) == [0, 300, 342, 1842]
+
+
+def test_argument_errors_are_reported_on_the_host(B):
+    global B_mod
+    B_mod = B
+    good = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, None)
+    reqs = (B._Request * 1)(_req())
+    nbytes = C.c_size_t(0)
+    assert B._lib.compactor_workspace_size(C.byref(good), reqs, 1, C.byref(nbytes)) == 0
+    assert nbytes.value > 0
+
+    def score(p, r, scores=0x3000, status=0x4000, ws=0x10000, wsb=1 << 40):
+        return B._lib.compactor_score(C.byref(p), r, 1, scores, status, ws, wsb, None)
+
+    bad_dim = B._Params(2, 2, 64, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, None)
+    assert score(bad_dim, reqs) == B.EUNSUPPORTED
+    bad_ks = B._Params(2, 2, 128, 40, 0x2000, 0.0, 0.3, 0, 0, 0, 0, None)
+    assert score(bad_ks, reqs) == B.EUNSUPPORTED
+    no_phi = B._Params(2, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, None)
+    assert score(no_phi, reqs) == B.EINVAL
+    neg_ridge = B._Params(2, 2, 128, 48, 0x2000, -1.0, 0.3, 0, 0, 0, 0, None)
+    assert score(neg_ridge, reqs) == B.EINVAL
+    assert score(good, (B._Request * 1)(_req(ratio=0.0))) == B.EINVAL
+    assert score(good, (B._Request * 1)(_req(ratio=1.5))) == B.EINVAL
+    assert score(good, (B._Request * 1)(_req(n=0))) == B.EINVAL
+    assert score(good, (B._Request * 1)(_req(ptr=0x1004))) == B.EALIGN
+    assert score(good, (B._Request * 1)(_req(stride_t=132))) == B.EALIGN
+    assert score(good, (B._Request * 1)(_req(stride_t=64))) == B.EINVAL
+    assert score(good, reqs, scores=0) == B.EINVAL
+    assert score(good, reqs, ws=0) == B.EWORKSPACE
+    assert score(good, reqs, wsb=16) == B.EWORKSPACE
+    assert score(good, reqs, ws=0x10010) == B.EALIGN
+    assert B._lib.compactor_select(C.byref(good), reqs, 1, 0, 0x3000, 0x4000, 0, 0, None) == B.EINVAL
+    assert B._lib.compactor_compact(C.byref(good), reqs, 1, 0x3000, 0x4000, 0, 0x6000, None) == B.EINVAL
+    assert B._lib.compactor_compress(C.byref(good), reqs, 1, 0, 0x3000, 0x4000, 0x5000, 0x6000, 0,
+                                     0x10000, 1 << 40, None) == B.EINVAL
+    assert B.compactor_error_string(B.EWORKSPACE).startswith("workspace")
+    assert B.compactor_error_string(0) == "ok"
+    assert B.compactor_version().count(".") == 1
+
+
+def test_default_params(B):
+    p = B.compactor_default_params(32, 8)
+    assert (p.layers, p.kv_heads, p.head_dim, p.sketch_dim) == (32, 8, 128, 48)
+    assert abs(p.lambda_blend - 0.3) < 1e-7 and p.ridge_rel == 0.0 and p.streams == 0
