@@ -98,8 +98,8 @@ int score_tokens_for(const compactor_params_t *p, const SegTable &T, int cus) {
 }
 
 struct GroupBytes {
-  size_t partials, g64, wt, scores;
-  size_t total() const { return partials + g64 + wt + scores; }
+  size_t partials, g64, wt, hist1, scores;
+  size_t total() const { return partials + g64 + wt + hist1 + scores; }
 };
 
 GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bool need_scores) {
@@ -112,6 +112,7 @@ GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bo
                         GRAM_PARTIAL_FLOATS * sizeof(float));
   g.g64 = align_up((size_t)T.nheads * D * D * sizeof(double));
   g.wt = align_up((size_t)T.nheads * W_TERMS * m * D * sizeof(uint16_t));
+  g.hist1 = align_up((size_t)T.nheads * HIST1_BINS * sizeof(int));
   g.scores = need_scores ? align_up((size_t)rows * sizeof(float)) : 0;
   return g;
 }
@@ -251,13 +252,19 @@ struct Marks {
     if (rc_ != COMPACTOR_OK) return rc_; \
   } while (0)
 
-// score (+ blend) of one group
+// score (+ blend) of one group.  *hist1_out receives the per-head histogram of the top 12 key
+// bits of the final scores (for the selection), or null when a blend rewrote the scores.
 int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows, float *scores,
-                  int32_t *status, unsigned char *ws, hipStream_t st) {
+                  int32_t *status, unsigned char *ws, hipStream_t st, const int **hist1_out) {
   const GroupBytes gb = group_bytes_needed(p, T, false);
   float *partials = reinterpret_cast<float *>(ws);
   double *g64 = reinterpret_cast<double *>(ws + gb.partials);
   uint16_t *wt = reinterpret_cast<uint16_t *>(ws + gb.partials + gb.g64);
+  int *hist1 = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt);
+  bool blended = false;
+  for (int i = 0; i < T.nseg; ++i) blended |= T.s[i].attn != nullptr;
+  if (blended || hist1_out == nullptr) hist1 = nullptr;
+  if (hist1_out) *hist1_out = hist1;
   const int cus = compute_units();
   const GramPlan gp = gram_plan(p, T, cus);
   const int rpw = gp.tiles_per_wg;
@@ -268,14 +275,14 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   if (p->sketch_dim > 0) {
     hipEvent_t mid = m.ev ? static_cast<hipEvent_t>(m.ev[COMPACTOR_STAGE_REDUCE + 1]) : nullptr;
     HIP_TRY(launch_sketch_solve(T, p->sketch_dim, rpw, partials, p->phi, p->ridge_rel, g64, wt,
-                                status, st, mid));
+                                status, hist1, st, mid));
   } else {
-    HIP_TRY(launch_gram_reduce(T, rpw, partials, g64, st));
+    HIP_TRY(launch_gram_reduce(T, rpw, partials, g64, hist1, st));
     MARK(m, COMPACTOR_STAGE_REDUCE + 1);
     HIP_TRY(launch_solve(T, p->ridge_rel, g64, wt, status, st));
   }
   MARK(m, COMPACTOR_STAGE_SOLVE + 1);
-  HIP_TRY(launch_score(T, p->sketch_dim, score_tokens_for(p, T, cus), wt, scores, status, st));
+  HIP_TRY(launch_score(T, p->sketch_dim, score_tokens_for(p, T, cus), wt, scores, status, hist1, st));
   MARK(m, COMPACTOR_STAGE_SCORE + 1);
   HIP_TRY(launch_blend(T, p->lambda_blend, scores, st));
   MARK(m, COMPACTOR_STAGE_BLEND + 1);
@@ -394,7 +401,7 @@ int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs
   return run_groups(p, reqs, nreq, false, static_cast<unsigned char *>(workspace), slice,
                     static_cast<hipStream_t>(stream),
                     [&](const SegTable &T, long long rows, hipStream_t st, unsigned char *ws) {
-                      return enqueue_score(p, T, rows, scores, status, ws, st);
+                      return enqueue_score(p, T, rows, scores, status, ws, st, nullptr);
                     });
 }
 
@@ -408,7 +415,7 @@ int compactor_select(const compactor_params_t *p, const compactor_request_t *req
   if (!scores || !kept_idx || !kept_cnt) return COMPACTOR_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   return for_each_group(p, reqs, nreq, 1ll << 60, false, [&](const SegTable &T, long long) {
-    HIP_TRY(launch_select(T, scores, kept_idx, kept_cnt, st));
+    HIP_TRY(launch_select(T, scores, nullptr, kept_idx, kept_cnt, st));
     return COMPACTOR_OK;
   });
 }
@@ -452,12 +459,13 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
     float *sc = scores;
     if (local_scores) {
       const GroupBytes gb = group_bytes_needed(p, T, true);
-      sc = reinterpret_cast<float *>(ws + gb.partials + gb.g64 + gb.wt);
+      sc = reinterpret_cast<float *>(ws + gb.partials + gb.g64 + gb.wt + gb.hist1);
     }
-    const int rc2 = enqueue_score(p, T, rows, sc, status, ws, st);
+    const int *hist1 = nullptr;
+    const int rc2 = enqueue_score(p, T, rows, sc, status, ws, st, &hist1);
     if (rc2) return rc2;
     const Marks m{p->stage_events, st};
-    HIP_TRY(launch_select(T, sc, kept_idx, kept_cnt, st));
+    HIP_TRY(launch_select(T, sc, hist1, kept_idx, kept_cnt, st));
     MARK(m, COMPACTOR_STAGE_SELECT + 1);
     HIP_TRY(launch_gather(T, kept_idx, static_cast<uint16_t *>(k_packed),
                           static_cast<uint16_t *>(v_packed), st));

@@ -100,6 +100,16 @@ __device__ __forceinline__ Where locate_block(const SegTable &T, int blk, int pe
   return w;
 }
 
+// Order-preserving 32-bit key of an fp32 score: larger score <=> larger key.  NaN ranks below
+// everything (key 0); -0.0 is folded onto +0.0 first.
+__device__ __forceinline__ uint32_t score_key(float s) {
+  s += 0.0f;
+  if (s != s) return 0u;
+  const uint32_t u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+constexpr int HIST1_BINS = 4096;      // first radix digit of the selection: the top 12 key bits
+
 // Streaming (non-temporal) 16-byte accesses for data that is touched once per pass: they do
 // not allocate in the caches and sustain a higher HBM rate than ordinary loads (measured:
 // about 7.1 TB/s against 6.2 TB/s for a plain slab read on MI355X).
@@ -226,7 +236,7 @@ hipError_t launch_gram(const SegTable &T, int nwg, int tiles_per_wg, float *part
 
 // G64[lhead] = sum over splits of the head's partials, in fp64.
 hipError_t launch_gram_reduce(const SegTable &T, int tiles_per_wg, const float *partials,
-                              double *g64, hipStream_t st);
+                              double *g64, int *hist1, hipStream_t st);
 
 // Exact mode: factor G + rho I and emit W^T (as W_TERMS bf16 planes, [term][128][128] per head)
 // and the status word.
@@ -238,17 +248,20 @@ hipError_t launch_solve(const SegTable &T, float ridge_rel, const double *g64, u
 // two kernels.
 hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, const float *partials,
                                const float *phi, float ridge_rel, double *s_parts, uint16_t *wt,
-                               int32_t *status, hipStream_t st, hipEvent_t mid);
+                               int32_t *status, int *hist1, hipStream_t st, hipEvent_t mid);
 
 // scores[i] = || W^T k_i ||^2
+// Also tallies every head's scores into hist1[lhead][HIST1_BINS] (top 12 key bits), which must
+// be zero on entry; hist1 may be null.
 hipError_t launch_score(const SegTable &T, int ks, int tokens_per_wg, const uint16_t *wt,
-                        float *scores, int32_t *status, hipStream_t st);
+                        float *scores, int32_t *status, int *hist1, hipStream_t st);
 
 // s = z(a) + lambda z(o) in place over the scores of heads whose request has attn
 hipError_t launch_blend(const SegTable &T, float lambda, float *scores, hipStream_t st);
 
-hipError_t launch_select(const SegTable &T, const float *scores, int32_t *kept_idx,
-                         int32_t *kept_cnt, hipStream_t st);
+// hist1: per-head histogram of the top 12 key bits made by the score kernel, or null.
+hipError_t launch_select(const SegTable &T, const float *scores, const int *hist1,
+                         int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st);
 
 hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, uint16_t *k_packed,
                          uint16_t *v_packed, hipStream_t st);

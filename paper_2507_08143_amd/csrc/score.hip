@@ -34,11 +34,13 @@ template <int M>
 __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tokens_per_wg,
                                                        const uint16_t *__restrict__ wt,
                                                        float *__restrict__ scores,
-                                                       int32_t *__restrict__ status) {
+                                                       int32_t *__restrict__ status,
+                                                       int *__restrict__ hist1) {
   constexpr int NSUB = 2, WTOK = 16 * NSUB, STEP = 4 * WTOK;     // tokens per wave / per WG step
   constexpr int NLD = WTOK * 16 / 64;                            // 16-B loads per lane per step
   __shared__ __attribute__((aligned(16))) uint16_t wl[W_TERMS * M * WPITCH];
   __shared__ __attribute__((aligned(16))) uint16_t kl[4][WTOK * WPITCH];
+  __shared__ int hl[HIST1_BINS];     // first radix digit of the selection, tallied on the way out
 
 #ifdef SCORE_REVERSE
   const Where w = locate_block(T, gridDim.x - 1 - blockIdx.x, tokens_per_wg, SCORE_STEP, false);
@@ -77,6 +79,7 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
   load_step(1, stB);
 #endif
 
+  for (int i = tid; i < HIST1_BINS; i += 256) hl[i] = 0;
   const uint16_t *wh = wt + (size_t)w.lhead * (W_TERMS * M * D);
   for (int cidx = tid; cidx < W_TERMS * M * 16; cidx += 256) {
     const int row = cidx >> 4, ch = cidx & 15;
@@ -141,6 +144,7 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
     if (g < 2 && tok < tok_end) {
       sp[tok] = x;
       bad |= !(fabsf(x) <= 3.0e38f);
+      atomicAdd(&hl[score_key(x) >> 20], 1);
     }
   };
 
@@ -165,26 +169,34 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
   if (__any(bad)) {
     if (lane == 0) atomicOr(&status[s.ghead0 + w.head], COMPACTOR_STATUS_NONFINITE);
   }
+  if (hist1 != nullptr) {        // integer adds: the per-head histogram is order independent
+    __syncthreads();
+    int *h1 = hist1 + (size_t)w.lhead * HIST1_BINS;
+    for (int i = tid; i < HIST1_BINS; i += 256) {
+      const int c = hl[i];
+      if (c) atomicAdd(&h1[i], c);
+    }
+  }
 }
 
 template <int M>
 static hipError_t launch_m(const SegTable &T, int tokens_per_wg, const uint16_t *wt,
-                           float *scores, int32_t *status, hipStream_t st) {
+                           float *scores, int32_t *status, int *hist1, hipStream_t st) {
   const long long nb = total_blocks(T, tokens_per_wg, SCORE_STEP, false);
   if (nb <= 0) return hipSuccess;
   hipLaunchKernelGGL((score_kernel<M>), dim3((unsigned)nb), dim3(256), 0, st, T, tokens_per_wg, wt,
-                     scores, status);
+                     scores, status, hist1);
   return hipGetLastError();
 }
 
 hipError_t launch_score(const SegTable &T, int ks, int tokens_per_wg, const uint16_t *wt,
-                        float *scores, int32_t *status, hipStream_t st) {
+                        float *scores, int32_t *status, int *hist1, hipStream_t st) {
   switch (ks) {
-    case 16: return launch_m<16>(T, tokens_per_wg, wt, scores, status, st);
-    case 32: return launch_m<32>(T, tokens_per_wg, wt, scores, status, st);
-    case 48: return launch_m<48>(T, tokens_per_wg, wt, scores, status, st);
-    case 64: return launch_m<64>(T, tokens_per_wg, wt, scores, status, st);
-    case 0:  return launch_m<128>(T, tokens_per_wg, wt, scores, status, st);
+    case 16: return launch_m<16>(T, tokens_per_wg, wt, scores, status, hist1, st);
+    case 32: return launch_m<32>(T, tokens_per_wg, wt, scores, status, hist1, st);
+    case 48: return launch_m<48>(T, tokens_per_wg, wt, scores, status, hist1, st);
+    case 64: return launch_m<64>(T, tokens_per_wg, wt, scores, status, hist1, st);
+    case 0:  return launch_m<128>(T, tokens_per_wg, wt, scores, status, hist1, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -11,15 +11,6 @@
 
 namespace cmp {
 
-// Order-preserving key: larger score <=> larger key.  NaN ranks below everything (key 0);
-// -0.0 is folded onto +0.0 first.
-__device__ __forceinline__ uint32_t score_key(float s) {
-  s += 0.0f;
-  if (s != s) return 0u;
-  const uint32_t u = __float_as_uint(s);
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
 // Exclusive prefix sum of one int per thread over the 1024-thread workgroup; *total gets the
 // workgroup sum.  wsum is 16 ints of LDS.
 __device__ __forceinline__ int block_exclusive_scan(int v, int *wsum, int *total) {
@@ -161,14 +152,58 @@ __device__ void emit_kept(const float *__restrict__ sp, const uint32_t *keys, in
   }
 }
 
+// Second radix pass for heads too long for LDS: histogram of key bits 19..8 among the keys whose
+// top digit is d1, and at the same time those keys are compacted into LDS (wave ballot +
+// one LDS atomic per wave) so that the last pass need not read global memory again.
+__device__ int radix_pass2_collect(const float *__restrict__ sp, uint32_t *keys, int n, uint32_t d1,
+                                   int *need, int *hist, int *wsum, int *found, int *ncand_s,
+                                   int *ncand) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  for (int i = tid; i < 4096; i += SELECT_THREADS) hist[i] = 0;
+  if (tid == 0) *ncand_s = 0;
+  __syncthreads();
+  auto take = [&](uint32_t k, bool valid) {
+    const bool c = valid && (k >> 20) == d1;
+    const unsigned long long m = __ballot(c);
+    if (m) {
+      int base = 0;
+      if (lane == __ffsll((long long)m) - 1) base = atomicAdd(ncand_s, __popcll(m));
+      base = __shfl(base, __ffsll((long long)m) - 1);
+      if (c) {
+        atomicAdd(&hist[(k >> 8) & 0xfff], 1);
+        const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+        if (pos < LDS_KEYS) keys[pos] = k;
+      }
+    }
+  };
+  const bool vec = (reinterpret_cast<uintptr_t>(sp) & 15u) == 0;
+  const int nv = vec ? n >> 2 : 0;
+  for (int i0 = 0; i0 < nv; i0 += SELECT_THREADS) {       // uniform trip count: ballots inside
+    const int i = i0 + tid;
+    float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < nv) f = reinterpret_cast<const float4 *>(sp)[i];
+    take(score_key(f.x), i < nv); take(score_key(f.y), i < nv);
+    take(score_key(f.z), i < nv); take(score_key(f.w), i < nv);
+  }
+  for (int i0 = 4 * nv; i0 < n; i0 += SELECT_THREADS) {
+    const int i = i0 + tid;
+    take(i < n ? score_key(sp[i]) : 0u, i < n);
+  }
+  __syncthreads();
+  *ncand = *ncand_s;
+  return find_digit(hist, 4096, need, wsum, found);
+}
+
 __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T,
                                                                 const float *__restrict__ scores,
+                                                                const int *__restrict__ hist1,
                                                                 int32_t *__restrict__ kept_idx,
                                                                 int32_t *__restrict__ kept_cnt) {
   __shared__ __attribute__((aligned(16))) uint32_t keys[LDS_KEYS];
   __shared__ int hist[4096];
   __shared__ int wsum[SELECT_THREADS / 64];
   __shared__ int found[2];
+  __shared__ int ncand_s;
 
   const Where w = locate_block(T, blockIdx.x, 0, 1, false);
   const Seg &s = T.s[w.seg];
@@ -177,18 +212,35 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T
   int32_t *out = kept_idx + (s.kept_off + (long long)w.head * k);
   const int tid = threadIdx.x;
   if (tid == 0) kept_cnt[s.ghead0 + w.head] = k;
+  const bool small = n <= LDS_KEYS;      // one read of the scores; everything else out of LDS
 
   // threshold key = the k-th largest, by three radix passes (12 + 12 + 8 bits)
   int need = k;
-  if (n <= LDS_KEYS) {       // one read of the scores; everything else runs out of LDS
-    const uint32_t d1 = radix_pass<false, true>(sp, keys, n, 20, 12, 32, 0u, &need, hist, wsum, found);
-    const uint32_t d2 = radix_pass<true, false>(sp, keys, n, 8, 12, 20, d1, &need, hist, wsum, found);
-    const uint32_t d3 = radix_pass<true, false>(sp, keys, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
+  uint32_t d1, d2, d3;
+  if (hist1 != nullptr) {                // first digit already tallied by the score kernel
+    const int *h1 = hist1 + (size_t)w.lhead * HIST1_BINS;
+    for (int i = tid; i < HIST1_BINS; i += SELECT_THREADS) hist[i] = h1[i];
+    __syncthreads();
+    d1 = find_digit(hist, HIST1_BINS, &need, wsum, found);
+  } else if (small) {
+    d1 = radix_pass<false, true>(sp, keys, n, 20, 12, 32, 0u, &need, hist, wsum, found);
+  } else {
+    d1 = radix_pass<false, false>(sp, keys, n, 20, 12, 32, 0u, &need, hist, wsum, found);
+  }
+  if (small) {
+    if (hist1 != nullptr)
+      d2 = radix_pass<false, true>(sp, keys, n, 8, 12, 20, d1, &need, hist, wsum, found);
+    else
+      d2 = radix_pass<true, false>(sp, keys, n, 8, 12, 20, d1, &need, hist, wsum, found);
+    d3 = radix_pass<true, false>(sp, keys, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
     emit_kept<true>(sp, keys, n, k, (d1 << 20) | (d2 << 8) | d3, need, out, wsum);
   } else {
-    const uint32_t d1 = radix_pass<false, false>(sp, keys, n, 20, 12, 32, 0u, &need, hist, wsum, found);
-    const uint32_t d2 = radix_pass<false, false>(sp, keys, n, 8, 12, 20, d1, &need, hist, wsum, found);
-    const uint32_t d3 = radix_pass<false, false>(sp, keys, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
+    int ncand;
+    d2 = radix_pass2_collect(sp, keys, n, d1, &need, hist, wsum, found, &ncand_s, &ncand);
+    if (ncand <= LDS_KEYS)               // the candidates (top digit d1) sit in LDS
+      d3 = radix_pass<true, false>(sp, keys, ncand, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
+    else
+      d3 = radix_pass<false, false>(sp, keys, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
     emit_kept<false>(sp, keys, n, k, (d1 << 20) | (d2 << 8) | d3, need, out, wsum);
   }
 }
@@ -234,11 +286,11 @@ __global__ __launch_bounds__(SELECT_THREADS) void blend_kernel(const SegTable T,
     o[i] = (float)((a[i] - ma) * ia + (o[i] - mo) * io);
 }
 
-hipError_t launch_select(const SegTable &T, const float *scores, int32_t *kept_idx,
-                         int32_t *kept_cnt, hipStream_t st) {
+hipError_t launch_select(const SegTable &T, const float *scores, const int *hist1,
+                         int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st) {
   if (T.nheads <= 0) return hipSuccess;
   hipLaunchKernelGGL(select_kernel, dim3((unsigned)T.nheads), dim3(SELECT_THREADS), 0, st, T,
-                     scores, kept_idx, kept_cnt);
+                     scores, hist1, kept_idx, kept_cnt);
   return hipGetLastError();
 }
 
