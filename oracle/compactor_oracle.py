@@ -41,6 +41,9 @@ __all__ = [
     "approx_leverage_ridge",
     "approx_leverage_qr",
     "approx_leverage_eig",
+    "attention_scores_raw",
+    "mean_pool",
+    "attention_scores",
     "zscore",
     "blend_scores",
     "keep_count",
@@ -180,6 +183,61 @@ def approx_leverage_eig(K: np.ndarray, Phi: np.ndarray, eps: float = 1e-6) -> np
     lam = np.maximum(lam, eps)
     U = (K_hat @ V) / np.sqrt(lam)
     return np.sum(U * U, axis=1)
+
+
+# --------------------------------------------------------------------------
+# attention-based scores  (Sec. 3.2, "Attention-Based Scoring")
+# --------------------------------------------------------------------------
+def attention_scores_raw(Q: np.ndarray, K: np.ndarray, chunk: int = 256,
+                         scale: float | None = None) -> np.ndarray:
+    """a = concat_i 1^T softmax(Q[i] K[i]^T): non-causal attention inside blocks of `chunk`
+    consecutive positions, summed over the block's queries (column sums), for one query head.
+
+    Q[i], K[i] are rows (i-1)C+1 .. iC; the last block is shorter when C does not divide N.
+    The softmax normalises each query's row over the keys of its own block.  The paper's
+    formula shows no logit scale; `scale` (default 1/sqrt(d), the model's own attention scale)
+    multiplies Q K^T before the softmax.
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    n, d = K.shape
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    a = np.zeros(n)
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        S = (Q[lo:hi] @ K[lo:hi].T) * scale
+        S = S - S.max(axis=1, keepdims=True)
+        P = np.exp(S)
+        P = P / P.sum(axis=1, keepdims=True)
+        a[lo:hi] = P.sum(axis=0)
+    return a
+
+
+def mean_pool(a: np.ndarray, width: int) -> np.ndarray:
+    """Mean pooling along the sequence as SnapKV applies it: window `width` (odd), stride 1,
+    zero padding of width//2 on both sides, every window divided by `width`."""
+    a = np.asarray(a, dtype=np.float64)
+    if width <= 1:
+        return a.copy()
+    h = width // 2
+    padded = np.concatenate([np.zeros(h), a, np.zeros(h)])
+    out = np.zeros_like(a)
+    for u in range(width):
+        out += padded[u:u + a.shape[0]]
+    return out / width
+
+
+def attention_scores(Q_heads, K: np.ndarray, chunk: int = 256, pool: int = 7,
+                     scale: float | None = None) -> np.ndarray:
+    """Attention score vector a of one kv-head: the raw block-wise column sums averaged over
+    the query heads that share the kv-head (grouped-query attention), then mean-pooled.
+
+    The paper leaves the reduction over a group's query heads and the pooling width open;
+    mean over the group and width 7 are this build's readings.
+    """
+    raw = np.mean([attention_scores_raw(Q, K, chunk, scale) for Q in Q_heads], axis=0)
+    return mean_pool(raw, pool)
 
 
 # --------------------------------------------------------------------------

@@ -331,3 +331,69 @@ def test_compress_head_end_to_end_small():
     s2, kept2, _, _ = O.compress_head(K, Kb, Vb, 0.25, None)
     np.testing.assert_allclose(s2, O.leverage_hat_diagonal(K), rtol=1e-7)
     assert kept2.tolist() == _brute_topk(s2, 75)
+
+
+# ---------------------------------------------------------------- attention scores (Sec. 3.2)
+def _brute_attention(Q, K, chunk, scale):
+    n = K.shape[0]
+    a = [0.0] * n
+    for i in range(n):                       # query i attends inside its own block only
+        lo = (i // chunk) * chunk
+        hi = min(n, lo + chunk)
+        logits = [scale * float(np.dot(Q[i], K[j])) for j in range(lo, hi)]
+        m = max(logits)
+        w = [math.exp(x - m) for x in logits]
+        z = sum(w)
+        for t, j in enumerate(range(lo, hi)):
+            a[j] += w[t] / z
+    return np.array(a)
+
+
+def test_attention_scores_raw_against_brute_force_and_invariants():
+    r = _rng(80)
+    n, d, C = 37, 8, 16                       # ragged last block of 5
+    Q, K = r.standard_normal((n, d)) * 2, r.standard_normal((n, d)) * 2
+    a = O.attention_scores_raw(Q, K, C, scale=0.5)
+    np.testing.assert_allclose(a, _brute_attention(Q, K, C, 0.5), atol=1e-12)
+    # every query distributes one unit of attention inside its block
+    assert abs(a[:16].sum() - 16) < 1e-10 and abs(a[16:32].sum() - 16) < 1e-10 and abs(a[32:].sum() - 5) < 1e-10
+    # blocks are independent: changing block 2's keys leaves block 1's scores alone
+    K2 = K.copy(); K2[16:32] += 3.0
+    assert np.array_equal(O.attention_scores_raw(Q, K2, C, 0.5)[:16], a[:16])
+    # the order of the queries inside a block does not matter (column sums)
+    p = np.arange(n); p[:16] = r.permutation(16)
+    np.testing.assert_allclose(O.attention_scores_raw(Q[p], K, C, 0.5), a, atol=1e-12)
+    # one block covering everything is plain non-causal attention: 1^T softmax(Q K^T)
+    S = Q @ K.T * 0.5
+    P = np.exp(S - S.max(axis=1, keepdims=True)); P /= P.sum(axis=1, keepdims=True)
+    np.testing.assert_allclose(O.attention_scores_raw(Q, K, 64, 0.5), P.sum(axis=0), atol=1e-12)
+    # default scale is 1/sqrt(d)
+    np.testing.assert_allclose(O.attention_scores_raw(Q, K, C), O.attention_scores_raw(Q, K, C, 1 / math.sqrt(d)), atol=0)
+
+
+def test_attention_scores_closed_forms():
+    # zero queries: uniform attention, every key of a full block gets rows/cols = 1
+    K = _rng(81).standard_normal((8, 4))
+    np.testing.assert_allclose(O.attention_scores_raw(np.zeros((8, 4)), K, 4), np.ones(8), atol=1e-15)
+    # two tokens, logits [[0, ln 3], [0, 0]]: rows (1/4, 3/4) and (1/2, 1/2) -> sums (3/4, 5/4)
+    Q = np.array([[1.0], [0.0]]); Kk = np.array([[0.0], [math.log(3.0)]])
+    np.testing.assert_allclose(O.attention_scores_raw(Q, Kk, 2, scale=1.0), [0.75, 1.25], atol=1e-15)
+    # a dominant key takes everything in its block
+    Qb = np.ones((4, 1)); Kb = np.array([[0.0], [100.0], [0.0], [0.0]])
+    np.testing.assert_allclose(O.attention_scores_raw(Qb, Kb, 4, scale=1.0), [0, 4, 0, 0], atol=1e-12)
+
+
+def test_mean_pool_and_group_average():
+    np.testing.assert_allclose(O.mean_pool(np.ones(6), 3), [2 / 3, 1, 1, 1, 1, 2 / 3], atol=1e-15)
+    np.testing.assert_allclose(O.mean_pool(np.array([0, 0, 7.0, 0, 0, 0]), 7), [1, 1, 1, 1, 1, 1], atol=1e-15)
+    x = _rng(82).standard_normal(20)
+    assert np.array_equal(O.mean_pool(x, 1), x)
+    assert abs(O.mean_pool(x, 5)[10] - x[8:13].mean()) < 1e-15
+    # linear: pooling commutes with the average over a group's query heads
+    r = _rng(83)
+    K = r.standard_normal((40, 6)); Qs = [r.standard_normal((40, 6)) for _ in range(3)]
+    a = O.attention_scores(Qs, K, chunk=16, pool=5)
+    want = O.mean_pool(np.mean([O.attention_scores_raw(Q, K, 16) for Q in Qs], axis=0), 5)
+    np.testing.assert_allclose(a, want, atol=1e-15)
+    # a single query head and no pooling is the raw vector
+    np.testing.assert_allclose(O.attention_scores([Qs[0]], K, 16, pool=1), O.attention_scores_raw(Qs[0], K, 16), atol=0)
