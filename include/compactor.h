@@ -182,6 +182,45 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
                        void *k_packed, void *v_packed, int32_t *status,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- attention-based scores (Sec. 3.2, "Attention-Based Scoring") ------------------------- */
+
+/* One context: the queries and keys its attention scores are computed from. */
+typedef struct compactor_attn_request {
+  const void *q;          /* device, bf16 [L, Hq, n, d]: queries (as the model's attention sees
+                             them, i.e. position-encoded), d contiguous */
+  const void *k;          /* device, bf16 [L, H, n, d]: keys (likewise) */
+  int64_t q_stride_l, q_stride_h, q_stride_t;   /* element strides, multiples of 8 */
+  int64_t k_stride_l, k_stride_h, k_stride_t;
+  int32_t n;              /* tokens */
+} compactor_attn_request_t;
+
+typedef struct compactor_attn_params {
+  int32_t layers;         /* L */
+  int32_t kv_heads;       /* H */
+  int32_t q_heads;        /* Hq, a multiple of H: query heads h*G .. h*G+G-1 share kv head h */
+  int32_t head_dim;       /* 128 */
+  int32_t chunk;          /* block size C of Sec. 3.2; 256 (the paper's value) is supported */
+  int32_t pool;           /* mean-pooling window along the sequence: odd, 1..63; 1 = none */
+  float   scale;          /* logit scale; 0 = 1/sqrt(head_dim) */
+} compactor_attn_params_t;
+
+/* Bytes of device workspace compactor_attention_scores needs (the unpooled sums). host. */
+int compactor_attention_workspace_size(const compactor_attn_params_t *p,
+                                       const compactor_attn_request_t *reqs, int32_t nreq,
+                                       size_t *bytes);
+
+/* a = concat_i 1^T softmax(scale * Q[i] K[i]^T) over blocks i of `chunk` consecutive positions
+ * (non-causal inside a block; the last block may be shorter), averaged over the query heads of
+ * each kv head, then mean-pooled with window `pool` (stride 1, zero padding, divided by pool,
+ * as SnapKV pools its scores).
+ *   attn  device, fp32 [sum_b L*H*n_b], request b at the prefix sum of L*H*n_b (the layout of
+ *         the scores buffer): pass attn + offset_b as compactor_request_t.attn.
+ * The group average and the pooling width are this library's readings of passages the paper
+ * leaves open. */
+int compactor_attention_scores(const compactor_attn_params_t *p,
+                               const compactor_attn_request_t *reqs, int32_t nreq, float *attn,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
 /* Context-calibrated retention (Sec. 3.4): the smallest r in (0,1] with
  * f(r) = (exp(r b - b) - exp(-b)) / (1 - exp(-b)) >= tau, b = alpha*nll + beta, i.e.
  * r* = 1 + ln(tau (1 - e^-b) + e^-b) / b (r* = tau in the limit b -> 0). host. */

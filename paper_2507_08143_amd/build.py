@@ -19,7 +19,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libcompactor.so")
-SOURCES = ["api.hip", "gram.hip", "solve.hip", "score.hip", "select.hip", "gather.hip"]
+SOURCES = ["api.hip", "gram.hip", "solve.hip", "score.hip", "select.hip", "gather.hip", "attention.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -43,7 +43,24 @@ class _Params(C.Structure):
                 ("stage_events", C.c_void_p)]
 
 
+class _AttnRequest(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("k", C.c_void_p),
+                ("q_stride_l", C.c_int64), ("q_stride_h", C.c_int64), ("q_stride_t", C.c_int64),
+                ("k_stride_l", C.c_int64), ("k_stride_h", C.c_int64), ("k_stride_t", C.c_int64),
+                ("n", C.c_int32)]
+
+
+class _AttnParams(C.Structure):
+    _fields_ = [("layers", C.c_int32), ("kv_heads", C.c_int32), ("q_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("chunk", C.c_int32), ("pool", C.c_int32),
+                ("scale", C.c_float)]
+
+
 _PP, _RP = C.POINTER(_Params), C.POINTER(_Request)
+_APP, _ARP = C.POINTER(_AttnParams), C.POINTER(_AttnRequest)
+_lib.compactor_attention_workspace_size.argtypes = [_APP, _ARP, C.c_int32, C.POINTER(C.c_size_t)]
+_lib.compactor_attention_scores.argtypes = [_APP, _ARP, C.c_int32, C.c_void_p, C.c_void_p,
+                                            C.c_size_t, C.c_void_p]
 _lib.compactor_default_params.argtypes = [_PP, C.c_int32, C.c_int32]
 _lib.compactor_default_params.restype = None
 _lib.compactor_keep_count.argtypes = [C.c_int32, C.c_float]
@@ -69,7 +86,8 @@ _lib.compactor_version.restype = C.c_char_p
 EXPORTS = ["compactor_default_params", "compactor_keep_count", "compactor_layout",
            "compactor_workspace_size", "compactor_score", "compactor_select",
            "compactor_compact", "compactor_compress", "compactor_calibrated_ratio",
-           "compactor_error_string", "compactor_version"]
+           "compactor_error_string", "compactor_version",
+           "compactor_attention_workspace_size", "compactor_attention_scores"]
 
 
 STAGES = ["gram", "reduce", "solve", "score", "blend", "select", "gather"]
@@ -305,3 +323,55 @@ def compactor_compress(params: Params, reqs: Sequence[Request], want_scores: boo
                                    workspace.numel(), _stream(stream)))
     return {"scores": scores, "kept_idx": kept_idx, "kept_cnt": kept_cnt, "k_packed": k_packed,
             "v_packed": v_packed, "status": status, "workspace": workspace}
+
+
+@dataclass
+class AttnParams:
+    layers: int
+    kv_heads: int
+    q_heads: int
+    head_dim: int = 128
+    chunk: int = 256
+    pool: int = 7
+    scale: float = 0.0          # 0 = 1/sqrt(head_dim)
+
+    def c(self) -> _AttnParams:
+        return _AttnParams(self.layers, self.kv_heads, self.q_heads, self.head_dim, self.chunk,
+                           self.pool, self.scale)
+
+
+@dataclass
+class AttnRequest:
+    q: torch.Tensor             # bf16 [L, Hq, n, d]
+    k: torch.Tensor             # bf16 [L, H, n, d]
+
+    def c(self) -> _AttnRequest:
+        q, k = self.q, self.k
+        assert q.dtype == torch.bfloat16 and k.dtype == torch.bfloat16
+        assert q.dim() == 4 and k.dim() == 4 and q.stride(3) == 1 and k.stride(3) == 1
+        assert q.shape[2] == k.shape[2]
+        return _AttnRequest(q.data_ptr(), k.data_ptr(), q.stride(0), q.stride(1), q.stride(2),
+                            k.stride(0), k.stride(1), k.stride(2), k.shape[2])
+
+
+def compactor_attention_workspace_size(params: AttnParams, reqs: Sequence[AttnRequest]) -> int:
+    arr = (_AttnRequest * len(reqs))(*[r.c() for r in reqs])
+    out = C.c_size_t(0)
+    _check(_lib.compactor_attention_workspace_size(C.byref(params.c()), arr, len(reqs), C.byref(out)))
+    return int(out.value)
+
+
+def compactor_attention_scores(params: AttnParams, reqs: Sequence[AttnRequest], attn=None,
+                               workspace=None, stream=None):
+    """-> attn fp32 [sum_b L*H*n_b]; request b starts at the prefix sum of L*H*n_b."""
+    dev = reqs[0].k.device
+    total = sum(params.layers * params.kv_heads * r.k.shape[2] for r in reqs)
+    if attn is None:
+        attn = torch.empty(total, dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(256, compactor_attention_workspace_size(params, reqs)),
+                                dtype=torch.uint8, device=dev)
+    arr = (_AttnRequest * len(reqs))(*[r.c() for r in reqs])
+    _check(_lib.compactor_attention_scores(C.byref(params.c()), arr, len(reqs), _ptr(attn),
+                                           _ptr(workspace), workspace.numel(), _stream(stream)))
+    return attn

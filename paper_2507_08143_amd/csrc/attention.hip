@@ -1,0 +1,341 @@
+// Attention-based scores (paper Sec. 3.2, "Attention-Based Scoring"):
+//     a = concat_i 1^T softmax(Q[i] K[i]^T)
+// non-causal attention inside blocks of C = 256 consecutive positions, summed over the block's
+// queries, averaged over the query heads that share a kv-head, then mean-pooled along the
+// sequence.  The result is the `attn` input of the scoring entry points (Eq. "scoring").
+//
+// One workgroup per (kv-head, block).  The transposed product S^T = K Q^T is formed so that the
+// softmax statistics of a query are per-lane quantities: wave w keeps its 64 keys as MFMA A
+// operands in registers for the whole block; the query rows (64 at a time, every query head of
+// the group in turn) pass through LDS as B operands.  Both operands are plain 16-byte pieces of
+// rows (the contraction runs over channels), so nothing is transposed.  The four waves each
+// see a quarter of a query's keys; they exchange (max, sum) once per step through LDS and
+// merge them as in an online softmax.  The column sums accumulate in 16 registers per lane and
+// are reduced across lanes once per block.
+#include <math.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace cmp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int ATT_C = 256;          // block (chunk) size C of the paper
+constexpr int ATT_QB = 64;          // queries per step
+constexpr int QPITCH = 136;         // bf16 per LDS row of staged queries (272 B)
+constexpr int ATT_MAX_SEG = 16;
+
+struct AttnSeg {
+  const uint16_t *q, *k;
+  long long q_stride_l, q_stride_h, q_stride_t;
+  long long k_stride_l, k_stride_h, k_stride_t;
+  long long out_off;      // float offset of the request's head (0,0) in the output
+  int n;
+  int head_begin, head_count;   // kv heads (l*H+h) of the request covered by this launch
+  int H, G;               // kv heads per layer, query heads per kv head
+};
+struct AttnTable {
+  AttnSeg s[ATT_MAX_SEG];
+  int nseg;
+  float scale;
+  int pool;
+};
+
+__global__ __launch_bounds__(256, 2) void attn_colsum_kernel(const AttnTable T,
+                                                             float *__restrict__ raw) {
+  __shared__ __attribute__((aligned(16))) uint16_t ql[2][ATT_QB * QPITCH];
+  __shared__ float st_m[2][4][ATT_QB];
+  __shared__ float st_l[2][4][ATT_QB];
+
+  // locate (segment, kv head, block)
+  int seg = 0, head = 0, blk = 0;
+  {
+    int base = 0;
+    for (int i = 0; i < T.nseg; ++i) {
+      const int bph = (T.s[i].n + ATT_C - 1) / ATT_C;
+      const int nb = bph * T.s[i].head_count;
+      if ((int)blockIdx.x < base + nb || i == T.nseg - 1) {
+        const int local = blockIdx.x - base;
+        seg = i;
+        head = T.s[i].head_begin + local / bph;
+        blk = local % bph;
+        break;
+      }
+      base += nb;
+    }
+  }
+  const AttnSeg &s = T.s[seg];
+  const int n = s.n, c0 = blk * ATT_C;
+  const int layer = head / s.H, kvh = head - layer * s.H;
+  const uint16_t *kp = s.k + (long long)layer * s.k_stride_l + (long long)kvh * s.k_stride_h;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int l16 = lane & 15, lq = lane >> 4;
+
+  // this wave's 64 keys as A operands: tile kt, lane (key l16, channel group lq)
+  bf16x8 ka[4][4];
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt) {
+    const int key = c0 + 64 * wave + 16 * kt + l16;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      union { uint4 u; bf16x8 v; } t;
+      t.u = make_uint4(0, 0, 0, 0);
+      if (key < n) t.u = *reinterpret_cast<const uint4 *>(kp + (long long)key * s.k_stride_t + 32 * kk + 8 * lq);
+      ka[kt][kk] = t.v;
+    }
+  }
+  // keys this lane sees in the MFMA result: tile kt, register v -> key c0 + 64*wave + 16*kt + 4*lq + v
+  const int key_base = c0 + 64 * wave + 4 * lq;
+
+  float pacc[4][4];
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) pacc[kt][v] = 0.f;
+
+  const int nsteps = s.G * (ATT_C / ATT_QB);          // (query head of the group, 64-query block)
+  const int ld_row = tid >> 4, ld_chunk = tid & 15;   // loader: 16 lanes per 256-B query row
+  auto q_rows = [&](int step) -> const uint16_t * {
+    const int qh = step / (ATT_C / ATT_QB);
+    return s.q + (long long)layer * s.q_stride_l + (long long)(kvh * s.G + qh) * s.q_stride_h;
+  };
+  auto load_q = [&](int step, uint4 (&stg)[4]) {
+    const uint16_t *qp = q_rows(step);
+    const int r0 = c0 + (step % (ATT_C / ATT_QB)) * ATT_QB;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = r0 + ld_row + 16 * i;
+      stg[i] = make_uint4(0, 0, 0, 0);
+      if (step < nsteps && row < n)
+        stg[i] = load_stream16(qp + (long long)row * s.q_stride_t + ld_chunk * 8);
+    }
+  };
+  auto store_q = [&](int buf, const uint4 (&stg)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<uint4 *>(&ql[buf][(ld_row + 16 * i) * QPITCH + ld_chunk * 8]) = stg[i];
+  };
+
+  uint4 stg[4];
+  load_q(0, stg);
+  store_q(0, stg);
+  __syncthreads();
+
+  const float scale = T.scale;
+  for (int step = 0; step < nsteps; ++step) {
+    const int buf = step & 1;
+    load_q(step + 1, stg);                              // in flight during the MFMAs
+
+    // S^T tiles: acc[slice][kt] = keys (tile kt) x queries (slice), contraction over channels
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl) {
+      bf16x8 qb[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        qb[kk] = *reinterpret_cast<const bf16x8 *>(&ql[buf][(16 * sl + l16) * QPITCH + 32 * kk + 8 * lq]);
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt) {
+        acc[sl][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          acc[sl][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt][kk], qb[kk], acc[sl][kt], 0, 0, 0);
+      }
+    }
+
+    // local softmax statistics of every query over this wave's 64 keys
+    const int q0 = c0 + (step % (ATT_C / ATT_QB)) * ATT_QB;
+    float mloc[4], lloc[4];
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl) {
+      float m = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const bool valid = key_base + 16 * kt + v < n;
+          const float x = valid ? acc[sl][kt][v] * scale : -INFINITY;
+          acc[sl][kt][v] = x;
+          m = fmaxf(m, x);
+        }
+      m = fmaxf(m, __shfl_xor(m, 16));
+      m = fmaxf(m, __shfl_xor(m, 32));
+      const float ms = m == -INFINITY ? 0.f : m;        // a wave whose keys are all past the end
+      float l = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float e = __expf(acc[sl][kt][v] - ms);
+          acc[sl][kt][v] = e;
+          l += e;
+        }
+      l += __shfl_xor(l, 16);
+      l += __shfl_xor(l, 32);
+      mloc[sl] = ms;
+      lloc[sl] = l;
+      if (lq == 0) {
+        st_m[buf][wave][16 * sl + l16] = m == -INFINITY ? -INFINITY : ms;
+        st_l[buf][wave][16 * sl + l16] = l;
+      }
+    }
+
+    store_q(buf ^ 1, stg);
+    __syncthreads();        // statistics of this step and the next step's queries are in LDS
+
+    // merge the four waves' statistics and add this step's probabilities to the column sums
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl) {
+      const int qi = 16 * sl + l16;
+      float m = -INFINITY;
+#pragma unroll
+      for (int w2 = 0; w2 < 4; ++w2) m = fmaxf(m, st_m[buf][w2][qi]);
+      float l = 0.f;
+#pragma unroll
+      for (int w2 = 0; w2 < 4; ++w2) {
+        const float mw = st_m[buf][w2][qi];
+        l += mw == -INFINITY ? 0.f : st_l[buf][w2][qi] * __expf(mw - m);
+      }
+      const bool qvalid = q0 + qi < n;
+      const float f = qvalid ? __expf(mloc[sl] - m) / l : 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) pacc[kt][v] += acc[sl][kt][v] * f;
+    }
+  }
+
+  // column sums: add over the 16 query lanes of each quarter, average over the query heads
+  const float inv_g = 1.f / (float)s.G;
+  float *out = raw + s.out_off + (long long)head * n;
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      float x = pacc[kt][v];
+      x += __shfl_xor(x, 1);
+      x += __shfl_xor(x, 2);
+      x += __shfl_xor(x, 4);
+      x += __shfl_xor(x, 8);
+      const int key = key_base + 16 * kt + v;
+      if (l16 == 0 && key < n) out[key] = x * inv_g;
+    }
+}
+
+// Mean pooling along the sequence: window `pool` (odd), zero padding, divided by `pool`.
+__global__ __launch_bounds__(256) void attn_pool_kernel(const AttnTable T,
+                                                        const float *__restrict__ raw,
+                                                        float *__restrict__ attn) {
+  int seg = 0, head = 0, blk = 0;
+  {
+    int base = 0;
+    for (int i = 0; i < T.nseg; ++i) {
+      const int bph = (T.s[i].n + 1023) / 1024;
+      const int nb = bph * T.s[i].head_count;
+      if ((int)blockIdx.x < base + nb || i == T.nseg - 1) {
+        const int local = blockIdx.x - base;
+        seg = i;
+        head = T.s[i].head_begin + local / bph;
+        blk = local % bph;
+        break;
+      }
+      base += nb;
+    }
+  }
+  const AttnSeg &s = T.s[seg];
+  const int n = s.n, h = T.pool / 2;
+  const float *src = raw + s.out_off + (long long)head * n;
+  float *dst = attn + s.out_off + (long long)head * n;
+  const float inv = 1.f / (float)T.pool;
+  for (int t = blk * 1024 + threadIdx.x; t < min(n, (blk + 1) * 1024); t += 256) {
+    float acc = 0.f;
+    for (int u = -h; u <= h; ++u) {
+      const int j = t + u;
+      if (j >= 0 && j < n) acc += src[j];
+    }
+    dst[t] = acc * inv;
+  }
+}
+
+}  // namespace cmp
+
+using namespace cmp;
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+int compactor_attention_workspace_size(const compactor_attn_params_t *p,
+                                       const compactor_attn_request_t *reqs, int32_t nreq,
+                                       size_t *bytes) {
+  if (!p || !reqs || !bytes || nreq < 1) return COMPACTOR_EINVAL;
+  if (p->layers < 1 || p->kv_heads < 1) return COMPACTOR_EINVAL;
+  size_t tot = 0;
+  for (int b = 0; b < nreq; ++b) {
+    if (reqs[b].n < 1) return COMPACTOR_EINVAL;
+    tot += (size_t)p->layers * p->kv_heads * reqs[b].n;
+  }
+  *bytes = (tot * sizeof(float) + 255) / 256 * 256;
+  return COMPACTOR_OK;
+}
+
+int compactor_attention_scores(const compactor_attn_params_t *p,
+                               const compactor_attn_request_t *reqs, int32_t nreq, float *attn,
+                               void *workspace, size_t workspace_bytes, void *stream) {
+  if (!p || !reqs || nreq < 1 || !attn) return COMPACTOR_EINVAL;
+  if (p->layers < 1 || p->kv_heads < 1 || p->q_heads < p->kv_heads || p->q_heads % p->kv_heads)
+    return COMPACTOR_EINVAL;
+  if (p->head_dim != D || p->chunk != ATT_C) return COMPACTOR_EUNSUPPORTED;
+  if (p->pool < 1 || p->pool > 63 || !(p->pool & 1)) return COMPACTOR_EINVAL;
+  if (!(p->scale >= 0.f) || !isfinite(p->scale)) return COMPACTOR_EINVAL;
+  for (int b = 0; b < nreq; ++b) {
+    const compactor_attn_request_t &r = reqs[b];
+    if (r.n < 1 || !r.q || !r.k) return COMPACTOR_EINVAL;
+    if (r.q_stride_t < D || r.k_stride_t < D) return COMPACTOR_EINVAL;
+    if ((r.q_stride_t | r.q_stride_h | r.q_stride_l | r.k_stride_t | r.k_stride_h | r.k_stride_l) & 7)
+      return COMPACTOR_EALIGN;
+    if ((reinterpret_cast<uintptr_t>(r.q) | reinterpret_cast<uintptr_t>(r.k)) & 15u) return COMPACTOR_EALIGN;
+  }
+  size_t need;
+  int rc = compactor_attention_workspace_size(p, reqs, nreq, &need);
+  if (rc) return rc;
+  if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return COMPACTOR_EALIGN;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float *raw = static_cast<float *>(workspace);
+  const int LH = p->layers * p->kv_heads;
+  long long off = 0;
+  for (int b0 = 0; b0 < nreq; b0 += ATT_MAX_SEG) {
+    AttnTable T;
+    memset(&T, 0, sizeof(T));
+    T.scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)D);
+    T.pool = p->pool;
+    long long nb_col = 0, nb_pool = 0;
+    for (int b = b0; b < nreq && b < b0 + ATT_MAX_SEG; ++b) {
+      const compactor_attn_request_t &r = reqs[b];
+      AttnSeg &s = T.s[T.nseg++];
+      s.q = static_cast<const uint16_t *>(r.q);
+      s.k = static_cast<const uint16_t *>(r.k);
+      s.q_stride_l = r.q_stride_l; s.q_stride_h = r.q_stride_h; s.q_stride_t = r.q_stride_t;
+      s.k_stride_l = r.k_stride_l; s.k_stride_h = r.k_stride_h; s.k_stride_t = r.k_stride_t;
+      s.out_off = off;
+      s.n = r.n;
+      s.head_begin = 0; s.head_count = LH;
+      s.H = p->kv_heads; s.G = p->q_heads / p->kv_heads;
+      off += (long long)LH * r.n;
+      nb_col += (long long)LH * ((r.n + ATT_C - 1) / ATT_C);
+      nb_pool += (long long)LH * ((r.n + 1023) / 1024);
+    }
+    if (nb_col > 0x7fffffffll) return COMPACTOR_EINVAL;
+    hipLaunchKernelGGL(attn_colsum_kernel, dim3((unsigned)nb_col), dim3(256), 0, st, T, raw);
+    if (hipGetLastError() != hipSuccess) return COMPACTOR_EHIP;
+    hipLaunchKernelGGL(attn_pool_kernel, dim3((unsigned)nb_pool), dim3(256), 0, st, T, raw, attn);
+    if (hipGetLastError() != hipSuccess) return COMPACTOR_EHIP;
+  }
+  return COMPACTOR_OK;
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -216,6 +216,17 @@ def synthetic_attention_scores(L, H, n, device="cpu", seed=0) -> torch.Tensor:
     return torch.exp(torch.randn(L, H, n, generator=g, device=device, dtype=torch.float32))
 
 
+def synthetic_queries(L, Hq, n, d=HEAD_DIM, device="cpu", seed=0, request=0) -> torch.Tensor:
+    """Stand-in for the model's queries, bf16 [L, Hq, n, d]: N(0,1) entries with a per-head
+    gain in [0.5, 1.5], so that heads differ in how peaked their attention is."""
+    g = _gen(device, seed, 8, request)
+    q = torch.empty(L, Hq, n, d, device=device, dtype=torch.bfloat16)
+    for l in range(L):
+        gain = 0.5 + torch.rand(Hq, 1, 1, generator=g, device=device, dtype=torch.float32)
+        q[l] = (gain * torch.randn(Hq, n, d, generator=g, device=device, dtype=torch.float32)).to(torch.bfloat16)
+    return q
+
+
 def bf16_bits(t: torch.Tensor):
     """Raw bit patterns (numpy uint16) of a bf16 tensor, for the oracle."""
     return t.contiguous().view(torch.int16).cpu().numpy().view("uint16")

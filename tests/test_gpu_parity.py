@@ -346,3 +346,58 @@ def test_config4_ragged_batch_full_lengths(C):
     st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 1))
     _say("  %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
     _structure_checks(C, w, out)
+
+
+# ------------------------------------------------------------------ attention scores (Sec. 3.2)
+def _attention_case(C, L, H, G, n, keys, pool=7, seed=0):
+    w = keys(device=DEV, L=L, H=H, n=n)
+    k = w.requests[0].k
+    q = W.synthetic_queries(L, H * G, n, device=DEV, seed=seed)
+    ap = C.AttnParams(L, H, H * G, pool=pool)
+    a = C.compactor_attention_scores(ap, [C.AttnRequest(q, k)])
+    torch.cuda.synchronize()
+    a = a.view(L, H, n).cpu().numpy()
+    worst = 0.0
+    for l in range(L):
+        for h in range(H):
+            K = O.bf16_bits_to_f64(W.bf16_bits(k[l, h]))
+            Qs = [O.bf16_bits_to_f64(W.bf16_bits(q[l, h * G + j])) for j in range(G)]
+            want = O.attention_scores(Qs, K, chunk=256, pool=pool)
+            err = np.abs(a[l, h] - want)
+            bound = 1e-3 * np.abs(want) + 1e-6
+            assert np.all(err <= bound), "attention scores layer %d head %d: worst rel err %.3g" % (
+                l, h, float(np.max(err / np.maximum(want, 1e-12))))
+            worst = max(worst, float(np.max(err / np.maximum(want, 1e-12))))
+    return worst, w, q, a
+
+
+@pytest.mark.parametrize("n", [1, 100, 256, 700, 3000])
+def test_attention_scores_match_oracle(C, n):
+    _say("attention scores: 2 layers x 2 kv heads x 4 query heads, n=%d" % n)
+    worst, _, _, a = _attention_case(C, 2, 2, 4, n, W.config1)
+    _say("  max rel err %.3g" % worst)
+    if n == 256:     # one full block, no pooling: every query hands out one unit of attention
+        w2, _, _, raw = _attention_case(C, 1, 1, 2, 256, W.config1, pool=1)
+        assert abs(raw.sum() - 256) < 1e-2
+
+
+def test_attention_scores_low_rank_keys_and_blend_end_to_end(C):
+    _say("attention scores on config-2 keys, then the full blend: compress with a from the GPU")
+    L, H, G, n = 1, 4, 4, 4100
+    worst, w, q, a = _attention_case(C, L, H, G, n, W.config2)
+    _say("  attention max rel err %.3g" % worst)
+    w.requests[0].attn = torch.from_numpy(a).to(DEV).contiguous()
+    st, _ = U.run_and_check(C, w, DEV, kept_tol_scale=50.0)
+    _say("  fused compress with blended scores: swaps %d" % st["swaps"])
+
+
+def test_attention_error_codes(C):
+    k = torch.zeros(1, 1, 64, 128, dtype=torch.bfloat16, device=DEV)
+    q = torch.zeros(1, 3, 64, 128, dtype=torch.bfloat16, device=DEV)
+    for bad in (C.AttnParams(1, 2, 3), C.AttnParams(1, 1, 3, pool=4)):
+        with pytest.raises(C.CompactorError) as e:
+            C.compactor_attention_scores(bad, [C.AttnRequest(q, k)])
+        assert e.value.code == C.EINVAL
+    with pytest.raises(C.CompactorError) as e:
+        C.compactor_attention_scores(C.AttnParams(1, 1, 3, chunk=128), [C.AttnRequest(q, k)])
+    assert e.value.code == C.EUNSUPPORTED
