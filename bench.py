@@ -45,6 +45,10 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a dispatch of known size against "
                          "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
+    ap.add_argument("--attention", action="store_true",
+                    help="measure compactor_attention_scores (Sec. 3.2 scores a) and the blended "
+                         "compress on the same workload instead of the default line")
+    ap.add_argument("--q-per-kv", type=int, default=4, help="query heads per kv head for --attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--allow-flagged", action="store_true",
                     help="do not fail when a head reports a status flag (kernel experiments only)")
@@ -113,6 +117,50 @@ def cpu_baseline(W, O, w, phi, budget_s):
                       (done, LH * len(w.requests), head_rows, t_total)}
 
 
+def attention_mode(a, torch, C, W, w, reqs, params, bufs, dev):
+    """Times the attention-score kernels alone and the full Compactor step (a, then the fused
+    compress with the blend), on the same synthetic keys plus synthetic queries."""
+    G = a.q_per_kv
+    ap = C.AttnParams(w.layers, w.kv_heads, w.kv_heads * G)
+    qs = [W.synthetic_queries(w.layers, w.kv_heads * G, r.n, device=dev, request=i) for i, r in enumerate(w.requests)]
+    areqs = [C.AttnRequest(q, r.k) for q, r in zip(qs, w.requests)]
+    total = sum(w.layers * w.kv_heads * r.n for r in w.requests)
+    attn = torch.empty(total, dtype=torch.float32, device=dev)
+    aws = torch.empty(max(256, C.compactor_attention_workspace_size(ap, areqs)), dtype=torch.uint8, device=dev)
+    off, breqs = 0, []
+    for r in w.requests:
+        cnt = w.layers * w.kv_heads * r.n
+        breqs.append(C.Request(k_score=r.k, v_cache=r.v, ratio=r.ratio, attn=attn[off:off + cnt]))
+        off += cnt
+
+    def run(fn):
+        for _ in range(a.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / a.steps * 1e3
+
+    ms_attn = run(lambda: C.compactor_attention_scores(ap, areqs, attn=attn, workspace=aws))
+    ms_full = run(lambda: (C.compactor_attention_scores(ap, areqs, attn=attn, workspace=aws),
+                           C.compactor_compress(params, breqs, want_scores=False, **bufs)))
+    rows_q = sum(r.n for r in w.requests) * w.layers * w.kv_heads * G
+    rows_k = sum(r.n for r in w.requests) * w.layers * w.kv_heads
+    flops = 2.0 * 256 * 128 * rows_q                   # Q K^T inside 256-token blocks
+    nbytes = 256.0 * (rows_q + rows_k) + 8.0 * rows_k  # Q and K read once, sums written and pooled
+    print(json.dumps({
+        "metric": "attention scores a (Sec. 3.2) and full Compactor step at 1 GPU",
+        "config": {"workload": w.name, "q_heads_per_kv_head": G, "chunk": 256, "pool": 7, "tokens": w.tokens},
+        "attention_ms": ms_attn, "attention_TFLOP/s": flops / (ms_attn * 1e-3) / 1e12,
+        "attention_GB/s": nbytes / (ms_attn * 1e-3) / 1e9,
+        "attention_frac_of_8TB/s": nbytes / (ms_attn * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "attention_frac_of_bf16_mfma_peak": flops / (ms_attn * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "full_step_ms": ms_full, "full_step_tokens_per_s": w.tokens / (ms_full * 1e-3),
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "dtype": "bf16", "data": "synthetic"}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -151,6 +199,10 @@ def main():
 
     def step(p):
         C.compactor_compress(p, reqs, want_scores=False, **bufs)
+
+    if a.attention:
+        attention_mode(a, torch, C, W, w, reqs, params, bufs, dev)
+        return
 
     if a.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()

@@ -123,7 +123,8 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(const AttnTable T,
   store_q(0, stg);
   __syncthreads();
 
-  const float scale = T.scale;
+  const float c2 = T.scale * 1.4426950408889634f;      // logits in units of log 2
+  const bool ragged = c0 + ATT_C > n;                   // only the last block of a head
   for (int step = 0; step < nsteps; ++step) {
     const int buf = step & 1;
     load_q(step + 1, stg);                              // in flight during the MFMAs
@@ -145,39 +146,42 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(const AttnTable T,
       }
     }
 
-    // local softmax statistics of every query over this wave's 64 keys
+    // local softmax statistics of every query over this wave's 64 keys, in the base-2 domain:
+    // e = 2^(c*s - m) with c = scale * log2(e), so an element costs one max, one fma, one exp
+    // and one add.  Keys past the end exist only in the last block (uniform branch).
     const int q0 = c0 + (step % (ATT_C / ATT_QB)) * ATT_QB;
-    float mloc[4], lloc[4];
+    float mloc[4];
 #pragma unroll
     for (int sl = 0; sl < 4; ++sl) {
+      if (ragged) {
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (key_base + 16 * kt + v >= n) acc[sl][kt][v] = -INFINITY;
+      }
       float m = -INFINITY;
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const bool valid = key_base + 16 * kt + v < n;
-          const float x = valid ? acc[sl][kt][v] * scale : -INFINITY;
-          acc[sl][kt][v] = x;
-          m = fmaxf(m, x);
-        }
+        for (int v = 0; v < 4; ++v) m = fmaxf(m, acc[sl][kt][v]);
       m = fmaxf(m, __shfl_xor(m, 16));
       m = fmaxf(m, __shfl_xor(m, 32));
-      const float ms = m == -INFINITY ? 0.f : m;        // a wave whose keys are all past the end
+      const float mc = m == -INFINITY ? 0.f : m * c2;   // a wave whose keys are all past the end
       float l = 0.f;
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          const float e = __expf(acc[sl][kt][v] - ms);
+          const float e = __builtin_amdgcn_exp2f(fmaf(acc[sl][kt][v], c2, -mc));
           acc[sl][kt][v] = e;
           l += e;
         }
       l += __shfl_xor(l, 16);
       l += __shfl_xor(l, 32);
-      mloc[sl] = ms;
-      lloc[sl] = l;
+      mloc[sl] = mc;
       if (lq == 0) {
-        st_m[buf][wave][16 * sl + l16] = m == -INFINITY ? -INFINITY : ms;
+        st_m[buf][wave][16 * sl + l16] = m == -INFINITY ? -INFINITY : mc;
         st_l[buf][wave][16 * sl + l16] = l;
       }
     }
@@ -189,21 +193,22 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(const AttnTable T,
 #pragma unroll
     for (int sl = 0; sl < 4; ++sl) {
       const int qi = 16 * sl + l16;
-      float m = -INFINITY;
-#pragma unroll
-      for (int w2 = 0; w2 < 4; ++w2) m = fmaxf(m, st_m[buf][w2][qi]);
-      float l = 0.f;
+      float mw[4], m = -INFINITY;
 #pragma unroll
       for (int w2 = 0; w2 < 4; ++w2) {
-        const float mw = st_m[buf][w2][qi];
-        l += mw == -INFINITY ? 0.f : st_l[buf][w2][qi] * __expf(mw - m);
+        mw[w2] = st_m[buf][w2][qi];
+        m = fmaxf(m, mw[w2]);
       }
-      const bool qvalid = q0 + qi < n;
-      const float f = qvalid ? __expf(mloc[sl] - m) / l : 0.f;
+      float l = 0.f;
+#pragma unroll
+      for (int w2 = 0; w2 < 4; ++w2)
+        l += mw[w2] == -INFINITY ? 0.f : st_l[buf][w2][qi] * __builtin_amdgcn_exp2f(mw[w2] - m);
+      const bool qvalid = !ragged || q0 + qi < n;
+      const float f = qvalid ? __builtin_amdgcn_exp2f(mloc[sl] - m) * __builtin_amdgcn_rcpf(l) : 0.f;
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) pacc[kt][v] += acc[sl][kt][v] * f;
+        for (int v = 0; v < 4; ++v) pacc[kt][v] = fmaf(acc[sl][kt][v], f, pacc[kt][v]);
     }
   }
 
