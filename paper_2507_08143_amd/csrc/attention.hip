@@ -43,11 +43,212 @@ struct AttnTable {
   int pool;
 };
 
+// Exchange between the four 16-lane rows of a wave with the row-swap instructions of gfx950:
+// after swapping the upper half of one copy with the lower half of the other, the two results
+// of a lane are its own value and its partner's (32 lanes away; then 16 lanes away), so a max
+// or a sum of the pair finishes one level of the reduction in every lane, without LDS traffic.
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float rows_max(float x) {
+  u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+  u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// x holds one value per lane; out[r] = the value of lane 16*r + (lane & 15), in every lane
+__device__ __forceinline__ void rows_broadcast(float x, float (&out)[4]) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  const u32x2 a = __builtin_amdgcn_permlane16_swap(r[0], r[0], false, false);
+  const u32x2 b = __builtin_amdgcn_permlane16_swap(r[1], r[1], false, false);
+  out[0] = __uint_as_float(a[0]);
+  out[1] = __uint_as_float(a[1]);
+  out[2] = __uint_as_float(b[0]);
+  out[3] = __uint_as_float(b[1]);
+}
+
+struct AttnLds {
+  uint16_t ql[2][ATT_QB * QPITCH];   // staged query rows, double buffered
+  float st_m[2][4][ATT_QB];          // per wave: scaled maximum of every query of the step
+  float st_l[2][4][ATT_QB];          //           and the sum of its exponentials
+};
+
+// One (kv-head, block) of the column sums.  RAGGED is the last block of a head whose length is
+// not a multiple of the block: only there keys and queries past the end have to be masked.
+template <bool RAGGED>
+__device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int head, int c0,
+                                           AttnLds &L, float *__restrict__ raw) {
+  const int n = s.n;
+  const int layer = head / s.H, kvh = head - layer * s.H;
+  const uint16_t *kp = s.k + (long long)layer * s.k_stride_l + (long long)kvh * s.k_stride_h;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int l16 = lane & 15, lq = lane >> 4;
+
+  // this wave's 64 keys as A operands: tile kt, lane (key l16, channel group lq)
+  bf16x8 ka[4][4];
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt) {
+    const int key = c0 + 64 * wave + 16 * kt + l16;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      union { uint4 u; bf16x8 v; } t;
+      t.u = make_uint4(0, 0, 0, 0);
+      if (!RAGGED || key < n)
+        t.u = *reinterpret_cast<const uint4 *>(kp + (long long)key * s.k_stride_t + 32 * kk + 8 * lq);
+      ka[kt][kk] = t.v;
+    }
+  }
+  // keys this lane sees in the MFMA result: tile kt, register v -> key c0 + 64*wave + 16*kt + 4*lq + v
+  const int key_base = c0 + 64 * wave + 4 * lq;
+
+  float pacc[4][4];
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) pacc[kt][v] = 0.f;
+
+  const int nsteps = s.G * (ATT_C / ATT_QB);          // (query head of the group, 64-query block)
+  const int ld_row = tid >> 4, ld_chunk = tid & 15;   // loader: 16 lanes per 256-B query row
+  auto load_q = [&](int step, uint4 (&stg)[4]) {
+    const int qh = step / (ATT_C / ATT_QB);
+    const uint16_t *qp = s.q + (long long)layer * s.q_stride_l + (long long)(kvh * s.G + qh) * s.q_stride_h;
+    const int r0 = c0 + (step % (ATT_C / ATT_QB)) * ATT_QB;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = r0 + ld_row + 16 * i;
+      stg[i] = make_uint4(0, 0, 0, 0);
+      if (step < nsteps && (!RAGGED || row < n))
+        stg[i] = load_stream16(qp + (long long)row * s.q_stride_t + ld_chunk * 8);
+    }
+  };
+  auto store_q = [&](int buf, const uint4 (&stg)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<uint4 *>(&L.ql[buf][(ld_row + 16 * i) * QPITCH + ld_chunk * 8]) = stg[i];
+  };
+
+  // S^T tile of one 16-query slice: acc[kt] = keys (tile kt) x queries, contraction over channels
+  f32x4 acc[4][4];
+  auto product = [&](int buf, int sl) {
+    bf16x8 qb[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      qb[kk] = *reinterpret_cast<const bf16x8 *>(&L.ql[buf][(16 * sl + l16) * QPITCH + 32 * kk + 8 * lq]);
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+      acc[sl][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        acc[sl][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt][kk], qb[kk], acc[sl][kt], 0, 0, 0);
+    }
+  };
+
+  uint4 stg[4];
+  load_q(0, stg);
+  store_q(0, stg);
+  __syncthreads();
+  product(0, 0);
+
+  const float c2 = scale * 1.4426950408889634f;       // logits in units of log 2
+  for (int step = 0; step < nsteps; ++step) {
+    const int buf = step & 1;
+    load_q(step + 1, stg);                              // in flight during this step
+
+    // Local softmax statistics of every query over this wave's 64 keys, in the base-2 domain:
+    // e = 2^(c*s - m) with c = scale * log2(e), so an element costs one max, one fma, one exp
+    // and one add.  The product of the next slice is issued ahead of the arithmetic of this one.
+    float m_mine = 0.f, l_mine = 0.f;    // statistics of query `lane` of the step (slice lq)
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl) {
+      if (sl < 3) product(buf, sl + 1);
+      if (RAGGED) {
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (key_base + 16 * kt + v >= n) acc[sl][kt][v] = -INFINITY;
+      }
+      float m = acc[sl][0][0];
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) m = fmaxf(m, acc[sl][kt][v]);
+      m = rows_max(m);
+      float mc = m * c2, mx = mc;
+      if (RAGGED && m == -INFINITY) mc = 0.f;           // a wave whose keys are all past the end
+      float l = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float e = __builtin_amdgcn_exp2f(fmaf(acc[sl][kt][v], c2, -mc));
+          acc[sl][kt][v] = e;
+          l += e;
+        }
+      l = rows_sum(l);
+      if (lq == sl) {
+        m_mine = mx;
+        l_mine = l;
+      }
+    }
+    L.st_m[buf][wave][lane] = m_mine;
+    L.st_l[buf][wave][lane] = l_mine;
+
+    store_q(buf ^ 1, stg);
+    __syncthreads();        // statistics of this step and the next step's queries are in LDS
+
+    // merge the four waves' statistics, one query per lane, then hand every slice its factor
+    float m = L.st_m[buf][0][lane];
+    float mw[4];
+#pragma unroll
+    for (int w2 = 0; w2 < 4; ++w2) {
+      mw[w2] = L.st_m[buf][w2][lane];
+      m = fmaxf(m, mw[w2]);
+    }
+    float l = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < 4; ++w2) l = fmaf(L.st_l[buf][w2][lane], __builtin_amdgcn_exp2f(mw[w2] - m), l);
+    float f = __builtin_amdgcn_exp2f(m_mine - m) * __builtin_amdgcn_rcpf(l);
+    if (RAGGED) {
+      const int q0 = c0 + (step % (ATT_C / ATT_QB)) * ATT_QB;
+      if (q0 + lane >= n) f = 0.f;
+    }
+    float fs[4];
+    rows_broadcast(f, fs);
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl) {
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) pacc[kt][v] = fmaf(acc[sl][kt][v], fs[sl], pacc[kt][v]);
+      if (sl == 0 && step + 1 < nsteps) product(buf ^ 1, 0);   // first slice of the next step
+    }
+  }
+
+  // column sums: add over the 16 query lanes of each quarter, average over the query heads
+  const float inv_g = 1.f / (float)s.G;
+  float *out = raw + s.out_off + (long long)head * n;
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      float x = pacc[kt][v];
+      x += __shfl_xor(x, 1);
+      x += __shfl_xor(x, 2);
+      x += __shfl_xor(x, 4);
+      x += __shfl_xor(x, 8);
+      const int key = key_base + 16 * kt + v;
+      if (l16 == 0 && key < n) out[key] = x * inv_g;
+    }
+}
+
 __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(const AttnTable T,
                                                              float *__restrict__ raw) {
-  __shared__ __attribute__((aligned(16))) uint16_t ql[2][ATT_QB * QPITCH];
-  __shared__ float st_m[2][4][ATT_QB];
-  __shared__ float st_l[2][4][ATT_QB];
+  __shared__ __attribute__((aligned(16))) AttnLds L;
 
   // locate (segment, kv head, block)
   int seg = 0, head = 0, blk = 0;
@@ -67,166 +268,11 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(const AttnTable T,
     }
   }
   const AttnSeg &s = T.s[seg];
-  const int n = s.n, c0 = blk * ATT_C;
-  const int layer = head / s.H, kvh = head - layer * s.H;
-  const uint16_t *kp = s.k + (long long)layer * s.k_stride_l + (long long)kvh * s.k_stride_h;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int l16 = lane & 15, lq = lane >> 4;
-
-  // this wave's 64 keys as A operands: tile kt, lane (key l16, channel group lq)
-  bf16x8 ka[4][4];
-#pragma unroll
-  for (int kt = 0; kt < 4; ++kt) {
-    const int key = c0 + 64 * wave + 16 * kt + l16;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      union { uint4 u; bf16x8 v; } t;
-      t.u = make_uint4(0, 0, 0, 0);
-      if (key < n) t.u = *reinterpret_cast<const uint4 *>(kp + (long long)key * s.k_stride_t + 32 * kk + 8 * lq);
-      ka[kt][kk] = t.v;
-    }
-  }
-  // keys this lane sees in the MFMA result: tile kt, register v -> key c0 + 64*wave + 16*kt + 4*lq + v
-  const int key_base = c0 + 64 * wave + 4 * lq;
-
-  float pacc[4][4];
-#pragma unroll
-  for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-    for (int v = 0; v < 4; ++v) pacc[kt][v] = 0.f;
-
-  const int nsteps = s.G * (ATT_C / ATT_QB);          // (query head of the group, 64-query block)
-  const int ld_row = tid >> 4, ld_chunk = tid & 15;   // loader: 16 lanes per 256-B query row
-  auto q_rows = [&](int step) -> const uint16_t * {
-    const int qh = step / (ATT_C / ATT_QB);
-    return s.q + (long long)layer * s.q_stride_l + (long long)(kvh * s.G + qh) * s.q_stride_h;
-  };
-  auto load_q = [&](int step, uint4 (&stg)[4]) {
-    const uint16_t *qp = q_rows(step);
-    const int r0 = c0 + (step % (ATT_C / ATT_QB)) * ATT_QB;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = r0 + ld_row + 16 * i;
-      stg[i] = make_uint4(0, 0, 0, 0);
-      if (step < nsteps && row < n)
-        stg[i] = load_stream16(qp + (long long)row * s.q_stride_t + ld_chunk * 8);
-    }
-  };
-  auto store_q = [&](int buf, const uint4 (&stg)[4]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<uint4 *>(&ql[buf][(ld_row + 16 * i) * QPITCH + ld_chunk * 8]) = stg[i];
-  };
-
-  uint4 stg[4];
-  load_q(0, stg);
-  store_q(0, stg);
-  __syncthreads();
-
-  const float c2 = T.scale * 1.4426950408889634f;      // logits in units of log 2
-  const bool ragged = c0 + ATT_C > n;                   // only the last block of a head
-  for (int step = 0; step < nsteps; ++step) {
-    const int buf = step & 1;
-    load_q(step + 1, stg);                              // in flight during the MFMAs
-
-    // S^T tiles: acc[slice][kt] = keys (tile kt) x queries (slice), contraction over channels
-    f32x4 acc[4][4];
-#pragma unroll
-    for (int sl = 0; sl < 4; ++sl) {
-      bf16x8 qb[4];
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-        qb[kk] = *reinterpret_cast<const bf16x8 *>(&ql[buf][(16 * sl + l16) * QPITCH + 32 * kk + 8 * lq]);
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt) {
-        acc[sl][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-          acc[sl][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt][kk], qb[kk], acc[sl][kt], 0, 0, 0);
-      }
-    }
-
-    // local softmax statistics of every query over this wave's 64 keys, in the base-2 domain:
-    // e = 2^(c*s - m) with c = scale * log2(e), so an element costs one max, one fma, one exp
-    // and one add.  Keys past the end exist only in the last block (uniform branch).
-    const int q0 = c0 + (step % (ATT_C / ATT_QB)) * ATT_QB;
-    float mloc[4];
-#pragma unroll
-    for (int sl = 0; sl < 4; ++sl) {
-      if (ragged) {
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (key_base + 16 * kt + v >= n) acc[sl][kt][v] = -INFINITY;
-      }
-      float m = -INFINITY;
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) m = fmaxf(m, acc[sl][kt][v]);
-      m = fmaxf(m, __shfl_xor(m, 16));
-      m = fmaxf(m, __shfl_xor(m, 32));
-      const float mc = m == -INFINITY ? 0.f : m * c2;   // a wave whose keys are all past the end
-      float l = 0.f;
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const float e = __builtin_amdgcn_exp2f(fmaf(acc[sl][kt][v], c2, -mc));
-          acc[sl][kt][v] = e;
-          l += e;
-        }
-      l += __shfl_xor(l, 16);
-      l += __shfl_xor(l, 32);
-      mloc[sl] = mc;
-      if (lq == 0) {
-        st_m[buf][wave][16 * sl + l16] = m == -INFINITY ? -INFINITY : mc;
-        st_l[buf][wave][16 * sl + l16] = l;
-      }
-    }
-
-    store_q(buf ^ 1, stg);
-    __syncthreads();        // statistics of this step and the next step's queries are in LDS
-
-    // merge the four waves' statistics and add this step's probabilities to the column sums
-#pragma unroll
-    for (int sl = 0; sl < 4; ++sl) {
-      const int qi = 16 * sl + l16;
-      float mw[4], m = -INFINITY;
-#pragma unroll
-      for (int w2 = 0; w2 < 4; ++w2) {
-        mw[w2] = st_m[buf][w2][qi];
-        m = fmaxf(m, mw[w2]);
-      }
-      float l = 0.f;
-#pragma unroll
-      for (int w2 = 0; w2 < 4; ++w2)
-        l += mw[w2] == -INFINITY ? 0.f : st_l[buf][w2][qi] * __builtin_amdgcn_exp2f(mw[w2] - m);
-      const bool qvalid = !ragged || q0 + qi < n;
-      const float f = qvalid ? __builtin_amdgcn_exp2f(mloc[sl] - m) * __builtin_amdgcn_rcpf(l) : 0.f;
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) pacc[kt][v] = fmaf(acc[sl][kt][v], f, pacc[kt][v]);
-    }
-  }
-
-  // column sums: add over the 16 query lanes of each quarter, average over the query heads
-  const float inv_g = 1.f / (float)s.G;
-  float *out = raw + s.out_off + (long long)head * n;
-#pragma unroll
-  for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      float x = pacc[kt][v];
-      x += __shfl_xor(x, 1);
-      x += __shfl_xor(x, 2);
-      x += __shfl_xor(x, 4);
-      x += __shfl_xor(x, 8);
-      const int key = key_base + 16 * kt + v;
-      if (l16 == 0 && key < n) out[key] = x * inv_g;
-    }
+  const int c0 = blk * ATT_C;
+  if (c0 + ATT_C > s.n)
+    attn_block<true>(s, T.scale, head, c0, L, raw);
+  else
+    attn_block<false>(s, T.scale, head, c0, L, raw);
 }
 
 // Mean pooling along the sequence: window `pool` (odd), zero padding, divided by `pool`.
