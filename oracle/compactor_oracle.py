@@ -48,6 +48,7 @@ __all__ = [
     "blend_scores",
     "keep_count",
     "select_topk",
+    "select_topk_layer",
     "compact_rows",
     "compress_head",
     "calibration_curve",
@@ -299,6 +300,28 @@ def select_topk(s: np.ndarray, k_keep: int) -> np.ndarray:
     order = np.lexsort((np.arange(n), -val, isnan))
     kept = np.sort(order[:k_keep])
     return kept.astype(np.int32)
+
+
+def select_topk_layer(S: np.ndarray, k_total: int):
+    """Head-adaptive selection (Sec. 3.3, "across all heads"): the k_total largest of
+    the H*n scores of one layer's heads, wherever they fall.
+
+    S is [H, n].  The pool is one layer (scoring stays per head; only the budget
+    is shared, so a head with many high scores keeps more than ceil(r n) tokens and
+    another fewer, possibly none).  Same order as select_topk: higher score first,
+    equal scores by lower (head, token) position first, float32 comparison, NaN
+    last.  Returns a list of H ascending int32 index arrays (ragged).
+    """
+    S32 = np.asarray(S, dtype=np.float32)
+    H, n = S32.shape
+    flat = S32.reshape(-1)
+    isnan = np.isnan(flat)
+    val = np.where(isnan, 0.0, flat.astype(np.float64))
+    order = np.lexsort((np.arange(H * n), -val, isnan))
+    taken = np.zeros(H * n, dtype=bool)
+    taken[order[:k_total]] = True
+    taken = taken.reshape(H, n)
+    return [np.flatnonzero(taken[h]).astype(np.int32) for h in range(H)]
 
 
 def compact_rows(K_cache: np.ndarray, V: np.ndarray, kept: np.ndarray):

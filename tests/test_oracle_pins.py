@@ -397,3 +397,66 @@ def test_mean_pool_and_group_average():
     np.testing.assert_allclose(a, want, atol=1e-15)
     # a single query head and no pooling is the raw vector
     np.testing.assert_allclose(O.attention_scores([Qs[0]], K, 16, pool=1), O.attention_scores_raw(Qs[0], K, 16), atol=0)
+
+
+# ---------------------------------------------------------------- head-adaptive selection (Sec. 3.3)
+def _brute_layer(S, k_total):
+    """Pure-Python reference: sort (score descending, head, token) tuples."""
+    H, n = S.shape
+    items = []
+    for h in range(H):
+        for i in range(n):
+            v = float(np.float32(S[h, i]))
+            nan = v != v
+            items.append((nan, -(0.0 if nan else v), h, i))
+    items.sort()
+    out = [[] for _ in range(H)]
+    for _, _, h, i in items[:k_total]:
+        out[h].append(i)
+    return [sorted(x) for x in out]
+
+
+def test_select_topk_layer_brute_force_and_ties():
+    rng = np.random.default_rng(11)
+    for H, n, k in [(1, 7, 3), (3, 5, 1), (4, 9, 20), (2, 6, 12), (5, 8, 17)]:
+        # few distinct values: many ties inside and across heads
+        S = rng.integers(0, 4, size=(H, n)).astype(np.float64) / 3.0
+        S[rng.random((H, n)) < 0.1] = np.nan
+        S[rng.random((H, n)) < 0.05] = -np.inf
+        got = O.select_topk_layer(S, k)
+        want = _brute_layer(S, k)
+        assert [g.tolist() for g in got] == want
+        assert sum(len(g) for g in got) == k
+
+
+def test_select_topk_layer_properties():
+    rng = np.random.default_rng(12)
+    H, n, k_total = 6, 200, 333
+    S = rng.standard_normal((H, n)) * rng.uniform(0.2, 3.0, size=(H, 1))
+    got = O.select_topk_layer(S, k_total)
+    cnt = [len(g) for g in got]
+    assert sum(cnt) == k_total
+    S32 = S.astype(np.float32)
+    kept = np.zeros((H, n), dtype=bool)
+    for h in range(H):
+        assert np.all(np.diff(got[h]) > 0)
+        kept[h, got[h]] = True
+        # restricted to one head, the shared budget is that head's own top-cnt[h]
+        assert np.array_equal(got[h], O.select_topk(S[h], cnt[h])) or cnt[h] == 0
+    # one threshold for the whole layer: nothing evicted beats anything kept
+    assert S32[kept].min() >= S32[~kept].max()
+    # one head alone is the per-head rule
+    assert np.array_equal(O.select_topk_layer(S[:1], 50)[0], O.select_topk(S[0], 50))
+    # a head whose scores all exceed every other head's takes its whole length first
+    S2 = S.copy()
+    S2[2] += 100.0
+    got2 = O.select_topk_layer(S2, n + 10)
+    assert len(got2[2]) == n and sum(len(g) for g in got2) == n + 10
+    # equal scores everywhere: the budget fills heads in order, tokens in order
+    got3 = O.select_topk_layer(np.ones((3, 4)), 6)
+    assert [g.tolist() for g in got3] == [[0, 1, 2, 3], [0, 1], []]
+    # permuting the heads permutes the answer when there are no ties
+    perm = rng.permutation(H)
+    gotp = O.select_topk_layer(S[perm], k_total)
+    for j, h in enumerate(perm):
+        assert np.array_equal(gotp[j], got[h])
