@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--gram-wgs", type=int, default=0, help="tuning override (0 = library's choice)")
     ap.add_argument("--score-tokens", type=int, default=0, help="tuning override (0 = library's choice)")
     ap.add_argument("--streams", type=int, default=0, help="stream lanes (0 = library default)")
+    ap.add_argument("--scope", choices=["head", "layer"], default="head",
+                    help="selection pool: per head (the headline metric) or head-adaptive per layer")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a dispatch of known size against "
                          "which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
@@ -182,7 +184,8 @@ def main():
     mk = lambda events: C.Params(w.layers, w.kv_heads, sketch_dim=w.sketch_dim, phi=phi,
                                  ridge_rel=w.ridge_rel, group_bytes=group_bytes, stage_events=events,
                                  gram_wgs=a.gram_wgs, score_tokens=a.score_tokens,
-                                 streams=(1 if events is not None else a.streams))
+                                 streams=(1 if events is not None else a.streams),
+                                 select_scope=(C.SCOPE_LAYER if a.scope == "layer" else C.SCOPE_HEAD))
     params, params_ev = mk(None), mk(ev)
     reqs = [C.Request(k_score=r.k, v_cache=r.v, ratio=r.ratio) for r in w.requests]
     so, ko, kk = C.compactor_layout(params, reqs)
@@ -257,7 +260,7 @@ def main():
         "config": {"workload": w.name, "layers": w.layers, "kv_heads": w.kv_heads, "head_dim": 128,
                    "requests": len(reqs), "tokens": tokens, "head_rows": rows,
                    "kept_head_rows": kept, "sketch_dim": w.sketch_dim,
-                   "group_mb": a.group_mb},
+                   "group_mb": a.group_mb, "select_scope": a.scope},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "algorithmic_bytes": sbytes[dominant],

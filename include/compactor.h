@@ -101,6 +101,13 @@ typedef struct compactor_params {
                              forked from and joined back into the caller's stream by events, so
                              that latency-bound kernels of one group run beside streaming kernels
                              of another.  The workspace grows to one slice per lane. */
+  int32_t select_scope;   /* COMPACTOR_SCOPE_HEAD (default): every head keeps its own top k_keep.
+                             COMPACTOR_SCOPE_LAYER: head-adaptive selection (Sec. 3.3, retain the
+                             top scores "across all heads"; the paper's experiments, Sec. 4): the
+                             H kv heads of a layer share one budget of H*k_keep tokens, taken from
+                             the H*n scores of the layer wherever they fall; equal scores go to
+                             the lower (head, token) position.  Needs H*n < 2^31 - 64.  Heads
+                             then keep different numbers of tokens: see compactor_select. */
   void  **stage_events;   /* profiling aid, normally NULL.  host array of COMPACTOR_NUM_STAGES+1
                              hipEvent_t created by the caller: event[0] is recorded on the stream
                              before the first kernel of a group and event[i+1] after stage i's
@@ -109,6 +116,9 @@ typedef struct compactor_params {
                              hold the last group's times.  Stages a call does not run leave
                              their events unrecorded. */
 } compactor_params_t;
+
+#define COMPACTOR_SCOPE_HEAD    0
+#define COMPACTOR_SCOPE_LAYER   1
 
 /* stage indices for compactor_params_t.stage_events */
 #define COMPACTOR_STAGE_GRAM     0   /* partial Gram matrices K^T K (MFMA) */
@@ -163,7 +173,13 @@ int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs
  *             tokens of each head, ascending
  *   kept_cnt  device, int32 [nreq*L*H]: number of indices written per head (= k_keep_b)
  * Order: higher score first, equal scores by lower token index; NaN ranks below every number
- * and -0.0 equals +0.0.  The reqs' tensors are not read, only n and ratio. */
+ * and -0.0 equals +0.0.  The reqs' tensors are not read, only n and ratio.
+ * Layer scope (params.select_scope): the region of layer l of request b, kept_off[b] + l*H*k_keep_b
+ * .. + H*k_keep_b, holds the retained tokens of head 0 (ascending), then head 1, and so on,
+ * kept_cnt[b][l][h] of them for head h (any number from 0 to n; they add up to H*k_keep_b).
+ * compactor_compact packs rows in the same ragged order.
+ * workspace: needed (size: compactor_workspace_size) in layer scope or when a head has more than
+ * 32768 tokens; may be NULL otherwise. */
 int compactor_select(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
                      const float *scores, int32_t *kept_idx, int32_t *kept_cnt,
                      void *workspace, size_t workspace_bytes, void *stream);

@@ -40,7 +40,7 @@ class _Params(C.Structure):
                 ("sketch_dim", C.c_int32), ("phi", C.c_void_p), ("ridge_rel", C.c_float),
                 ("lambda_blend", C.c_float), ("group_bytes", C.c_int64),
                 ("gram_wgs", C.c_int32), ("score_tokens", C.c_int32), ("streams", C.c_int32),
-                ("stage_events", C.c_void_p)]
+                ("select_scope", C.c_int32), ("stage_events", C.c_void_p)]
 
 
 class _AttnRequest(C.Structure):
@@ -138,6 +138,9 @@ def _check(rc: int):
         raise CompactorError(rc)
 
 
+SCOPE_HEAD, SCOPE_LAYER = 0, 1
+
+
 @dataclass
 class Params:
     layers: int
@@ -152,6 +155,7 @@ class Params:
     gram_wgs: int = 0                              # tuning knobs, 0 = library's choice
     score_tokens: int = 0
     streams: int = 0                                # 2..4 = spread head groups over helper streams
+    select_scope: int = 0                           # SCOPE_HEAD, or SCOPE_LAYER (head-adaptive)
 
     def c(self) -> _Params:
         phi = 0
@@ -161,7 +165,7 @@ class Params:
         ev = C.cast(self.stage_events.array, C.c_void_p) if self.stage_events is not None else None
         return _Params(self.layers, self.kv_heads, self.head_dim, self.sketch_dim, phi,
                        self.ridge_rel, self.lambda_blend, self.group_bytes, self.gram_wgs,
-                       self.score_tokens, self.streams, ev)
+                       self.score_tokens, self.streams, self.select_scope, ev)
 
 
 @dataclass
@@ -226,7 +230,8 @@ def compactor_default_params(layers: int, kv_heads: int) -> Params:
     p = _Params()
     _lib.compactor_default_params(C.byref(p), layers, kv_heads)
     return Params(p.layers, p.kv_heads, p.sketch_dim, None, p.ridge_rel, p.lambda_blend,
-                  p.group_bytes, p.head_dim, None, p.gram_wgs, p.score_tokens, p.streams)
+                  p.group_bytes, p.head_dim, None, p.gram_wgs, p.score_tokens, p.streams,
+                  p.select_scope)
 
 
 def compactor_layout(params: Params, reqs: Sequence[Request]):
@@ -268,7 +273,7 @@ def compactor_score(params: Params, reqs: Sequence[Request], scores=None, status
 
 
 def compactor_select(params: Params, reqs: Sequence[Request], scores: torch.Tensor,
-                     kept_idx=None, kept_cnt=None, stream=None):
+                     kept_idx=None, kept_cnt=None, workspace=None, stream=None):
     """-> (kept_idx int32 [sum L*H*k_keep], kept_cnt int32 [nreq*L*H])"""
     _, ko, _ = compactor_layout(params, reqs)
     dev = scores.device
@@ -277,8 +282,11 @@ def compactor_select(params: Params, reqs: Sequence[Request], scores: torch.Tens
     if kept_cnt is None:
         kept_cnt = torch.empty(len(reqs) * params.layers * params.kv_heads, dtype=torch.int32, device=dev)
     pp, arr, n = _marshal(params, reqs)
-    _check(_lib.compactor_select(pp, arr, n, _ptr(scores), _ptr(kept_idx), _ptr(kept_cnt), 0, 0,
-                                 _stream(stream)))
+    if workspace is None:
+        nbytes = max(256, compactor_workspace_size(params, reqs))
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    _check(_lib.compactor_select(pp, arr, n, _ptr(scores), _ptr(kept_idx), _ptr(kept_cnt),
+                                 _ptr(workspace), workspace.numel(), _stream(stream)))
     return kept_idx, kept_cnt
 
 

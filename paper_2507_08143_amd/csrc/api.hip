@@ -34,6 +34,16 @@ int check_params(const compactor_params_t *p, bool scoring) {
   }
   if (p->group_bytes < 0 || p->gram_wgs < 0 || p->score_tokens < 0 || p->streams < 0)
     return COMPACTOR_EINVAL;
+  if (p->select_scope != COMPACTOR_SCOPE_HEAD && p->select_scope != COMPACTOR_SCOPE_LAYER)
+    return COMPACTOR_EINVAL;
+  return COMPACTOR_OK;
+}
+
+// Layer scope pools H heads: their tokens and their budget are counted in 32-bit integers.
+int check_scope(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq) {
+  if (p->select_scope != COMPACTOR_SCOPE_LAYER) return COMPACTOR_OK;
+  for (int b = 0; b < nreq; ++b)
+    if ((long long)reqs[b].n * p->kv_heads > 0x7fffffffll - 64) return COMPACTOR_EINVAL;
   return COMPACTOR_OK;
 }
 
@@ -98,8 +108,8 @@ int score_tokens_for(const compactor_params_t *p, const SegTable &T, int cus) {
 }
 
 struct GroupBytes {
-  size_t partials, g64, wt, hist1, scores;
-  size_t total() const { return partials + g64 + wt + hist1 + scores; }
+  size_t partials, g64, wt, hist1, sel, scores;   // in this order in the workspace
+  size_t total() const { return partials + g64 + wt + hist1 + sel + scores; }
 };
 
 GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bool need_scores) {
@@ -113,6 +123,7 @@ GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bo
   g.g64 = align_up((size_t)T.nheads * D * D * sizeof(double));
   g.wt = align_up((size_t)T.nheads * W_TERMS * m * D * sizeof(uint16_t));
   g.hist1 = align_up((size_t)T.nheads * HIST1_BINS * sizeof(int));
+  g.sel = align_up((size_t)select_scratch(T).ints() * sizeof(int));
   g.scores = need_scores ? align_up((size_t)rows * sizeof(float)) : 0;
   return g;
 }
@@ -129,12 +140,15 @@ int for_each_group(const compactor_params_t *p, const compactor_request_t *reqs,
   while (b < nreq) {
     SegTable T;
     memset(&T, 0, sizeof(T));
+    T.layer_scope = p->select_scope == COMPACTOR_SCOPE_LAYER;
+    const int unit = T.layer_scope ? p->kv_heads : 1;     // heads are taken in whole pools
     long long rows = 0, local_off = 0;
     while (b < nreq && T.nseg < MAX_SEG && rows < group_rows) {
       const compactor_request_t &r = reqs[b];
       const int kk = compactor_keep_count(r.n, r.ratio);
       long long can = (group_rows - rows + r.n - 1) / r.n;
-      if (can < 1) can = 1;
+      can = (can + unit - 1) / unit * unit;
+      if (can < unit) can = unit;
       const int take = (int)(can < (long long)(LH - h) ? can : (long long)(LH - h));
       Seg &s = T.s[T.nseg++];
       s.k_score = static_cast<const uint16_t *>(r.k_score);
@@ -260,11 +274,21 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   float *partials = reinterpret_cast<float *>(ws);
   double *g64 = reinterpret_cast<double *>(ws + gb.partials);
   uint16_t *wt = reinterpret_cast<uint16_t *>(ws + gb.partials + gb.g64);
-  int *hist1 = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt);
+  int *hist_base = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt);
+  int *hist1 = hist_base;
   bool blended = false;
   for (int i = 0; i < T.nseg; ++i) blended |= T.s[i].attn != nullptr;
   if (blended || hist1_out == nullptr) hist1 = nullptr;
   if (hist1_out) *hist1_out = hist1;
+  // histograms cleared on the way: the score kernel's, and those of a pooled selection that
+  // follows (they sit right behind it)
+  int *zero = nullptr;
+  long long zero_ints = 0;
+  if (hist1_out != nullptr) {
+    zero = hist_base;
+    zero_ints = (long long)T.nheads * HIST1_BINS;
+    if (select_needs_pools(T)) zero_ints += select_scratch(T).zero_ints();
+  }
   const int cus = compute_units();
   const GramPlan gp = gram_plan(p, T, cus);
   const int rpw = gp.tiles_per_wg;
@@ -275,9 +299,9 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   if (p->sketch_dim > 0) {
     hipEvent_t mid = m.ev ? static_cast<hipEvent_t>(m.ev[COMPACTOR_STAGE_REDUCE + 1]) : nullptr;
     HIP_TRY(launch_sketch_solve(T, p->sketch_dim, rpw, partials, p->phi, p->ridge_rel, g64, wt,
-                                status, hist1, st, mid));
+                                status, zero, zero_ints, st, mid));
   } else {
-    HIP_TRY(launch_gram_reduce(T, rpw, partials, g64, hist1, st));
+    HIP_TRY(launch_gram_reduce(T, rpw, partials, g64, zero, zero_ints, st));
     MARK(m, COMPACTOR_STAGE_REDUCE + 1);
     HIP_TRY(launch_solve(T, p->ridge_rel, g64, wt, status, st));
   }
@@ -341,6 +365,7 @@ void compactor_default_params(compactor_params_t *p, int32_t layers, int32_t kv_
   p->gram_wgs = 0;
   p->score_tokens = 0;
   p->streams = 0;
+  p->select_scope = COMPACTOR_SCOPE_HEAD;
   p->stage_events = nullptr;
 }
 
@@ -407,15 +432,39 @@ int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs
 
 int compactor_select(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
                      const float *scores, int32_t *kept_idx, int32_t *kept_cnt,
-                     void * /*workspace*/, size_t /*workspace_bytes*/, void *stream) {
+                     void *workspace, size_t workspace_bytes, void *stream) {
   int rc = check_params(p, false);
   if (rc) return rc;
   rc = check_requests(reqs, nreq, 0);
   if (rc) return rc;
+  rc = check_scope(p, reqs, nreq);
+  if (rc) return rc;
   if (!scores || !kept_idx || !kept_cnt) return COMPACTOR_EINVAL;
+  // only a pooled selection (long heads, layer scope) uses the workspace: its histograms
+  const long long grows = group_rows_of(p, reqs, nreq);
+  size_t need = 0;
+  rc = for_each_group(p, reqs, nreq, grows, false, [&](const SegTable &T, long long) {
+    if (select_needs_pools(T)) {
+      const GroupBytes gb = group_bytes_needed(p, T, false);
+      if (gb.hist1 + gb.sel > need) need = gb.hist1 + gb.sel;
+    }
+    return COMPACTOR_OK;
+  });
+  if (rc) return rc;
+  if (need > 0) {
+    if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
-  return for_each_group(p, reqs, nreq, 1ll << 60, false, [&](const SegTable &T, long long) {
-    HIP_TRY(launch_select(T, scores, nullptr, kept_idx, kept_cnt, st));
+  return for_each_group(p, reqs, nreq, grows, false, [&](const SegTable &T, long long) {
+    if (select_needs_pools(T)) {
+      const GroupBytes gb = group_bytes_needed(p, T, false);
+      int *hist1 = static_cast<int *>(workspace);
+      int *sel = reinterpret_cast<int *>(static_cast<unsigned char *>(workspace) + gb.hist1);
+      HIP_TRY(launch_select_pools(T, scores, hist1, false, sel, false, kept_idx, kept_cnt, st));
+    } else {
+      HIP_TRY(launch_select(T, scores, nullptr, kept_idx, kept_cnt, st));
+    }
     return COMPACTOR_OK;
   });
 }
@@ -427,11 +476,13 @@ int compactor_compact(const compactor_params_t *p, const compactor_request_t *re
   if (rc) return rc;
   rc = check_requests(reqs, nreq, NEED_PACK);
   if (rc) return rc;
+  rc = check_scope(p, reqs, nreq);
+  if (rc) return rc;
   if (!kept_idx || !kept_cnt || !k_packed || !v_packed) return COMPACTOR_EINVAL;
   if (!aligned16(k_packed) || !aligned16(v_packed)) return COMPACTOR_EALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
   return for_each_group(p, reqs, nreq, 1ll << 60, false, [&](const SegTable &T, long long) {
-    HIP_TRY(launch_gather(T, kept_idx, static_cast<uint16_t *>(k_packed),
+    HIP_TRY(launch_gather(T, kept_idx, kept_cnt, static_cast<uint16_t *>(k_packed),
                           static_cast<uint16_t *>(v_packed), st));
     return COMPACTOR_OK;
   });
@@ -445,6 +496,8 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
   if (rc) return rc;
   rc = check_requests(reqs, nreq, NEED_SCORE | NEED_PACK);
   if (rc) return rc;
+  rc = check_scope(p, reqs, nreq);
+  if (rc) return rc;
   if (!kept_idx || !kept_cnt || !k_packed || !v_packed || !status) return COMPACTOR_EINVAL;
   if (!aligned16(k_packed) || !aligned16(v_packed)) return COMPACTOR_EALIGN;
   const bool local_scores = scores == nullptr;
@@ -457,17 +510,23 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
                     static_cast<hipStream_t>(stream),
                     [&](const SegTable &T, long long rows, hipStream_t st, unsigned char *ws) {
     float *sc = scores;
-    if (local_scores) {
-      const GroupBytes gb = group_bytes_needed(p, T, true);
-      sc = reinterpret_cast<float *>(ws + gb.partials + gb.g64 + gb.wt + gb.hist1);
-    }
+    const GroupBytes gb = group_bytes_needed(p, T, true);
+    if (local_scores)
+      sc = reinterpret_cast<float *>(ws + gb.partials + gb.g64 + gb.wt + gb.hist1 + gb.sel);
     const int *hist1 = nullptr;
     const int rc2 = enqueue_score(p, T, rows, sc, status, ws, st, &hist1);
     if (rc2) return rc2;
     const Marks m{p->stage_events, st};
-    HIP_TRY(launch_select(T, sc, hist1, kept_idx, kept_cnt, st));
+    if (select_needs_pools(T)) {
+      int *hist_base = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt);
+      int *sel = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt + gb.hist1);
+      HIP_TRY(launch_select_pools(T, sc, hist_base, hist1 != nullptr, sel, true, kept_idx, kept_cnt,
+                                  st));
+    } else {
+      HIP_TRY(launch_select(T, sc, hist1, kept_idx, kept_cnt, st));
+    }
     MARK(m, COMPACTOR_STAGE_SELECT + 1);
-    HIP_TRY(launch_gather(T, kept_idx, static_cast<uint16_t *>(k_packed),
+    HIP_TRY(launch_gather(T, kept_idx, kept_cnt, static_cast<uint16_t *>(k_packed),
                           static_cast<uint16_t *>(v_packed), st));
     MARK(m, COMPACTOR_STAGE_GATHER + 1);
     return (int)COMPACTOR_OK;

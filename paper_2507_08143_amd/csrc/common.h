@@ -49,7 +49,14 @@ struct SegTable {
   Seg s[MAX_SEG];
   int nseg;
   int nheads;            // launch-local heads in total
+  int layer_scope;       // selection pool: 0 = one head, 1 = the kv heads of one layer (every
+                         // segment then covers whole layers)
 };
+
+// Heads per selection pool of a segment.
+__host__ __device__ __forceinline__ int pool_heads(const SegTable &T, const Seg &s) {
+  return T.layer_scope ? s.H : 1;
+}
 
 // Where a workgroup works: segment, head inside the request, tile inside the head.
 struct Where {
@@ -122,6 +129,15 @@ __device__ __forceinline__ void store_stream16(void *p, const uint4 &v) {
   u32x4 t;
   t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
   __builtin_nontemporal_store(t, reinterpret_cast<u32x4 *>(p));
+}
+
+// Clears z[0, count), the work split evenly over the workgroups of the launch (scratch that a
+// later kernel of the same stream adds into).
+__device__ __forceinline__ void zero_slice(int *__restrict__ z, long long count) {
+  if (z == nullptr) return;
+  const long long per = (count + gridDim.x - 1) / gridDim.x;
+  const long long b = per * blockIdx.x, e = b + per < count ? b + per : count;
+  for (long long i = b + threadIdx.x; i < e; i += blockDim.x) z[i] = 0;
 }
 
 __device__ __forceinline__ const uint16_t *head_ptr(const uint16_t *base, const Seg &s, int head) {
@@ -235,8 +251,9 @@ hipError_t launch_gram(const SegTable &T, int nwg, int tiles_per_wg, float *part
                        hipStream_t st);
 
 // G64[lhead] = sum over splits of the head's partials, in fp64.
+// zero[0, zero_ints) is cleared on the way (selection histograms), if not null.
 hipError_t launch_gram_reduce(const SegTable &T, int tiles_per_wg, const float *partials,
-                              double *g64, int *hist1, hipStream_t st);
+                              double *g64, int *zero, long long zero_ints, hipStream_t st);
 
 // Exact mode: factor G + rho I and emit W^T (as W_TERMS bf16 planes, [term][128][128] per head)
 // and the status word.
@@ -248,11 +265,12 @@ hipError_t launch_solve(const SegTable &T, float ridge_rel, const double *g64, u
 // two kernels.
 hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, const float *partials,
                                const float *phi, float ridge_rel, double *s_parts, uint16_t *wt,
-                               int32_t *status, int *hist1, hipStream_t st, hipEvent_t mid);
+                               int32_t *status, int *zero, long long zero_ints, hipStream_t st,
+                               hipEvent_t mid);
 
 // scores[i] = || W^T k_i ||^2
-// Also tallies every head's scores into hist1[lhead][HIST1_BINS] (top 12 key bits), which must
-// be zero on entry; hist1 may be null.
+// Also tallies the scores into hist1[selection pool][HIST1_BINS] (top 12 key bits; the pool is
+// the head, or the layer when T.layer_scope), which must be zero on entry; hist1 may be null.
 hipError_t launch_score(const SegTable &T, int ks, int tokens_per_wg, const uint16_t *wt,
                         float *scores, int32_t *status, int *hist1, hipStream_t st);
 
@@ -263,8 +281,25 @@ hipError_t launch_blend(const SegTable &T, float lambda, float *scores, hipStrea
 hipError_t launch_select(const SegTable &T, const float *scores, const int *hist1,
                          int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st);
 
-hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, uint16_t *k_packed,
-                         uint16_t *v_packed, hipStream_t st);
+// Selection by several workgroups per pool (long heads, or layer scope).  hist1 (pools x 4096
+// ints) and the scratch `sel` must be adjacent in memory, hist1 first: hist1 | hist2 | hist3 are
+// cleared together.  hist1_ready: the score kernel has tallied it; zeroed: somebody has cleared
+// hist1 .. hist3 already.
+struct SelectScratch {
+  int pools;
+  long long chunks, hist2_ints, hist3_ints, rec_ints, coff_ints, thr_ints;
+  long long ints() const { return hist2_ints + hist3_ints + rec_ints + coff_ints + thr_ints; }
+  long long zero_ints() const { return hist2_ints + hist3_ints; }
+};
+SelectScratch select_scratch(const SegTable &T);
+bool select_needs_pools(const SegTable &T);
+hipError_t launch_select_pools(const SegTable &T, const float *scores, int *hist1, bool hist1_ready,
+                               int *sel, bool zeroed, int32_t *kept_idx, int32_t *kept_cnt,
+                               hipStream_t st);
+
+// kept_cnt is read in layer scope only (ragged heads inside a layer's region).
+hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, const int32_t *kept_cnt,
+                         uint16_t *k_packed, uint16_t *v_packed, hipStream_t st);
 
 // Total workgroups of a launch whose blocks-per-head rule is (per_block, by_keep).
 inline long long total_blocks(const SegTable &T, int per_block, int step, bool by_keep) {

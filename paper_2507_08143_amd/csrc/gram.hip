@@ -174,13 +174,12 @@ __device__ __constant__ int kBlockJ[10] = {0, 1, 2, 3, 1, 2, 3, 2, 3, 3};
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const SegTable T, int tiles_per_wg,
                                                           const float *__restrict__ partials,
                                                           double *__restrict__ g64,
-                                                          int *__restrict__ hist1) {
+                                                          int *__restrict__ zero,
+                                                          long long zero_ints) {
   __shared__ double tile[32][33];
   const int lhead = blockIdx.x / 10;
   const int blk = blockIdx.x - lhead * 10;
-  if (hist1 != nullptr && blk < 8)   // the score kernel adds into this histogram: clear an eighth
-    for (int i = threadIdx.x; i < HIST1_BINS / 8; i += 256)
-      hist1[(size_t)lhead * HIST1_BINS + blk * (HIST1_BINS / 8) + i] = 0;
+  zero_slice(zero, zero_ints);   // histograms that the score and selection kernels add into
   int nsplit;
   const long long pb = partial_base(T, lhead, tiles_per_wg, nsplit);
   const int e = threadIdx.x * 4;                 // 4 consecutive elements of the block
@@ -213,10 +212,10 @@ hipError_t launch_gram(const SegTable &T, int nwg, int tiles_per_wg, float *part
 }
 
 hipError_t launch_gram_reduce(const SegTable &T, int tiles_per_wg, const float *partials,
-                              double *g64, int *hist1, hipStream_t st) {
+                              double *g64, int *zero, long long zero_ints, hipStream_t st) {
   if (T.nheads <= 0) return hipSuccess;
   hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)T.nheads * 10), dim3(256), 0, st, T,
-                     tiles_per_wg, partials, g64, hist1);
+                     tiles_per_wg, partials, g64, zero, zero_ints);
   return hipGetLastError();
 }
 

@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
   }
   if (hist1 != nullptr) {        // integer adds: the per-head histogram is order independent
     __syncthreads();
-    int *h1 = hist1 + (size_t)w.lhead * HIST1_BINS;
+    int *h1 = hist1 + (size_t)(w.lhead / pool_heads(T, s)) * HIST1_BINS;
     for (int i = tid; i < HIST1_BINS; i += 256) {
       const int c = hl[i];
       if (c) atomicAdd(&h1[i], c);

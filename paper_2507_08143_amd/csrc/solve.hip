@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void sketch_kernel(const SegTable T, int tiles
                                                      const float *__restrict__ partials,
                                                      const float *__restrict__ phi,
                                                      double *__restrict__ s_parts,
-                                                     int *__restrict__ hist1) {
+                                                     int *__restrict__ zero, long long zero_ints) {
   constexpr int GP = D + 1, TP = M + 1;
   __shared__ double Gs[32 * GP];
   __shared__ double Ts[32 * TP];
@@ -143,9 +143,7 @@ __global__ __launch_bounds__(256) void sketch_kernel(const SegTable T, int tiles
   const int tid = threadIdx.x;
   for (int idx = tid; idx < D * M / 4; idx += 256)
     reinterpret_cast<float4 *>(PH)[idx] = reinterpret_cast<const float4 *>(phi)[idx];
-  if (hist1 != nullptr)      // the score kernel adds into this histogram: clear this block's quarter
-    for (int i = tid; i < HIST1_BINS / 4; i += 256)
-      hist1[(size_t)lhead * HIST1_BINS + I * (HIST1_BINS / 4) + i] = 0;
+  zero_slice(zero, zero_ints);   // histograms that the score and selection kernels add into
 
   // rows 32I .. 32I+31 of G from the stored upper blocks (mirror blocks read transposed)
   int nsplit;
@@ -354,10 +352,10 @@ __global__ __launch_bounds__(64) void solve_wave_kernel(const SegTable T,
 template <int M>
 static hipError_t launch_sketched(const SegTable &T, int tiles_per_wg, const float *partials,
                                   const float *phi, float ridge_rel, double *s_parts,
-                                  uint16_t *wt, int32_t *status, int *hist1, hipStream_t st,
-                                  hipEvent_t mid) {
+                                  uint16_t *wt, int32_t *status, int *zero, long long zero_ints,
+                                  hipStream_t st, hipEvent_t mid) {
   hipLaunchKernelGGL((sketch_kernel<M>), dim3((unsigned)T.nheads * 4), dim3(256), 0, st, T,
-                     tiles_per_wg, partials, phi, s_parts, hist1);
+                     tiles_per_wg, partials, phi, s_parts, zero, zero_ints);
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   if (mid && hipEventRecord(mid, st) != hipSuccess) return hipErrorLaunchFailure;
   hipLaunchKernelGGL((solve_wave_kernel<M>), dim3((unsigned)T.nheads * 2), dim3(64), 0, st, T, phi,
@@ -369,13 +367,14 @@ static hipError_t launch_sketched(const SegTable &T, int tiles_per_wg, const flo
 // recorded between them (profiling).
 hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, const float *partials,
                                const float *phi, float ridge_rel, double *s_parts, uint16_t *wt,
-                               int32_t *status, int *hist1, hipStream_t st, hipEvent_t mid) {
+                               int32_t *status, int *zero, long long zero_ints, hipStream_t st,
+                               hipEvent_t mid) {
   if (T.nheads <= 0) return hipSuccess;
   switch (ks) {
-    case 16: return launch_sketched<16>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, hist1, st, mid);
-    case 32: return launch_sketched<32>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, hist1, st, mid);
-    case 48: return launch_sketched<48>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, hist1, st, mid);
-    case 64: return launch_sketched<64>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, hist1, st, mid);
+    case 16: return launch_sketched<16>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, zero, zero_ints, st, mid);
+    case 32: return launch_sketched<32>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, zero, zero_ints, st, mid);
+    case 48: return launch_sketched<48>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, zero, zero_ints, st, mid);
+    case 64: return launch_sketched<64>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, zero, zero_ints, st, mid);
     default: return hipErrorInvalidValue;
   }
 }

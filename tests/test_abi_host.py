@@ -65,7 +65,7 @@ def _req(n=100, ratio=0.5, ptr=0x1000, stride_t=128):
 def test_layout_offsets(B):
     global B_mod
     B_mod = B
-    p = B._Params(3, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, None)
+    p = B._Params(3, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, 0, None)
     reqs = (B._Request * 3)(_req(100, 0.5), _req(7, 1.0), _req(1000, 0.25))
     so, ko, kk = (C.c_int64 * 4)(), (C.c_int64 * 4)(), (C.c_int32 * 3)()
     assert B._lib.compactor_layout(C.byref(p), reqs, 3, so, ko, kk) == 0
@@ -77,7 +77,7 @@ def test_layout_offsets(B):
 def test_argument_errors_are_reported_on_the_host(B):
     global B_mod
     B_mod = B
-    good = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, None)
+    good = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 0, None)
     reqs = (B._Request * 1)(_req())
     nbytes = C.c_size_t(0)
     assert B._lib.compactor_workspace_size(C.byref(good), reqs, 1, C.byref(nbytes)) == 0
@@ -86,13 +86,15 @@ def test_argument_errors_are_reported_on_the_host(B):
     def score(p, r, scores=0x3000, status=0x4000, ws=0x10000, wsb=1 << 40):
         return B._lib.compactor_score(C.byref(p), r, 1, scores, status, ws, wsb, None)
 
-    bad_dim = B._Params(2, 2, 64, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, None)
+    bad_dim = B._Params(2, 2, 64, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 0, None)
     assert score(bad_dim, reqs) == B.EUNSUPPORTED
-    bad_ks = B._Params(2, 2, 128, 40, 0x2000, 0.0, 0.3, 0, 0, 0, 0, None)
+    bad_ks = B._Params(2, 2, 128, 40, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 0, None)
     assert score(bad_ks, reqs) == B.EUNSUPPORTED
-    no_phi = B._Params(2, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, None)
+    no_phi = B._Params(2, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, 0, None)
     assert score(no_phi, reqs) == B.EINVAL
-    neg_ridge = B._Params(2, 2, 128, 48, 0x2000, -1.0, 0.3, 0, 0, 0, 0, None)
+    bad_scope = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 7, None)
+    assert score(bad_scope, reqs) == B.EINVAL
+    neg_ridge = B._Params(2, 2, 128, 48, 0x2000, -1.0, 0.3, 0, 0, 0, 0, 0, None)
     assert score(neg_ridge, reqs) == B.EINVAL
     assert score(good, (B._Request * 1)(_req(ratio=0.0))) == B.EINVAL
     assert score(good, (B._Request * 1)(_req(ratio=1.5))) == B.EINVAL

@@ -24,9 +24,21 @@ def _say(*a):
 
 
 # ------------------------------------------------------------------ select (integer work: exact)
-def _select_case(C, ns, ratios, L, H, maker, seed):
+def _check_layer_selection(C, scores_b, kept, cnt, ko_b, k, b, L, H, n, what):
+    """kept/cnt of request b against the oracle's head-adaptive selection of the same scores."""
+    for l in range(L):
+        want = O.select_topk_layer(scores_b[l * H * n:(l + 1) * H * n].reshape(H, n), H * k)
+        pos = ko_b + l * H * k
+        for h in range(H):
+            c = int(cnt[(b * L + l) * H + h])
+            assert c == len(want[h]), "%s: layer %d head %d keeps %d, oracle %d" % (what, l, h, c, len(want[h]))
+            assert np.array_equal(kept[pos:pos + c], want[h]), "%s: layer %d head %d" % (what, l, h)
+            pos += c
+
+
+def _select_case(C, ns, ratios, L, H, maker, seed, scope=0):
     rng = np.random.default_rng(seed)
-    params = C.Params(L, H, sketch_dim=48)
+    params = C.Params(L, H, sketch_dim=48, select_scope=scope)
     reqs, host_scores = [], []
     for n, r in zip(ns, ratios):
         k = torch.empty(L, H, n, 128, dtype=torch.bfloat16, device=DEV)   # never read by select
@@ -39,6 +51,10 @@ def _select_case(C, ns, ratios, L, H, maker, seed):
     kept, cnt = kept.cpu().numpy(), cnt.cpu().numpy()
     for b, n in enumerate(ns):
         assert kk[b] == O.keep_count(n, ratios[b])
+        if scope == C.SCOPE_LAYER:
+            _check_layer_selection(C, host_scores[b], kept, cnt, ko[b], kk[b], b, L, H, n,
+                                   "layer select: req %d n=%d k=%d" % (b, n, kk[b]))
+            continue
         for g in range(L * H):
             want = O.select_topk(host_scores[b][g * n:(g + 1) * n], kk[b])
             got = kept[ko[b] + g * kk[b]: ko[b] + (g + 1) * kk[b]]
@@ -70,6 +86,79 @@ def test_select_all_equal_and_leverage_like(C):
     _say("select: all-equal scores; tiny positive leverage-like scores")
     _select_case(C, [5000, 131072], [0.37, 0.2], 1, 1, lambda r, m: np.full(m, 0.25), 3)
     _select_case(C, [100000], [0.32], 1, 2, lambda r, m: r.chisquare(48, m) / m, 4)
+
+
+def test_select_across_the_heads_of_a_layer(C):
+    _say("select, layer scope: gaussian scores with per-head spread, ragged batch")
+
+    def spread(r, m):          # heads differ in scale, so their shares of the budget differ
+        return r.standard_normal(m) * np.repeat(r.uniform(0.2, 3.0, 64), (m + 63) // 64)[:m]
+    _select_case(C, [1, 5, 63, 1023, 1024, 4097, 70001], [1.0, 0.5, 0.3, 0.2, 0.999, 0.6, 0.25],
+                 2, 3, spread, 5, scope=C.SCOPE_LAYER)
+    _say("select, layer scope: ties, zeros of both signs, NaN, infinities; all equal")
+
+    def maker(r, m):
+        s = r.integers(-4, 5, m).astype(np.float32) / 8.0
+        s[r.integers(0, m, max(1, m // 50))] = np.nan
+        s[r.integers(0, m, max(1, m // 60))] = -np.inf
+        s[r.integers(0, m, max(1, m // 70))] = np.inf
+        z = np.flatnonzero(s == 0)
+        s[z[::2]] = -0.0
+        return s
+    _select_case(C, [7, 300, 4096, 9000, 33000], [0.5, 0.9, 0.1, 0.45, 0.32], 2, 4, maker, 6,
+                 scope=C.SCOPE_LAYER)
+    _select_case(C, [5000, 40000], [0.37, 0.2], 1, 3, lambda r, m: np.full(m, 0.25), 7,
+                 scope=C.SCOPE_LAYER)
+
+
+def test_layer_scope_compress_end_to_end(C):
+    _say("compress, layer scope: config 2 shape (L=2, H=4, n=3000) and a ragged batch")
+    for w in (W.config2(DEV, L=2, H=4, n=3000), W.config4(DEV, L=1, H=3, n_req=3, n_lo=500, n_hi=2500)):
+        params, reqs = U.make_call(C, w, DEV)
+        params.select_scope = C.SCOPE_LAYER
+        out = C.compactor_compress(params, reqs, want_scores=True)
+        torch.cuda.synchronize()
+        so, ko, kk = C.compactor_layout(params, reqs)
+        L, H = w.layers, w.kv_heads
+        scores = out["scores"].cpu().numpy()
+        kept = out["kept_idx"].cpu().numpy()
+        cnt = out["kept_cnt"].cpu().numpy()
+        phi_np = params.phi.double().cpu().numpy()
+        swaps = 0
+        for b, r in enumerate(w.requests):
+            n, k = r.n, kk[b]
+            sb = scores[so[b]:so[b] + L * H * n]
+            # exact: the library's selection is the oracle's selection of the library's scores
+            _check_layer_selection(C, sb, kept, cnt, ko[b], k, b, L, H, n, "%s req %d" % (w.name, b))
+            for l in range(L):
+                ref = np.stack([U.oracle_head(w, b, l, h, phi_np)[0] for h in range(H)])
+                for h in range(H):
+                    U.check_scores(sb[(l * H + h) * n:(l * H + h + 1) * n], ref[h], "%s req %d l %d h %d" % (w.name, b, l, h))
+                # against the oracle's own scores: differences only next to the layer's threshold
+                want = O.select_topk_layer(ref, H * k)
+                thr = min(ref[h][want[h]].min() for h in range(H) if len(want[h]))
+                pos = ko[b] + l * H * k
+                for h in range(H):
+                    c = int(cnt[(b * L + l) * H + h])
+                    got = kept[pos:pos + c]
+                    diff = np.setxor1d(got, want[h])
+                    swaps += len(diff)
+                    assert np.all(np.abs(ref[h][diff] - thr) <= 2 * (U.RTOL * abs(thr) + U.ATOL))
+                    rows = slice(pos, pos + c)
+                    kp = out["k_packed"][rows].view(torch.int16).cpu().numpy().view(np.uint16)
+                    vp = out["v_packed"][rows].view(torch.int16).cpu().numpy().view(np.uint16)
+                    assert np.array_equal(kp, W.bf16_bits(r.k[l, h])[got])
+                    assert np.array_equal(vp, W.bf16_bits(r.v[l, h])[got])
+                    pos += c
+        _say("  %s: tokens that differ from the oracle's selection (near-threshold): %d" % (w.name, swaps))
+        # the three separate calls give the same bits as the fused call
+        sc, st = C.compactor_score(params, reqs)
+        ki, kc = C.compactor_select(params, reqs, sc)
+        kp, vp = C.compactor_compact(params, reqs, ki, kc)
+        torch.cuda.synchronize()
+        assert torch.equal(ki, out["kept_idx"]) and torch.equal(kc, out["kept_cnt"])
+        assert torch.equal(kp.view(torch.int16), out["k_packed"].view(torch.int16))
+        assert torch.equal(vp.view(torch.int16), out["v_packed"].view(torch.int16))
 
 
 # ------------------------------------------------------------------ compact (byte work: exact)
