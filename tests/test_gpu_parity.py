@@ -409,6 +409,47 @@ def test_config2_full_size_as_benchmarked(C):
     _structure_checks(C, w, out)
 
 
+def test_config2_full_size_layer_scope(C):
+    _say("config 2 at full size, head-adaptive selection across the 8 heads of each layer")
+    w = W.config2(device=DEV)
+    params, reqs = U.make_call(C, w, DEV)
+    params.select_scope = C.SCOPE_LAYER
+    out = C.compactor_compress(params, reqs, want_scores=True)
+    torch.cuda.synchronize()
+    so, ko, kk = C.compactor_layout(params, reqs)
+    L, H, n, k = w.layers, w.kv_heads, w.requests[0].n, kk[0]
+    assert int(out["status"].max()) == 0
+    cnt = out["kept_cnt"].view(L, H)
+    assert torch.all(cnt.sum(dim=1) == H * k) and int(cnt.min()) >= 0
+    s = out["scores"].view(L, H * n)
+    idx = out["kept_idx"].view(L, H * k).long()
+    # flat position (head * n + token) of every retained token, from the ragged per-head counts
+    off = torch.cumsum(cnt, dim=1) - cnt
+    j = torch.arange(H * k, device=DEV).unsqueeze(0).expand(L, -1)
+    head = (j.unsqueeze(-1) >= off.unsqueeze(1)).sum(dim=-1) - 1
+    flat = head * n + idx
+    assert torch.all(flat[:, 1:] > flat[:, :-1])            # heads in order, tokens ascending
+    kept_min = torch.gather(s, 1, flat).min(dim=1).values
+    mask = torch.ones_like(s, dtype=torch.bool).scatter_(1, flat, False)
+    ev_max = torch.where(mask, s, torch.full_like(s, -1.0)).max(dim=1).values
+    assert torch.all(kept_min >= ev_max)                    # one threshold per layer
+    src_k = w.requests[0].k.reshape(L, H * n, 128).view(torch.int16)
+    src_v = w.requests[0].v.reshape(L, H * n, 128).view(torch.int16)
+    sel = flat.unsqueeze(-1).expand(-1, -1, 128)
+    assert torch.equal(out["k_packed"].view(L, H * k, 128).view(torch.int16), torch.gather(src_k, 1, sel))
+    assert torch.equal(out["v_packed"].view(L, H * k, 128).view(torch.int16), torch.gather(src_v, 1, sel))
+    # two layers against the oracle's selection of the same scores: exact, ties included
+    sc, ki, kc = out["scores"].cpu().numpy(), out["kept_idx"].cpu().numpy(), out["kept_cnt"].cpu().numpy()
+    for l in (3, 29):
+        want = O.select_topk_layer(sc[l * H * n:(l + 1) * H * n].reshape(H, n), H * k)
+        pos = l * H * k
+        for h in range(H):
+            c = int(kc[l * H + h])
+            assert c == len(want[h]) and np.array_equal(ki[pos:pos + c], want[h]), (l, h)
+            pos += c
+    _say("  per-head counts of layer 3: %s (uniform would be %d)" % (kc[3 * H:4 * H].tolist(), k))
+
+
 def test_config3_full_length(C):
     _say("config 3 at full length (n = 131072), 4 of 28 layers")
     w = W.config3(device=DEV, L=4)
