@@ -50,6 +50,8 @@ __all__ = [
     "select_topk",
     "select_topk_layer",
     "compact_rows",
+    "compact_rows_paged",
+    "compact_pages_in_place",
     "compress_head",
     "calibration_curve",
     "calibrated_ratio",
@@ -327,6 +329,33 @@ def select_topk_layer(S: np.ndarray, k_total: int):
 def compact_rows(K_cache: np.ndarray, V: np.ndarray, kept: np.ndarray):
     """Packed cache: the retained rows, in ascending token order (bit copies)."""
     return K_cache[kept].copy(), V[kept].copy()
+
+
+def compact_rows_paged(pages: np.ndarray, rows: np.ndarray, kept: np.ndarray,
+                       block_table: np.ndarray) -> None:
+    """Retained rows of one head written into a paged cache (Sec. 3 overview: the
+    compressed cache is the retained key/value pairs; here it lives in fixed-size
+    pages named by a block table, as serving engines store it).
+
+    pages [num_pages, page_size, d] is this head's view of the page pool and is
+    modified in place: retained token j goes to page block_table[j // page_size],
+    slot j % page_size.  Everything else in the pool is left as it was.
+    """
+    ps = pages.shape[1]
+    for j, t in enumerate(kept):
+        pages[block_table[j // ps], j % ps] = rows[t]
+
+
+def compact_pages_in_place(pages: np.ndarray, kept: np.ndarray, block_table: np.ndarray) -> None:
+    """The same when the head's n tokens already live in these pages (token t at page
+    block_table[t // page_size], slot t % page_size): rows move towards the front one
+    after the other, in ascending order, so that a row is read before its slot is
+    reused (kept[j] >= j).  Afterwards the first ceil(len(kept) / page_size) logical
+    pages hold the compressed head and the rest can be released.
+    """
+    ps = pages.shape[1]
+    for j, t in enumerate(kept):
+        pages[block_table[j // ps], j % ps] = pages[block_table[t // ps], t % ps]
 
 
 def compress_head(

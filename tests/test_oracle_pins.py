@@ -460,3 +460,40 @@ def test_select_topk_layer_properties():
     gotp = O.select_topk_layer(S[perm], k_total)
     for j, h in enumerate(perm):
         assert np.array_equal(gotp[j], got[h])
+
+
+# ---------------------------------------------------------------- paged compaction target
+def test_paged_compaction_matches_dense_and_in_place_matches_snapshot():
+    rng = np.random.default_rng(21)
+    n, d, ps = 53, 4, 8
+    rows = rng.integers(0, 1 << 16, size=(n, d)).astype(np.uint16)
+    kept = np.sort(rng.choice(n, size=19, replace=False)).astype(np.int32)
+    npages = 12
+    table = rng.permutation(npages)[: (n + ps - 1) // ps].astype(np.int32)   # scattered pages
+    pool0 = rng.integers(0, 1 << 16, size=(npages, ps, d)).astype(np.uint16)
+    # out of place: reading the pages back in logical order gives the dense packed rows
+    pool = pool0.copy()
+    O.compact_rows_paged(pool, rows, kept, table)
+    dense, _ = O.compact_rows(rows, rows, kept)
+    logical = pool[table].reshape(-1, d)
+    assert np.array_equal(logical[: len(kept)], dense)
+    # nothing else in the pool changed
+    touched = np.zeros((npages, ps), dtype=bool)
+    for j in range(len(kept)):
+        touched[table[j // ps], j % ps] = True
+    assert np.array_equal(pool[~touched], pool0[~touched])
+    # in place: same result as gathering from a snapshot of the pages
+    pool = pool0.copy()
+    for t in range(n):
+        pool[table[t // ps], t % ps] = rows[t]
+    snap = pool.copy()
+    O.compact_pages_in_place(pool, kept, table)
+    assert np.array_equal(pool[table].reshape(-1, d)[: len(kept)], dense)
+    assert np.array_equal(pool[~touched], snap[~touched])
+    # keeping everything moves nothing; keeping the tail moves it to the front
+    pool = snap.copy()
+    O.compact_pages_in_place(pool, np.arange(n, dtype=np.int32), table)
+    assert np.array_equal(pool, snap)
+    pool = snap.copy()
+    O.compact_pages_in_place(pool, np.arange(n - 10, n, dtype=np.int32), table)
+    assert np.array_equal(pool[table].reshape(-1, d)[:10], rows[n - 10:])
