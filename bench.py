@@ -51,6 +51,9 @@ def parse():
                     help="measure compactor_attention_scores (Sec. 3.2 scores a) and the blended "
                          "compress on the same workload instead of the default line")
     ap.add_argument("--q-per-kv", type=int, default=4, help="query heads per kv head for --attention")
+    ap.add_argument("--paged", action="store_true",
+                    help="time the compaction stage with a paged destination (and in place)")
+    ap.add_argument("--page-size", type=int, default=16, help="slots per page for --paged")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--allow-flagged", action="store_true",
                     help="do not fail when a head reports a status flag (kernel experiments only)")
@@ -163,6 +166,70 @@ def attention_mode(a, torch, C, W, w, reqs, params, bufs, dev):
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "dtype": "bf16", "data": "synthetic"}))
 
 
+def paged_mode(a, torch, C, W, w, reqs, params, bufs, dev):
+    """Times the compaction stage alone with a paged destination: dense source into pages, and in
+    place inside the pages, beside the dense gather of the headline path."""
+    ps = a.page_size
+    C.compactor_compress(params, reqs, want_scores=False, **bufs)
+    torch.cuda.synchronize()
+    L, H = w.layers, w.kv_heads
+    need = [(r.n + ps - 1) // ps for r in w.requests]
+    num_pages = sum(need)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(5)
+    perm = torch.randperm(num_pages, generator=g).to(torch.int32).to(dev)   # scattered pages
+    tables, at = [], 0
+    for m in need:
+        tables.append(perm[at:at + m].contiguous())
+        at += m
+    # one [pages, slot, head, d] pool per layer, seen as [page, layer, slot, head, d]
+    kpool = torch.empty(L, num_pages, ps, H, 128, dtype=torch.bfloat16, device=dev)
+    vpool = torch.empty_like(kpool)
+    kview, vview = kpool.permute(1, 0, 2, 3, 4), vpool.permute(1, 0, 2, 3, 4)
+
+    def fill():          # token t of every head at logical slot t
+        for b, r in enumerate(w.requests):
+            t = torch.arange(r.n, device=dev)
+            pg, sl = tables[b].long()[t // ps], t % ps
+            kview[pg, :, sl] = r.k.permute(2, 0, 1, 3)
+            vview[pg, :, sl] = r.v.permute(2, 0, 1, 3)
+
+    def timed(fn, before=None):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ms = []
+        for i in range(a.warmup + a.steps):
+            if before:
+                before()
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            if i >= a.warmup:
+                ms.append(e0.elapsed_time(e1))
+        return sum(ms) / len(ms)
+
+    ki, kc = bufs["kept_idx"], bufs["kept_cnt"]
+    ms_dense = timed(lambda: C.compactor_compact(params, reqs, ki, kc, bufs["k_packed"], bufs["v_packed"]))
+    ms_paged = timed(lambda: C.compactor_compact_paged(params, reqs, ki, kc, kview, vview, tables))
+    steps = min(a.steps, 5)          # the refill is slow host-driven indexing
+    a.steps, a.warmup = steps, 1
+    ms_inplace = timed(lambda: C.compactor_compact_paged(params, reqs, ki, kc, kview, vview, tables,
+                                                         in_place=True), before=fill)
+    kept_rows = sum(L * H * C.compactor_keep_count(r.n, r.ratio) for r in w.requests)
+    nbytes = 1028.0 * kept_rows
+    print(json.dumps({
+        "metric": "compaction stage with a paged destination at 1 GPU",
+        "config": {"workload": w.name, "page_size": ps, "pages": num_pages, "kept_head_rows": kept_rows,
+                   "select_scope": a.scope},
+        "dense_ms": ms_dense, "dense_GB/s": nbytes / ms_dense / 1e6,
+        "paged_ms": ms_paged, "paged_GB/s": nbytes / ms_paged / 1e6,
+        "in_place_ms": ms_inplace, "in_place_GB/s": nbytes / ms_inplace / 1e6,
+        "frac_of_8TB/s": {"dense": nbytes / ms_dense / 1e6 / HBM_PEAK_GBS,
+                          "paged": nbytes / ms_paged / 1e6 / HBM_PEAK_GBS,
+                          "in_place": nbytes / ms_inplace / 1e6 / HBM_PEAK_GBS},
+        "n_gpus": 1, "dtype": "bf16", "data": "synthetic"}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -205,6 +272,9 @@ def main():
 
     if a.attention:
         attention_mode(a, torch, C, W, w, reqs, params, bufs, dev)
+        return
+    if a.paged:
+        paged_mode(a, torch, C, W, w, reqs, params, bufs, dev)
         return
 
     if a.calibrate_copy:

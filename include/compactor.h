@@ -191,6 +191,43 @@ int compactor_compact(const compactor_params_t *p, const compactor_request_t *re
                       const int32_t *kept_idx, const int32_t *kept_cnt,
                       void *k_packed, void *v_packed, void *stream);
 
+/* ---- paged cache as the compaction target ------------------------------------------------- */
+/* Serving engines keep the cache in fixed-size pages named by a block table per context; the
+ * compressed cache (Sec. 3: the retained key/value pairs) can be written there directly, or an
+ * existing paged cache can be compacted in place so that its tail pages can be released. */
+typedef struct compactor_page_pool {
+  void *k_pages;          /* device, bf16.  Element (page p, layer l, kv head h, slot s, channel c) */
+  void *v_pages;          /* is at p*page_stride + l*layer_stride + h*head_stride + s*slot_stride + c */
+  int64_t page_stride, layer_stride, head_stride, slot_stride;   /* elements, multiples of 8;
+                             slot_stride >= head_dim.  E.g. a [pages, page_size, H, d] pool per
+                             layer has slot_stride = H*d, head_stride = d. */
+  int32_t page_size;      /* slots (tokens) per page, >= 1 */
+  int32_t num_pages;      /* pages in the pool; a table entry outside [0, num_pages) is skipped */
+} compactor_page_pool_t;
+
+typedef struct compactor_page_table {
+  const int32_t *pages;   /* device, int32 [len]: physical page of logical page i of this context.
+                             The pages of one context must be distinct. */
+  int32_t len;
+} compactor_page_table_t;
+
+/* compactor_compact with a paged destination: retained token j of head (l,h) of request b goes to
+ * logical slot j of that head, i.e. page tables[b].pages[j / page_size], slot j % page_size
+ * (in layer scope j counts inside the head: 0 .. kept_cnt-1).  Slots that receive no row keep
+ * their contents.  tables: host array of nreq entries.
+ * in_place = 0: rows are read from the requests' k_cache / v_cache tensors as in compactor_compact.
+ * in_place = 1: rows are read from the pool itself, token t of a head at logical slot t (the
+ *   requests' tensors are not used and may be NULL); afterwards the first ceil(count / page_size)
+ *   logical pages hold the head and the others can be released.  kept_idx must be ascending
+ *   per head (as compactor_select writes it); an entry below its own rank is skipped.
+ * tables[b].len must cover ceil(rows / page_size) logical pages, rows = n_b when in place, else
+ * k_keep_b (layer scope: min(n_b, H*k_keep_b), since one head may take the whole budget).
+ * For callers whose cache is paged; no part of the paper. */
+int compactor_compact_paged(const compactor_params_t *p, const compactor_request_t *reqs,
+                            int32_t nreq, const int32_t *kept_idx, const int32_t *kept_cnt,
+                            const compactor_page_pool_t *pool, const compactor_page_table_t *tables,
+                            int32_t in_place, void *stream);
+
 /* score -> select -> compact on one stream, with no host synchronisation in between.
  * scores may be NULL (they then live in the workspace only). */
 int compactor_compress(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,

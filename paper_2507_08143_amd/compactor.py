@@ -56,6 +56,17 @@ class _AttnParams(C.Structure):
                 ("scale", C.c_float)]
 
 
+class _PagePool(C.Structure):
+    _fields_ = [("k_pages", C.c_void_p), ("v_pages", C.c_void_p),
+                ("page_stride", C.c_int64), ("layer_stride", C.c_int64),
+                ("head_stride", C.c_int64), ("slot_stride", C.c_int64),
+                ("page_size", C.c_int32), ("num_pages", C.c_int32)]
+
+
+class _PageTable(C.Structure):
+    _fields_ = [("pages", C.c_void_p), ("len", C.c_int32)]
+
+
 _PP, _RP = C.POINTER(_Params), C.POINTER(_Request)
 _APP, _ARP = C.POINTER(_AttnParams), C.POINTER(_AttnRequest)
 _lib.compactor_attention_workspace_size.argtypes = [_APP, _ARP, C.c_int32, C.POINTER(C.c_size_t)]
@@ -74,6 +85,9 @@ _lib.compactor_select.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p, C
                                   C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.compactor_compact.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_void_p]
+_lib.compactor_compact_paged.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p,
+                                         C.POINTER(_PagePool), C.POINTER(_PageTable), C.c_int32,
+                                         C.c_void_p]
 _lib.compactor_compress.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                     C.c_void_p]
@@ -85,7 +99,7 @@ _lib.compactor_version.restype = C.c_char_p
 
 EXPORTS = ["compactor_default_params", "compactor_keep_count", "compactor_layout",
            "compactor_workspace_size", "compactor_score", "compactor_select",
-           "compactor_compact", "compactor_compress", "compactor_calibrated_ratio",
+           "compactor_compact", "compactor_compact_paged", "compactor_compress", "compactor_calibrated_ratio",
            "compactor_error_string", "compactor_version",
            "compactor_attention_workspace_size", "compactor_attention_scores"]
 
@@ -303,6 +317,25 @@ def compactor_compact(params: Params, reqs: Sequence[Request], kept_idx: torch.T
     _check(_lib.compactor_compact(pp, arr, n, _ptr(kept_idx), _ptr(kept_cnt), _ptr(k_packed),
                                   _ptr(v_packed), _stream(stream)))
     return k_packed, v_packed
+
+
+def compactor_compact_paged(params: Params, reqs: Sequence[Request], kept_idx: torch.Tensor,
+                            kept_cnt: torch.Tensor, k_pages: torch.Tensor, v_pages: torch.Tensor,
+                            tables: Sequence[torch.Tensor], in_place: bool = False, stream=None):
+    """Retained rows into a paged cache.  k_pages / v_pages: bf16 views indexed
+    [page, layer, slot, head, channel] (any strides, channel contiguous, the same for both);
+    tables[b]: int32 device tensor, physical page of each logical page of request b."""
+    assert k_pages.dtype == torch.bfloat16 and v_pages.dtype == torch.bfloat16
+    assert k_pages.dim() == 5 and k_pages.stride(4) == 1 and v_pages.stride() == k_pages.stride()
+    pool = _PagePool(k_pages.data_ptr(), v_pages.data_ptr(), k_pages.stride(0), k_pages.stride(1),
+                     k_pages.stride(3), k_pages.stride(2), k_pages.shape[2], k_pages.shape[0])
+    for t in tables:
+        assert t.dtype == torch.int32 and t.is_contiguous()
+    tabs = (_PageTable * len(tables))(*[_PageTable(t.data_ptr(), t.numel()) for t in tables])
+    pp, arr, n = _marshal(params, reqs)
+    assert len(tables) == n
+    _check(_lib.compactor_compact_paged(pp, arr, n, _ptr(kept_idx), _ptr(kept_cnt), C.byref(pool),
+                                        tabs, 1 if in_place else 0, _stream(stream)))
 
 
 def compactor_compress(params: Params, reqs: Sequence[Request], want_scores: bool = False,

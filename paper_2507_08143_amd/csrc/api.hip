@@ -160,7 +160,7 @@ int for_each_group(const compactor_params_t *p, const compactor_request_t *reqs,
       s.kept_off = kept_off;
       s.n = r.n; s.k_keep = kk;
       s.head_begin = h; s.head_count = take;
-      s.ghead0 = b * LH; s.lhead0 = T.nheads; s.H = p->kv_heads;
+      s.ghead0 = b * LH; s.lhead0 = T.nheads; s.H = p->kv_heads; s.req = b;
       T.nheads += take;
       rows += (long long)take * r.n;
       local_off += (long long)take * r.n;
@@ -484,6 +484,52 @@ int compactor_compact(const compactor_params_t *p, const compactor_request_t *re
   return for_each_group(p, reqs, nreq, 1ll << 60, false, [&](const SegTable &T, long long) {
     HIP_TRY(launch_gather(T, kept_idx, kept_cnt, static_cast<uint16_t *>(k_packed),
                           static_cast<uint16_t *>(v_packed), st));
+    return COMPACTOR_OK;
+  });
+}
+
+int compactor_compact_paged(const compactor_params_t *p, const compactor_request_t *reqs,
+                            int32_t nreq, const int32_t *kept_idx, const int32_t *kept_cnt,
+                            const compactor_page_pool_t *pool, const compactor_page_table_t *tables,
+                            int32_t in_place, void *stream) {
+  int rc = check_params(p, false);
+  if (rc) return rc;
+  rc = check_requests(reqs, nreq, in_place ? 0 : NEED_PACK);
+  if (rc) return rc;
+  rc = check_scope(p, reqs, nreq);
+  if (rc) return rc;
+  if (!kept_idx || !kept_cnt || !pool || !tables) return COMPACTOR_EINVAL;
+  if (!pool->k_pages || !pool->v_pages || pool->page_size < 1 || pool->num_pages < 1)
+    return COMPACTOR_EINVAL;
+  if (pool->page_stride < 0 || pool->layer_stride < 0 || pool->head_stride < 0 ||
+      pool->slot_stride < D)
+    return COMPACTOR_EINVAL;
+  if (!aligned16(pool->k_pages) || !aligned16(pool->v_pages) ||
+      ((pool->page_stride | pool->layer_stride | pool->head_stride | pool->slot_stride) & 7))
+    return COMPACTOR_EALIGN;
+  for (int b = 0; b < nreq; ++b) {
+    // logical pages a head can need: all its tokens when they are read from the pages, else
+    // what it can retain (in layer scope one head may take the whole layer's budget)
+    const long long kk = compactor_keep_count(reqs[b].n, reqs[b].ratio);
+    long long rows = p->select_scope == COMPACTOR_SCOPE_LAYER ? kk * p->kv_heads : kk;
+    if (rows > reqs[b].n || in_place) rows = reqs[b].n;
+    if (!tables[b].pages || tables[b].len < (rows + pool->page_size - 1) / pool->page_size)
+      return COMPACTOR_EINVAL;
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return for_each_group(p, reqs, nreq, 1ll << 60, false, [&](const SegTable &T, long long) {
+    PagePool P;
+    memset(&P, 0, sizeof(P));
+    P.k = static_cast<uint16_t *>(pool->k_pages);
+    P.v = static_cast<uint16_t *>(pool->v_pages);
+    P.page_stride = pool->page_stride; P.layer_stride = pool->layer_stride;
+    P.head_stride = pool->head_stride; P.slot_stride = pool->slot_stride;
+    P.page_size = pool->page_size; P.num_pages = pool->num_pages;
+    for (int i = 0; i < T.nseg; ++i) {
+      P.t[i].pages = tables[T.s[i].req].pages;
+      P.t[i].len = tables[T.s[i].req].len;
+    }
+    HIP_TRY(launch_gather_paged(T, P, kept_idx, kept_cnt, in_place != 0, st));
     return COMPACTOR_OK;
   });
 }

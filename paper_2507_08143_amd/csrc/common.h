@@ -42,7 +42,7 @@ struct Seg {
   int ghead0;            // global index of the request's head 0 (status / kept_cnt)
   int lhead0;            // launch-local index of this segment's first head (workspace arrays)
   int H;                 // kv heads per layer
-  int pad_;
+  int req;               // index of the request in the call
 };
 
 struct SegTable {
@@ -300,6 +300,22 @@ hipError_t launch_select_pools(const SegTable &T, const float *scores, int *hist
 // kept_cnt is read in layer scope only (ragged heads inside a layer's region).
 hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, const int32_t *kept_cnt,
                          uint16_t *k_packed, uint16_t *v_packed, hipStream_t st);
+
+// A paged destination (or source and destination) for the retained rows: a pool of fixed-size
+// pages addressed through one block table per request.
+struct PageTab {
+  const int32_t *pages;   // physical page of each logical page of the segment's request
+  int len, pad_;
+};
+struct PagePool {
+  uint16_t *k, *v;
+  long long page_stride, layer_stride, head_stride, slot_stride;   // elements
+  int page_size, num_pages;
+  PageTab t[MAX_SEG];     // by segment of the launch
+};
+// in_place: the rows are read from the pages themselves (token t at logical slot t).
+hipError_t launch_gather_paged(const SegTable &T, const PagePool &P, const int32_t *kept_idx,
+                               const int32_t *kept_cnt, bool in_place, hipStream_t st);
 
 // Total workgroups of a launch whose blocks-per-head rule is (per_block, by_keep).
 inline long long total_blocks(const SegTable &T, int per_block, int step, bool by_keep) {

@@ -118,6 +118,157 @@ __global__ __launch_bounds__(256) void gather_layer_kernel(const SegTable T,
   }
 }
 
+// ---- paged cache as the target (and, in place, the source) ----------------------------------
+// Element offset of (logical slot j, layer l, head h) of a segment's request in the page pool,
+// or -1 when the block table does not cover it or names a page outside the pool.
+__device__ __forceinline__ long long page_slot(const PagePool &P, int seg, int l, int h, int j) {
+  const int lp = j / P.page_size, slot = j - lp * P.page_size;
+  if (lp >= P.t[seg].len) return -1;
+  const int pg = P.t[seg].pages[lp];
+  if (pg < 0 || pg >= P.num_pages) return -1;
+  return (long long)pg * P.page_stride + (long long)l * P.layer_stride +
+         (long long)h * P.head_stride + (long long)slot * P.slot_stride;
+}
+
+// Retained rows from the dense source tensors into pages: retained token j of a head goes to
+// logical slot j of that head.  Workgroups are dealt as in the dense gathers (64 rows each).
+__global__ __launch_bounds__(256) void gather_paged_kernel(const SegTable T, const PagePool P,
+                                                           const int32_t *__restrict__ kept_idx,
+                                                           const int32_t *__restrict__ kept_cnt) {
+  int seg = 0, head0 = 0, tile = 0, rows = 0;       // head0: the head, or the layer's first head
+  if (T.layer_scope) {
+    int base = 0;
+    for (int i = 0; i < T.nseg; ++i) {
+      const int bpl = (T.s[i].H * T.s[i].k_keep + GATHER_ROWS - 1) / GATHER_ROWS;
+      const int nb = bpl * (T.s[i].head_count / T.s[i].H);
+      if ((int)blockIdx.x < base + nb || i == T.nseg - 1) {
+        const int local = blockIdx.x - base, layer = local / bpl;
+        seg = i;
+        head0 = T.s[i].head_begin + layer * T.s[i].H;
+        tile = local - layer * bpl;
+        rows = T.s[i].H * T.s[i].k_keep;
+        break;
+      }
+      base += nb;
+    }
+  } else {
+    const Where w = locate_block(T, blockIdx.x, GATHER_ROWS, GATHER_ROWS, true);
+    seg = w.seg; head0 = w.head; tile = w.tile; rows = T.s[w.seg].k_keep;
+  }
+  const Seg &s = T.s[seg];
+  const int32_t *idx = kept_idx + (s.kept_off + (long long)head0 * s.k_keep);
+  const int32_t *cnt = kept_cnt + s.ghead0 + head0;
+  const int chunk = threadIdx.x & 15, sub = threadIdx.x >> 4;
+  const int layer = head0 / s.H;
+
+  uint4 kv[GATHER_ROWS / 16], vv[GATHER_ROWS / 16];
+  long long dst[GATHER_ROWS / 16];
+#pragma unroll
+  for (int p = 0; p < GATHER_ROWS / 16; ++p) {
+    const int j = tile * GATHER_ROWS + p * 16 + sub;
+    dst[p] = -1;
+    if (j < rows) {
+      int head = head0, jh = j;                      // head of the row and its rank in that head
+      if (T.layer_scope) {
+        head = -1;
+        int run = 0;
+        for (int hh = 0; hh < s.H; ++hh) {
+          const int c = cnt[hh];
+          if (j < run + c) { head = head0 + hh; jh = j - run; break; }
+          run += c;
+        }
+      }
+      const int tok = idx[j];
+      if (head >= 0 && tok >= 0 && tok < s.n) {
+        const long long off = (long long)tok * s.stride_t + chunk * 8;
+        kv[p] = load_stream16(head_ptr(s.k_cache ? s.k_cache : s.k_score, s, head) + off);
+        vv[p] = load_stream16(head_ptr(s.v_cache, s, head) + off);
+        dst[p] = page_slot(P, seg, layer, head - layer * s.H, jh);
+      }
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < GATHER_ROWS / 16; ++p) {
+    if (dst[p] >= 0) {
+      store_stream16(P.k + dst[p] + chunk * 8, kv[p]);
+      store_stream16(P.v + dst[p] + chunk * 8, vv[p]);
+    }
+  }
+}
+
+// In place: a head's tokens already live in the pages (token t at logical slot t) and its
+// retained rows move to the front.  One workgroup per head walks the retained list in ascending
+// runs of 128 rows: all rows of a run are read, the workgroup meets, the run is written.  A run's
+// sources lie at or behind its own destinations and strictly behind those of earlier runs
+// (kept[j] >= j, ascending), so nothing is overwritten before it has been read.
+constexpr int INPLACE_THREADS = 1024, INPLACE_RUN = 128;
+__global__ __launch_bounds__(INPLACE_THREADS) void compact_inplace_kernel(
+    const SegTable T, const PagePool P, const int32_t *__restrict__ kept_idx,
+    const int32_t *__restrict__ kept_cnt) {
+  const Where w = locate_block(T, blockIdx.x, 0, 1, false);      // one block per head
+  const Seg &s = T.s[w.seg];
+  const int layer = w.head / s.H, h = w.head - layer * s.H;
+  int rows = s.k_keep;
+  long long first = s.kept_off + (long long)w.head * s.k_keep;
+  if (T.layer_scope) {                  // ragged: this head's rows follow those of heads 0..h-1
+    const int32_t *cnt = kept_cnt + s.ghead0 + layer * s.H;
+    first = s.kept_off + (long long)layer * s.H * s.k_keep;
+    for (int hh = 0; hh < h; ++hh) first += cnt[hh];
+    rows = cnt[h];
+  }
+  const int32_t *idx = kept_idx + first;
+  const int chunk = threadIdx.x & 15, sub = threadIdx.x >> 4;    // 64 rows per pass
+  for (int base = 0; base < rows; base += INPLACE_RUN) {
+    uint4 kv[INPLACE_RUN / 64], vv[INPLACE_RUN / 64];
+    long long dst[INPLACE_RUN / 64];
+#pragma unroll
+    for (int p = 0; p < INPLACE_RUN / 64; ++p) {
+      const int j = base + p * 64 + sub;
+      dst[p] = -1;
+      if (j < rows) {
+        const int tok = idx[j];
+        const long long src = (tok >= j && tok < s.n) ? page_slot(P, w.seg, layer, h, tok) : -1;
+        if (src >= 0) {
+          kv[p] = *reinterpret_cast<const uint4 *>(P.k + src + chunk * 8);
+          vv[p] = *reinterpret_cast<const uint4 *>(P.v + src + chunk * 8);
+          dst[p] = tok == j ? -1 : page_slot(P, w.seg, layer, h, j);   // already in place
+        }
+      }
+    }
+    __syncthreads();      // every row of the run has been read (the barrier waits for the loads)
+#pragma unroll
+    for (int p = 0; p < INPLACE_RUN / 64; ++p) {
+      if (dst[p] >= 0) {
+        *reinterpret_cast<uint4 *>(P.k + dst[p] + chunk * 8) = kv[p];
+        *reinterpret_cast<uint4 *>(P.v + dst[p] + chunk * 8) = vv[p];
+      }
+    }
+  }
+}
+
+hipError_t launch_gather_paged(const SegTable &T, const PagePool &P, const int32_t *kept_idx,
+                               const int32_t *kept_cnt, bool in_place, hipStream_t st) {
+  if (T.nheads <= 0) return hipSuccess;
+  if (in_place) {
+    hipLaunchKernelGGL(compact_inplace_kernel, dim3((unsigned)T.nheads), dim3(INPLACE_THREADS), 0,
+                       st, T, P, kept_idx, kept_cnt);
+    return hipGetLastError();
+  }
+  long long nb = 0;
+  if (T.layer_scope) {
+    for (int i = 0; i < T.nseg; ++i)
+      nb += (long long)((T.s[i].H * (long long)T.s[i].k_keep + GATHER_ROWS - 1) / GATHER_ROWS) *
+            (T.s[i].head_count / T.s[i].H);
+  } else {
+    nb = total_blocks(T, GATHER_ROWS, GATHER_ROWS, true);
+  }
+  if (nb <= 0) return hipSuccess;
+  if (nb > 0x7fffffffll) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gather_paged_kernel, dim3((unsigned)nb), dim3(256), 0, st, T, P, kept_idx,
+                     kept_cnt);
+  return hipGetLastError();
+}
+
 hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, const int32_t *kept_cnt,
                          uint16_t *k_packed, uint16_t *v_packed, hipStream_t st) {
   if (T.layer_scope) {

@@ -531,3 +531,85 @@ def test_attention_error_codes(C):
     with pytest.raises(C.CompactorError) as e:
         C.compactor_attention_scores(C.AttnParams(1, 1, 3, chunk=128), [C.AttnRequest(q, k)])
     assert e.value.code == C.EUNSUPPORTED
+
+
+# ------------------------------------------------------------------ paged compaction target
+def _paged_case(C, w, scope, page_size, in_place, seed):
+    """Selection by the library, then compaction into pages (or inside them) against the oracle
+    replaying the same kept lists: byte work, compared over the whole pool."""
+    rng = np.random.default_rng(seed)
+    params, reqs = U.make_call(C, w, DEV)
+    params.select_scope = scope
+    out = C.compactor_compress(params, reqs, want_scores=False)
+    torch.cuda.synchronize()
+    so, ko, kk = C.compactor_layout(params, reqs)
+    L, H = w.layers, w.kv_heads
+    need = [(r.n + page_size - 1) // page_size for r in w.requests]     # enough for either mode
+    num_pages = sum(need) + 5
+    perm = rng.permutation(num_pages).astype(np.int32)                  # scattered, disjoint
+    tables_np, at = [], 0
+    for m in need:
+        tables_np.append(perm[at:at + m].copy())
+        at += m
+    tables = [torch.from_numpy(t).to(DEV) for t in tables_np]
+    # storage order [page, slot, layer, head, d], seen as [page, layer, slot, head, d]
+    shape = (num_pages, page_size, L, H, 128)
+    kpool = torch.randint(-30000, 30000, shape, dtype=torch.int16, device=DEV).view(torch.bfloat16)
+    vpool = torch.randint(-30000, 30000, shape, dtype=torch.int16, device=DEV).view(torch.bfloat16)
+    kview, vview = kpool.permute(0, 2, 1, 3, 4), vpool.permute(0, 2, 1, 3, 4)
+    if in_place:      # the cache already lives in the pages: token t at logical slot t
+        for b, r in enumerate(w.requests):
+            t = torch.arange(r.n, device=DEV)
+            pg, sl = tables[b].long()[t // page_size], t % page_size
+            kview[pg, :, sl] = r.k.permute(2, 0, 1, 3)
+            vview[pg, :, sl] = r.v.permute(2, 0, 1, 3)
+    k_ref = kview.contiguous().view(torch.int16).cpu().numpy().view(np.uint16).copy()
+    v_ref = vview.contiguous().view(torch.int16).cpu().numpy().view(np.uint16).copy()
+    C.compactor_compact_paged(params, reqs, out["kept_idx"], out["kept_cnt"], kview, vview, tables,
+                              in_place=in_place)
+    torch.cuda.synchronize()
+    kept, cnt = out["kept_idx"].cpu().numpy(), out["kept_cnt"].cpu().numpy()
+    for b, r in enumerate(w.requests):
+        k = kk[b]
+        for l in range(L):
+            pos = ko[b] + l * H * k
+            for h in range(H):
+                c = int(cnt[(b * L + l) * H + h])
+                assert scope == C.SCOPE_LAYER or c == k
+                mine = kept[pos:pos + c]
+                pos += c
+                for ref, src in ((k_ref, r.k), (v_ref, r.v)):
+                    if in_place:
+                        O.compact_pages_in_place(ref[:, l, :, h, :], mine, tables_np[b])
+                    else:
+                        O.compact_rows_paged(ref[:, l, :, h, :], W.bf16_bits(src[l, h]), mine, tables_np[b])
+    got_k = kview.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    got_v = vview.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got_k, k_ref), "paged K differs (scope %d, in_place %s)" % (scope, in_place)
+    assert np.array_equal(got_v, v_ref), "paged V differs (scope %d, in_place %s)" % (scope, in_place)
+
+
+@pytest.mark.parametrize("in_place", [False, True])
+def test_compact_into_pages(C, in_place):
+    _say("paged target, in_place=%s: head scope and layer scope, ragged batch, page sizes 16 and 7" % in_place)
+    _paged_case(C, W.config2(DEV, L=2, H=3, n=1000), C.SCOPE_HEAD, 16, in_place, 31)
+    _paged_case(C, W.config4(DEV, L=2, H=2, n_req=3, n_lo=100, n_hi=700), C.SCOPE_HEAD, 7, in_place, 32)
+    _paged_case(C, W.config2(DEV, L=1, H=4, n=777), C.SCOPE_LAYER, 16, in_place, 33)
+    _paged_case(C, W.config1(DEV, L=1, H=1, n=5000, ratio=1.0), C.SCOPE_HEAD, 256, in_place, 34)
+
+
+def test_compact_into_pages_error_codes(C):
+    w = W.config2(DEV, L=1, H=2, n=300)
+    params, reqs = U.make_call(C, w, DEV)
+    out = C.compactor_compress(params, reqs)
+    pool = torch.zeros(8, 1, 16, 2, 128, dtype=torch.bfloat16, device=DEV)
+    short = [torch.arange(2, dtype=torch.int32, device=DEV)]      # 90 rows need 6 pages of 16
+    with pytest.raises(C.CompactorError) as e:
+        C.compactor_compact_paged(params, reqs, out["kept_idx"], out["kept_cnt"], pool, pool.clone(), short)
+    assert e.value.code == C.EINVAL
+    # a table naming a page outside the pool is skipped, not followed
+    bad = [torch.tensor([0, 1, 99, 3, 4, 5], dtype=torch.int32, device=DEV)]
+    vp = pool.clone()
+    C.compactor_compact_paged(params, reqs, out["kept_idx"], out["kept_cnt"], pool, vp, bad)
+    torch.cuda.synchronize()
+    assert float(pool[2].abs().sum()) == 0.0 and float(pool[0].abs().sum()) > 0.0
