@@ -41,6 +41,8 @@ __all__ = [
     "approx_leverage_ridge",
     "approx_leverage_qr",
     "approx_leverage_eig",
+    "hadamard",
+    "srht_phi",
     "attention_scores_raw",
     "mean_pool",
     "attention_scores",
@@ -186,6 +188,29 @@ def approx_leverage_eig(K: np.ndarray, Phi: np.ndarray, eps: float = 1e-6) -> np
     lam = np.maximum(lam, eps)
     U = (K_hat @ V) / np.sqrt(lam)
     return np.sum(U * U, axis=1)
+
+
+def hadamard(d: int) -> np.ndarray:
+    """Walsh-Hadamard matrix of order d (a power of two), entries +-1, by Sylvester's
+    doubling H_2m = [[H_m, H_m], [H_m, -H_m]]."""
+    assert d >= 1 and d & (d - 1) == 0
+    H = np.ones((1, 1))
+    while H.shape[0] < d:
+        H = np.block([[H, H], [H, -H]])
+    return H
+
+
+def srht_phi(d: int, k_s: int, signs: np.ndarray, cols: np.ndarray) -> np.ndarray:
+    """Subsampled randomized Hadamard right-sketch (App. D): sqrt(d/k) R H D with D the
+    diagonal of Rademacher signs, H the +-1 Walsh-Hadamard matrix and R the choice of k_s
+    of its d rows, transposed into the d x k_s matrix that multiplies keys from the right:
+    Phi[i, j] = sqrt(d/k_s) * D_i * H[cols[j], i].
+
+    signs: d entries, nonzero = -1.  cols: k_s distinct indices in [0, d).
+    """
+    D = np.where(np.asarray(signs) != 0, -1.0, 1.0)
+    H = hadamard(d)
+    return math.sqrt(d / k_s) * (H[np.asarray(cols)] * D[None, :]).T
 
 
 # --------------------------------------------------------------------------

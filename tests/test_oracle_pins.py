@@ -497,3 +497,31 @@ def test_paged_compaction_matches_dense_and_in_place_matches_snapshot():
     pool = snap.copy()
     O.compact_pages_in_place(pool, np.arange(n - 10, n, dtype=np.int32), table)
     assert np.array_equal(pool[table].reshape(-1, d)[:10], rows[n - 10:])
+
+
+# ---------------------------------------------------------------- SRHT right-sketch (App. D)
+def test_srht_sketch_structure_and_scores():
+    rng = np.random.default_rng(41)
+    d, ks = 128, 48
+    H = O.hadamard(d)
+    assert np.array_equal(H, H.T) and np.array_equal(H @ H, d * np.eye(d))
+    # entry (i, j) is the parity of the common bits of i and j
+    i, j = np.meshgrid(np.arange(d), np.arange(d), indexing="ij")
+    par = np.zeros((d, d), dtype=np.int64)
+    for b in range(7):
+        par ^= ((i >> b) & (j >> b) & 1)
+    assert np.array_equal(H, 1.0 - 2.0 * par)
+    signs = rng.integers(0, 2, d)
+    cols = rng.choice(d, ks, replace=False)
+    Phi = O.srht_phi(d, ks, signs, cols)
+    assert Phi.shape == (d, ks) and np.allclose(np.abs(Phi), math.sqrt(d / ks))
+    # orthogonal columns of squared norm d^2/k: K Phi keeps squared row norms in expectation
+    np.testing.assert_allclose(Phi.T @ Phi, (d * d / ks) * np.eye(ks), atol=1e-9)
+    assert np.array_equal(np.sign(Phi[:, 0]), np.where(signs != 0, -1.0, 1.0) * H[cols[0]])
+    # with all d columns the sketch is invertible: sketched scores are the exact ones
+    K = rng.standard_normal((300, d))
+    full = O.srht_phi(d, d, signs, rng.permutation(d))
+    np.testing.assert_allclose(O.approx_leverage_alg1(K, full), O.leverage_svd(K), atol=1e-9)
+    # and a k_s-column SRHT is an admissible sketch: scores in [0, 1], sum k_s, below the exact ones
+    o = O.approx_leverage_alg1(K, Phi)
+    assert o.min() >= -1e-12 and abs(o.sum() - ks) < 1e-8 and np.all(o <= O.leverage_svd(K) + 1e-9)
