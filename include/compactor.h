@@ -151,6 +151,17 @@ int32_t compactor_keep_count(int32_t n, float ratio);
 int compactor_layout(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
                      int64_t *score_off, int64_t *kept_off, int32_t *k_keep);
 
+/* Fills phi with the subsampled randomized Hadamard right-sketch of App. D,
+ * Phi = (sqrt(d/k_s) R H D)^T: phi[i*k_s + j] = sqrt(d/k_s) * (signs[i] ? -1 : +1) * H[cols[j]][i],
+ * H the +-1 Walsh-Hadamard matrix of order d = 128 (H[a][b] = (-1)^popcount(a & b)).  An
+ * alternative to a Gaussian phi for compactor_params_t.phi; the random choices are the caller's.
+ *   signs  host, uint8 [128]: the Rademacher diagonal D (nonzero = -1)
+ *   cols   host, int32 [k_s]: the k_s rows of H that R selects, distinct, in [0, 128)
+ *   phi    device, fp32 [128, k_s], written on `stream`
+ * k_s in {16, 32, 48, 64}.  The host arrays are consumed before the call returns. */
+int compactor_srht_phi(int32_t sketch_dim, const uint8_t *signs, const int32_t *cols, float *phi,
+                       void *stream);
+
 /* Bytes of device workspace that score / select / compress need for this batch. host.
  * The workspace must be 256-byte aligned; its contents are scratch (no state is kept
  * between calls). */

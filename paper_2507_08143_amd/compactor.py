@@ -78,6 +78,7 @@ _lib.compactor_keep_count.argtypes = [C.c_int32, C.c_float]
 _lib.compactor_keep_count.restype = C.c_int32
 _lib.compactor_layout.argtypes = [_PP, _RP, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                   C.POINTER(C.c_int32)]
+_lib.compactor_srht_phi.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.compactor_workspace_size.argtypes = [_PP, _RP, C.c_int32, C.POINTER(C.c_size_t)]
 _lib.compactor_score.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_size_t, C.c_void_p]
@@ -98,7 +99,7 @@ _lib.compactor_error_string.restype = C.c_char_p
 _lib.compactor_version.restype = C.c_char_p
 
 EXPORTS = ["compactor_default_params", "compactor_keep_count", "compactor_layout",
-           "compactor_workspace_size", "compactor_score", "compactor_select",
+           "compactor_workspace_size", "compactor_srht_phi", "compactor_score", "compactor_select",
            "compactor_compact", "compactor_compact_paged", "compactor_compress", "compactor_calibrated_ratio",
            "compactor_error_string", "compactor_version",
            "compactor_attention_workspace_size", "compactor_attention_scores"]
@@ -246,6 +247,18 @@ def compactor_default_params(layers: int, kv_heads: int) -> Params:
     return Params(p.layers, p.kv_heads, p.sketch_dim, None, p.ridge_rel, p.lambda_blend,
                   p.group_bytes, p.head_dim, None, p.gram_wgs, p.score_tokens, p.streams,
                   p.select_scope)
+
+
+def compactor_srht_phi(sketch_dim: int, signs, cols, device, stream=None) -> torch.Tensor:
+    """SRHT right-sketch (App. D) -> fp32 [128, sketch_dim] on `device`.  signs: 128 values
+    (nonzero = -1); cols: sketch_dim distinct rows of the Hadamard matrix."""
+    sg = (C.c_uint8 * 128)(*[1 if int(x) else 0 for x in signs])
+    cl = (C.c_int32 * len(cols))(*[int(x) for x in cols])
+    phi = torch.empty(128, sketch_dim, dtype=torch.float32, device=device)
+    assert len(signs) == 128 and len(cols) == sketch_dim
+    with torch.cuda.device(phi.device):
+        _check(_lib.compactor_srht_phi(sketch_dim, sg, cl, _ptr(phi), _stream(stream)))
+    return phi
 
 
 def compactor_layout(params: Params, reqs: Sequence[Request]):

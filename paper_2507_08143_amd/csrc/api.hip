@@ -399,6 +399,21 @@ int compactor_layout(const compactor_params_t *p, const compactor_request_t *req
   return COMPACTOR_OK;
 }
 
+int compactor_srht_phi(int32_t sketch_dim, const uint8_t *signs, const int32_t *cols, float *phi,
+                       void *stream) {
+  if (!(sketch_dim == 16 || sketch_dim == 32 || sketch_dim == 48 || sketch_dim == 64))
+    return COMPACTOR_EUNSUPPORTED;
+  if (!signs || !cols || !phi) return COMPACTOR_EINVAL;
+  if (!aligned16(phi)) return COMPACTOR_EALIGN;
+  bool seen[D] = {false};
+  for (int j = 0; j < sketch_dim; ++j) {
+    if (cols[j] < 0 || cols[j] >= D || seen[cols[j]]) return COMPACTOR_EINVAL;
+    seen[cols[j]] = true;
+  }
+  HIP_TRY(launch_srht_phi(sketch_dim, signs, cols, phi, static_cast<hipStream_t>(stream)));
+  return COMPACTOR_OK;
+}
+
 int compactor_workspace_size(const compactor_params_t *p, const compactor_request_t *reqs,
                              int32_t nreq, size_t *bytes) {
   if (!bytes) return COMPACTOR_EINVAL;

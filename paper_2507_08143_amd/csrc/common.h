@@ -268,6 +268,10 @@ hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, cons
                                int32_t *status, int *zero, long long zero_ints, hipStream_t st,
                                hipEvent_t mid);
 
+// phi[128][ks] = sqrt(128/ks) * D H[cols]^T (signs, cols: host arrays, copied into the launch)
+hipError_t launch_srht_phi(int ks, const uint8_t *signs, const int32_t *cols, float *phi,
+                           hipStream_t st);
+
 // scores[i] = || W^T k_i ||^2
 // Also tallies the scores into hist1[selection pool][HIST1_BINS] (top 12 key bits; the pool is
 // the head, or the layer when T.layer_scope), which must be zero on entry; hist1 may be null.

@@ -379,6 +379,34 @@ hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, cons
   }
 }
 
+// Subsampled randomized Hadamard sketch (paper App. D) as a dense Phi: the sign bits and the
+// chosen rows of H travel as kernel arguments.
+struct SrhtSpec {
+  uint32_t sign_bits[D / 32];
+  uint8_t cols[64];
+};
+__global__ __launch_bounds__(256) void srht_phi_kernel(SrhtSpec spec, int ks, float value,
+                                                       float *__restrict__ phi) {
+  for (int idx = threadIdx.x + blockIdx.x * 256; idx < D * ks; idx += 256 * gridDim.x) {
+    const int i = idx / ks, j = idx - i * ks;
+    const unsigned neg = ((spec.sign_bits[i >> 5] >> (i & 31)) & 1u) ^
+                         (__popc((unsigned)i & (unsigned)spec.cols[j]) & 1u);
+    phi[idx] = neg ? -value : value;
+  }
+}
+
+hipError_t launch_srht_phi(int ks, const uint8_t *signs, const int32_t *cols, float *phi,
+                           hipStream_t st) {
+  SrhtSpec spec;
+  for (int w = 0; w < D / 32; ++w) spec.sign_bits[w] = 0;
+  for (int i = 0; i < D; ++i)
+    if (signs[i]) spec.sign_bits[i >> 5] |= 1u << (i & 31);
+  for (int j = 0; j < 64; ++j) spec.cols[j] = j < ks ? (uint8_t)cols[j] : 0;
+  hipLaunchKernelGGL(srht_phi_kernel, dim3(8), dim3(256), 0, st, spec, ks,
+                     sqrtf((float)D / (float)ks), phi);
+  return hipGetLastError();
+}
+
 // Exact mode: full G (fp64, from gram_reduce) -> Cholesky of G + rho I -> W^T = L^{-1}.
 hipError_t launch_solve(const SegTable &T, float ridge_rel, const double *g64, uint16_t *wt,
                         int32_t *status, hipStream_t st) {

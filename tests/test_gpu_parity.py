@@ -613,3 +613,52 @@ def test_compact_into_pages_error_codes(C):
     C.compactor_compact_paged(params, reqs, out["kept_idx"], out["kept_cnt"], pool, vp, bad)
     torch.cuda.synchronize()
     assert float(pool[2].abs().sum()) == 0.0 and float(pool[0].abs().sum()) > 0.0
+
+
+# ------------------------------------------------------------------ sketch variants (App. C, D)
+def test_srht_sketch_and_other_sketch_dims(C):
+    rng = np.random.default_rng(51)
+    w = W.config2(DEV, L=1, H=2, n=2000)
+    for ks in (16, 32, 48, 64):
+        _say("SRHT right-sketch, k_s = %d" % ks)
+        signs = rng.integers(0, 2, 128)
+        cols = rng.choice(128, ks, replace=False)
+        phi = C.compactor_srht_phi(ks, signs, cols, DEV)
+        torch.cuda.synchronize()
+        want = O.srht_phi(128, ks, signs, cols)
+        got = phi.cpu().numpy().astype(np.float64)
+        assert np.array_equal(np.sign(got), np.sign(want))              # every sign exact
+        np.testing.assert_allclose(np.abs(got), math.sqrt(128 / ks), rtol=2e-7)
+        w.sketch_dim = ks
+        params, reqs = U.make_call(C, w, DEV, phi=phi)
+        out = C.compactor_compress(params, reqs, want_scores=True)
+        torch.cuda.synchronize()
+        assert int(out["status"].max()) == 0
+        sc = out["scores"].cpu().numpy()
+        n = w.requests[0].n
+        for h in range(2):
+            K = O.bf16_bits_to_f64(W.bf16_bits(w.requests[0].k[0, h]))
+            ref = O.approx_leverage_ridge(K, want)      # the oracle's own Phi: scale is immaterial
+            U.check_scores(sc[h * n:(h + 1) * n], ref, "SRHT k_s=%d head %d" % (ks, h))
+    with pytest.raises(C.CompactorError):
+        C.compactor_srht_phi(48, np.zeros(128), np.zeros(48, dtype=int), DEV)      # repeated rows
+    for ks in (16, 32, 64):
+        _say("Gaussian right-sketch, k_s = %d" % ks)
+        w2 = W.config3(DEV, L=1, H=2, n=1500)
+        w2.sketch_dim = ks
+        st, _ = U.run_and_check(C, w2, DEV)
+        _say("  max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+
+
+def test_scores_agree_with_the_qr_and_eigen_routes(C):
+    _say("library scores against the oracle's QR and eigendecomposition routes (App. C)")
+    w = W.config1(DEV, n=3000)
+    params, reqs = U.make_call(C, w, DEV)
+    sc, st = C.compactor_score(params, reqs)
+    torch.cuda.synchronize()
+    K = O.bf16_bits_to_f64(W.bf16_bits(w.requests[0].k[0, 0]))
+    Phi = params.phi.double().cpu().numpy()
+    got = sc.cpu().numpy()
+    U.check_scores(got, O.approx_leverage_qr(K, Phi), "QR route")
+    U.check_scores(got, O.approx_leverage_eig(K, Phi, eps=1e-6), "eigen route, clamp 1e-6")
+    U.check_scores(got, O.approx_leverage_alg1(K, Phi), "Algorithm 1 (SVD of the sketched Gram matrix)")
