@@ -10,11 +10,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
                                                      const int32_t *__restrict__ kept_idx,
                                                      uint16_t *__restrict__ k_packed,
                                                      uint16_t *__restrict__ v_packed) {
-#ifdef GATHER_REVERSE
-  const Where w = locate_block(T, gridDim.x - 1 - blockIdx.x, GATHER_ROWS, GATHER_ROWS, true);
-#else
   const Where w = locate_block(T, blockIdx.x, GATHER_ROWS, GATHER_ROWS, true);
-#endif
   const Seg &s = T.s[w.seg];
   const int k = s.k_keep;
   const long long row0 = s.kept_off + (long long)w.head * k;      // first packed row of the head
@@ -43,13 +39,8 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
     const int j = w.tile * GATHER_ROWS + p * 16 + sub;
     if (j < k) {
       const long long off = (row0 + j) * D + chunk * 8;
-#ifdef GATHER_PLAIN_STORES
-      *reinterpret_cast<uint4 *>(k_packed + off) = kv[p];
-      *reinterpret_cast<uint4 *>(v_packed + off) = vv[p];
-#else
       store_stream16(k_packed + off, kv[p]);
       store_stream16(v_packed + off, vv[p]);
-#endif
     }
   }
 }
@@ -167,6 +158,8 @@ __global__ __launch_bounds__(256) void gather_paged_kernel(const SegTable T, con
   for (int p = 0; p < GATHER_ROWS / 16; ++p) {
     const int j = tile * GATHER_ROWS + p * 16 + sub;
     dst[p] = -1;
+    kv[p] = make_uint4(0, 0, 0, 0);
+    vv[p] = make_uint4(0, 0, 0, 0);
     if (j < rows) {
       int head = head0, jh = j;                      // head of the row and its rank in that head
       if (T.layer_scope) {
@@ -198,10 +191,10 @@ __global__ __launch_bounds__(256) void gather_paged_kernel(const SegTable T, con
 
 // In place: a head's tokens already live in the pages (token t at logical slot t) and its
 // retained rows move to the front.  One workgroup per head walks the retained list in ascending
-// runs of 128 rows: all rows of a run are read, the workgroup meets, the run is written.  A run's
+// runs of 256 rows: all rows of a run are read, the workgroup meets, the run is written.  A run's
 // sources lie at or behind its own destinations and strictly behind those of earlier runs
 // (kept[j] >= j, ascending), so nothing is overwritten before it has been read.
-constexpr int INPLACE_THREADS = 1024, INPLACE_RUN = 128;
+constexpr int INPLACE_THREADS = 1024, INPLACE_RUN = 256;
 __global__ __launch_bounds__(INPLACE_THREADS) void compact_inplace_kernel(
     const SegTable T, const PagePool P, const int32_t *__restrict__ kept_idx,
     const int32_t *__restrict__ kept_cnt) {
@@ -225,6 +218,8 @@ __global__ __launch_bounds__(INPLACE_THREADS) void compact_inplace_kernel(
     for (int p = 0; p < INPLACE_RUN / 64; ++p) {
       const int j = base + p * 64 + sub;
       dst[p] = -1;
+      kv[p] = make_uint4(0, 0, 0, 0);
+      vv[p] = make_uint4(0, 0, 0, 0);
       if (j < rows) {
         const int tok = idx[j];
         const long long src = (tok >= j && tok < s.n) ? page_slot(P, w.seg, layer, h, tok) : -1;

@@ -42,12 +42,8 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char *p) {
 // all tokens of the tile but owns its blocks outright, so no cross-wave reduction is needed and
 // a wave carries at most 48 accumulator registers.
 //   wave 0: (0,0) (0,1) (0,2)   wave 1: (0,3) (1,1) (1,2)   wave 2: (1,3) (2,2)   wave 3: (2,3) (3,3)
-#ifndef GRAM_OCC
-#define GRAM_OCC 2          // waves per SIMD the register budget is set for
-#endif
-#ifndef GRAM_TG_UNROLL
-#define GRAM_TG_UNROLL 4    // 16-token steps unrolled together (more = more operands in flight)
-#endif
+constexpr int GRAM_OCC = 2;         // waves per SIMD the register budget is set for
+constexpr int GRAM_TG_UNROLL = 4;   // 16-token steps unrolled together (more operands in flight)
 __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, int tiles_per_wg,
                                                              long long total,
                                                              float *__restrict__ partials) {

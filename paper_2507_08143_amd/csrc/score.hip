@@ -42,11 +42,7 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
   __shared__ __attribute__((aligned(16))) uint16_t kl[4][WTOK * WPITCH];
   __shared__ int hl[HIST1_BINS];     // first radix digit of the selection, tallied on the way out
 
-#ifdef SCORE_REVERSE
-  const Where w = locate_block(T, gridDim.x - 1 - blockIdx.x, tokens_per_wg, SCORE_STEP, false);
-#else
   const Where w = locate_block(T, blockIdx.x, tokens_per_wg, SCORE_STEP, false);
-#endif
   const Seg &s = T.s[w.seg];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int t16 = lane & 15, g = lane >> 4;
@@ -69,15 +65,9 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
     }
   };
 
-#ifndef SCORE_DEPTH
-#define SCORE_DEPTH 2
-#endif
-  uint4 stA[NLD];
+  uint4 stA[NLD], stB[NLD];
   load_step(0, stA);          // in flight while W^T is staged
-#if SCORE_DEPTH != 1
-  uint4 stB[NLD];
   load_step(1, stB);
-#endif
 
   for (int i = tid; i < HIST1_BINS; i += 256) hl[i] = 0;
   const uint16_t *wh = wt + (size_t)w.lhead * (W_TERMS * M * D);
@@ -148,13 +138,6 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
     }
   };
 
-#if SCORE_DEPTH == 1
-  for (int it = 0; it < nsteps; ++it) {     // one step of loads in flight behind the MFMAs
-    redistribute(stA);
-    load_step(it + 1, stA);
-    multiply(it);
-  }
-#else
   for (int it = 0; it < nsteps; it += 2) {
     redistribute(stA);
     load_step(it + 2, stA);
@@ -165,7 +148,6 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
       multiply(it + 1);
     }
   }
-#endif
   if (__any(bad)) {
     if (lane == 0) atomicOr(&status[s.ghead0 + w.head], COMPACTOR_STATUS_NONFINITE);
   }

@@ -278,9 +278,6 @@ __global__ __launch_bounds__(64) void solve_wave_kernel(const SegTable T,
   const bool rowlane = lane < M;
   const double *sp = s_parts + (size_t)lhead * 4 * (M * M);
 
-#ifdef SOLVE_PROFILE
-  long long tp0 = clock64(), tp1, tp2, tp3;
-#endif
   // S is symmetric: lane i reads S[j][i], contiguous across lanes, as its row entry (i, j)
   double row[64];
 #pragma unroll
@@ -305,9 +302,6 @@ __global__ __launch_bounds__(64) void solve_wave_kernel(const SegTable T,
   for (int j = 0; j < M; ++j) row[j] += (lane == j) ? rho : 0.0;
   for (int idx = lane; idx < M * LP; idx += 64) Ls[idx] = 0.0;
 
-#ifdef SOLVE_PROFILE
-  tp1 = clock64();
-#endif
   // right-looking Cholesky in 16-column panels; the window shrinks by 16 per panel
   double rsv = 0.0;                              // lane k: 1 / L[k][k] (0 for a dropped pivot)
   int flag = 0;
@@ -320,9 +314,6 @@ __global__ __launch_bounds__(64) void solve_wave_kernel(const SegTable T,
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-#ifdef SOLVE_PROFILE
-  tp2 = clock64();
-#endif
   // forward substitution, column oriented, same sliding window: v -= L[:, j] * y_j
   const int ch = 64 * half + lane;
   double v[64];
@@ -338,11 +329,6 @@ __global__ __launch_bounds__(64) void solve_wave_kernel(const SegTable T,
   if constexpr (M >= 32) fwd_panel<32>(v, M - 32, Ls, LP, rsv, wh, M, ch);
   fwd_panel<16>(v, M - 16, Ls, LP, rsv, wh, M, ch);
 
-#ifdef SOLVE_PROFILE
-  tp3 = clock64();
-  if (lane == 0 && blockIdx.x == 6)
-    printf("solve_wave phases (cycles): load %lld  chol %lld  fwd %lld\n", tp1 - tp0, tp2 - tp1, tp3 - tp2);
-#endif
   if (half == 0 && lane == 0) {
     const Where w = locate_head(T, lhead);
     status[T.s[w.seg].ghead0 + w.head] = flag;
