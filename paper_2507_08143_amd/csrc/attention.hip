@@ -276,14 +276,17 @@ __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(const AttnTable T,
 }
 
 // Mean pooling along the sequence: window `pool` (odd), zero padding, divided by `pool`.
+// A workgroup stages its 1024 positions and the halo once in LDS.
 __global__ __launch_bounds__(256) void attn_pool_kernel(const AttnTable T,
                                                         const float *__restrict__ raw,
                                                         float *__restrict__ attn) {
+  constexpr int SPAN = 1024, HALO = 32;           // pool <= 63: at most 31 positions each side
+  __shared__ float tile[SPAN + 2 * HALO];
   int seg = 0, head = 0, blk = 0;
   {
     int base = 0;
     for (int i = 0; i < T.nseg; ++i) {
-      const int bph = (T.s[i].n + 1023) / 1024;
+      const int bph = (T.s[i].n + SPAN - 1) / SPAN;
       const int nb = bph * T.s[i].head_count;
       if ((int)blockIdx.x < base + nb || i == T.nseg - 1) {
         const int local = blockIdx.x - base;
@@ -299,14 +302,17 @@ __global__ __launch_bounds__(256) void attn_pool_kernel(const AttnTable T,
   const int n = s.n, h = T.pool / 2;
   const float *src = raw + s.out_off + (long long)head * n;
   float *dst = attn + s.out_off + (long long)head * n;
+  const int t0 = blk * SPAN;
+  for (int i = threadIdx.x; i < SPAN + 2 * HALO; i += 256) {
+    const int j = t0 - HALO + i;
+    tile[i] = (j >= 0 && j < n) ? src[j] : 0.f;   // zero padding at both ends of the sequence
+  }
+  __syncthreads();
   const float inv = 1.f / (float)T.pool;
-  for (int t = blk * 1024 + threadIdx.x; t < min(n, (blk + 1) * 1024); t += 256) {
+  for (int i = threadIdx.x; i < SPAN && t0 + i < n; i += 256) {
     float acc = 0.f;
-    for (int u = -h; u <= h; ++u) {
-      const int j = t + u;
-      if (j >= 0 && j < n) acc += src[j];
-    }
-    dst[t] = acc * inv;
+    for (int u = -h; u <= h; ++u) acc += tile[HALO + i + u];
+    dst[t0 + i] = acc * inv;
   }
 }
 
