@@ -10,7 +10,7 @@
 // the group in turn) pass through LDS as B operands.  Both operands are plain 16-byte pieces of
 // rows (the contraction runs over channels), so nothing is transposed.  The four waves each
 // see a quarter of a query's keys; they exchange (max, sum) once per step through LDS and
-// merge them as in an online softmax.  The column sums accumulate in 16 registers per lane and
+// merge them as in an online softmax.  The column sums accumulate in 32 registers per lane and
 // are reduced across lanes once per block.
 #include <math.h>
 #include <string.h>
@@ -43,32 +43,25 @@ struct AttnTable {
   int pool;
 };
 
-// Exchange between the four 16-lane rows of a wave with the row-swap instructions of gfx950:
-// after swapping the upper half of one copy with the lower half of the other, the two results
-// of a lane are its own value and its partner's (32 lanes away; then 16 lanes away), so a max
-// or a sum of the pair finishes one level of the reduction in every lane, without LDS traffic.
+// Exchange between the two halves of a wave with the row-swap instruction of gfx950: after
+// swapping the upper half of one copy with the lower half of the other, the two results of a
+// lane are its own value and that of the lane 32 away, so a max or a sum of the pair finishes
+// the reduction in every lane, without LDS traffic.
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ float rows_max(float x) {
-  u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-  r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ float halves_max(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
-__device__ __forceinline__ float rows_sum(float x) {
-  u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-  r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+__device__ __forceinline__ float halves_sum(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
-// x holds one value per lane; out[r] = the value of lane 16*r + (lane & 15), in every lane
-__device__ __forceinline__ void rows_broadcast(float x, float (&out)[4]) {
-  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  const u32x2 a = __builtin_amdgcn_permlane16_swap(r[0], r[0], false, false);
-  const u32x2 b = __builtin_amdgcn_permlane16_swap(r[1], r[1], false, false);
-  out[0] = __uint_as_float(a[0]);
-  out[1] = __uint_as_float(a[1]);
-  out[2] = __uint_as_float(b[0]);
-  out[3] = __uint_as_float(b[1]);
+// the largest of three finite-or-infinite numbers in one instruction
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
 }
 
 struct AttnLds {
@@ -79,6 +72,10 @@ struct AttnLds {
 
 // One (kv-head, block) of the column sums.  RAGGED is the last block of a head whose length is
 // not a multiple of the block: only there keys and queries past the end have to be masked.
+//
+// The products are 32x32x16 MFMAs: D[key][query] leaves lane l with 16 keys of query l & 31
+// (keys 8*(v>>2) + 4*(l>>5) + (v&3), v = 0..15), so a query's 64 keys of this wave are the 32
+// registers of two key tiles in lanes l and l ^ 32.
 template <bool RAGGED>
 __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int head, int c0,
                                            AttnLds &L, float *__restrict__ raw) {
@@ -86,30 +83,30 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
   const int layer = head / s.H, kvh = head - layer * s.H;
   const uint16_t *kp = s.k + (long long)layer * s.k_stride_l + (long long)kvh * s.k_stride_h;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int l16 = lane & 15, lq = lane >> 4;
+  const int l32 = lane & 31, lh = lane >> 5;
 
-  // this wave's 64 keys as A operands: tile kt, lane (key l16, channel group lq)
-  bf16x8 ka[4][4];
+  // this wave's 64 keys as A operands: tile kt, lane (key l32, channels 16*kk + 8*lh ..)
+  bf16x8 ka[2][8];
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt) {
-    const int key = c0 + 64 * wave + 16 * kt + l16;
+  for (int kt = 0; kt < 2; ++kt) {
+    const int key = c0 + 64 * wave + 32 * kt + l32;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < 8; ++kk) {
       union { uint4 u; bf16x8 v; } t;
       t.u = make_uint4(0, 0, 0, 0);
       if (!RAGGED || key < n)
-        t.u = *reinterpret_cast<const uint4 *>(kp + (long long)key * s.k_stride_t + 32 * kk + 8 * lq);
+        t.u = *reinterpret_cast<const uint4 *>(kp + (long long)key * s.k_stride_t + 16 * kk + 8 * lh);
       ka[kt][kk] = t.v;
     }
   }
-  // keys this lane sees in the MFMA result: tile kt, register v -> key c0 + 64*wave + 16*kt + 4*lq + v
-  const int key_base = c0 + 64 * wave + 4 * lq;
+  // key of register v of key tile kt in this lane
+  auto key_of = [&](int kt, int v) { return c0 + 64 * wave + 32 * kt + 8 * (v >> 2) + 4 * lh + (v & 3); };
 
-  float pacc[4][4];
+  float pacc[2][16];
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt)
+  for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) pacc[kt][v] = 0.f;
+    for (int v = 0; v < 16; ++v) pacc[kt][v] = 0.f;
 
   const int nsteps = s.G * (ATT_C / ATT_QB);          // (query head of the group, 64-query block)
   const int ld_row = tid >> 4, ld_chunk = tid & 15;   // loader: 16 lanes per 256-B query row
@@ -131,20 +128,23 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
       *reinterpret_cast<uint4 *>(&L.ql[buf][(ld_row + 16 * i) * QPITCH + ld_chunk * 8]) = stg[i];
   };
 
-  // S^T tile of one 16-query slice: acc[kt] = keys (tile kt) x queries, contraction over channels
-  f32x4 acc[4][4];
-  auto product = [&](int buf, int sl) {
-    bf16x8 qb[4];
+  // S^T tiles of one 32-query tile: acc[qt][kt] = keys (tile kt) x queries, contraction over
+  // channels; the two key tiles alternate so that consecutive MFMAs are independent
+  f32x16 acc[2][2];
+  auto product = [&](int buf, int qt) {
+    bf16x8 qb[8];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-      qb[kk] = *reinterpret_cast<const bf16x8 *>(&L.ql[buf][(16 * sl + l16) * QPITCH + 32 * kk + 8 * lq]);
+    for (int kk = 0; kk < 8; ++kk)
+      qb[kk] = *reinterpret_cast<const bf16x8 *>(&L.ql[buf][(32 * qt + l32) * QPITCH + 16 * kk + 8 * lh]);
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt) {
-      acc[sl][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-        acc[sl][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kt][kk], qb[kk], acc[sl][kt], 0, 0, 0);
-    }
+      for (int v = 0; v < 16; ++v) acc[qt][kt][v] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+        acc[qt][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kt][kk], qb[kk], acc[qt][kt], 0, 0, 0);
   };
 
   uint4 stg[4];
@@ -159,38 +159,41 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
     load_q(step + 1, stg);                              // in flight during this step
 
     // Local softmax statistics of every query over this wave's 64 keys, in the base-2 domain:
-    // e = 2^(c*s - m) with c = scale * log2(e), so an element costs one max, one fma, one exp
-    // and one add.  The product of the next slice is issued ahead of the arithmetic of this one.
-    float m_mine = 0.f, l_mine = 0.f;    // statistics of query `lane` of the step (slice lq)
+    // e = 2^(c*s - m) with c = scale * log2(e), so an element costs half a max3, one fma, one
+    // exp and one add.  The product of the second query tile is issued ahead of the arithmetic
+    // of the first.
+    float m_mine = 0.f, l_mine = 0.f;    // statistics of query `lane` of the step (tile lh)
 #pragma unroll
-    for (int sl = 0; sl < 4; ++sl) {
-      if (sl < 3) product(buf, sl + 1);
+    for (int qt = 0; qt < 2; ++qt) {
+      if (qt == 0) product(buf, 1);
       if (RAGGED) {
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (key_base + 16 * kt + v >= n) acc[sl][kt][v] = -INFINITY;
+          for (int v = 0; v < 16; ++v)
+            if (key_of(kt, v) >= n) acc[qt][kt][v] = -INFINITY;
       }
-      float m = acc[sl][0][0];
+      float m = max3(acc[qt][0][0], acc[qt][0][1], acc[qt][1][0]);
+      m = max3(m, acc[qt][1][1], acc[qt][0][2]);
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
+      for (int v = 3; v < 16; v += 2) m = max3(m, acc[qt][0][v], acc[qt][0][v + (v < 15 ? 1 : 0)]);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) m = fmaxf(m, acc[sl][kt][v]);
-      m = rows_max(m);
-      float mc = m * c2, mx = mc;
+      for (int v = 2; v < 16; v += 2) m = max3(m, acc[qt][1][v], acc[qt][1][v + 1]);
+      m = halves_max(m);
+      float mc = m * c2;
+      const float mx = mc;
       if (RAGGED && m == -INFINITY) mc = 0.f;           // a wave whose keys are all past the end
       float l = 0.f;
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
+      for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const float e = __builtin_amdgcn_exp2f(fmaf(acc[sl][kt][v], c2, -mc));
-          acc[sl][kt][v] = e;
+        for (int v = 0; v < 16; ++v) {
+          const float e = __builtin_amdgcn_exp2f(fmaf(acc[qt][kt][v], c2, -mc));
+          acc[qt][kt][v] = e;
           l += e;
         }
-      l = rows_sum(l);
-      if (lq == sl) {
+      l = halves_sum(l);
+      if (lh == qt) {
         m_mine = mx;
         l_mine = l;
       }
@@ -201,9 +204,8 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
     store_q(buf ^ 1, stg);
     __syncthreads();        // statistics of this step and the next step's queries are in LDS
 
-    // merge the four waves' statistics, one query per lane, then hand every slice its factor
-    float m = L.st_m[buf][0][lane];
-    float mw[4];
+    // merge the four waves' statistics, one query per lane, then hand both tiles their factor
+    float mw[4], m = L.st_m[buf][0][lane];
 #pragma unroll
     for (int w2 = 0; w2 < 4; ++w2) {
       mw[w2] = L.st_m[buf][w2][lane];
@@ -217,32 +219,33 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
       const int q0 = c0 + (step % (ATT_C / ATT_QB)) * ATT_QB;
       if (q0 + lane >= n) f = 0.f;
     }
-    float fs[4];
-    rows_broadcast(f, fs);
+    const u32x2 fr = __builtin_amdgcn_permlane32_swap(__float_as_uint(f), __float_as_uint(f), false, false);
 #pragma unroll
-    for (int sl = 0; sl < 4; ++sl) {
+    for (int qt = 0; qt < 2; ++qt) {
+      const float fq = __uint_as_float(fr[qt]);        // factor of query 32*qt + l32
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
+      for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) pacc[kt][v] = fmaf(acc[sl][kt][v], fs[sl], pacc[kt][v]);
-      if (sl == 0 && step + 1 < nsteps) product(buf ^ 1, 0);   // first slice of the next step
+        for (int v = 0; v < 16; ++v) pacc[kt][v] = fmaf(acc[qt][kt][v], fq, pacc[kt][v]);
+      if (qt == 0 && step + 1 < nsteps) product(buf ^ 1, 0);   // first tile of the next step
     }
   }
 
-  // column sums: add over the 16 query lanes of each quarter, average over the query heads
+  // column sums: add over the 32 query lanes of each half, average over the query heads
   const float inv_g = 1.f / (float)s.G;
   float *out = raw + s.out_off + (long long)head * n;
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt)
+  for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
+    for (int v = 0; v < 16; ++v) {
       float x = pacc[kt][v];
       x += __shfl_xor(x, 1);
       x += __shfl_xor(x, 2);
       x += __shfl_xor(x, 4);
       x += __shfl_xor(x, 8);
-      const int key = key_base + 16 * kt + v;
-      if (l16 == 0 && key < n) out[key] = x * inv_g;
+      x += __shfl_xor(x, 16);
+      const int key = key_of(kt, v);
+      if (l32 == 0 && key < n) out[key] = x * inv_g;
     }
 }
 
