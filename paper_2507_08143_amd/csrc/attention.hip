@@ -173,25 +173,28 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
           for (int v = 0; v < 16; ++v)
             if (key_of(kt, v) >= n) acc[qt][kt][v] = -INFINITY;
       }
-      float m = max3(acc[qt][0][0], acc[qt][0][1], acc[qt][1][0]);
-      m = max3(m, acc[qt][1][1], acc[qt][0][2]);
+      // two independent chains each for the maximum and for the sum (one per key tile)
+      float mk[2];
 #pragma unroll
-      for (int v = 3; v < 16; v += 2) m = max3(m, acc[qt][0][v], acc[qt][0][v + (v < 15 ? 1 : 0)]);
+      for (int kt = 0; kt < 2; ++kt) {
+        mk[kt] = max3(acc[qt][kt][0], acc[qt][kt][1], acc[qt][kt][2]);
 #pragma unroll
-      for (int v = 2; v < 16; v += 2) m = max3(m, acc[qt][1][v], acc[qt][1][v + 1]);
-      m = halves_max(m);
+        for (int v = 3; v < 15; v += 2) mk[kt] = max3(mk[kt], acc[qt][kt][v], acc[qt][kt][v + 1]);
+      }
+      const float m = halves_max(max3(mk[0], mk[1], fmaxf(acc[qt][0][15], acc[qt][1][15])));
       float mc = m * c2;
       const float mx = mc;
       if (RAGGED && m == -INFINITY) mc = 0.f;           // a wave whose keys are all past the end
-      float l = 0.f;
+      float lk[2] = {0.f, 0.f};
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int v = 0; v < 16; ++v)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
+        for (int kt = 0; kt < 2; ++kt) {
           const float e = __builtin_amdgcn_exp2f(fmaf(acc[qt][kt][v], c2, -mc));
           acc[qt][kt][v] = e;
-          l += e;
+          lk[kt] += e;
         }
+      float l = lk[0] + lk[1];
       l = halves_sum(l);
       if (lh == qt) {
         m_mine = mx;
