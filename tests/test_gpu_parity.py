@@ -662,3 +662,44 @@ def test_scores_agree_with_the_qr_and_eigen_routes(C):
     U.check_scores(got, O.approx_leverage_qr(K, Phi), "QR route")
     U.check_scores(got, O.approx_leverage_eig(K, Phi, eps=1e-6), "eigen route, clamp 1e-6")
     U.check_scores(got, O.approx_leverage_alg1(K, Phi), "Algorithm 1 (SVD of the sketched Gram matrix)")
+
+
+# ------------------------------------------------------------------ graph capture
+def test_compress_replays_from_a_hip_graph(C):
+    """The fused call only launches kernels on the caller's stream (its scratch is cleared by
+    kernels), so it can be captured once and replayed: every replay must give what the eager
+    call gives on the inputs of that moment."""
+    _say("compress captured in a HIP graph, replayed on changing inputs")
+    w = W.config2(DEV, L=2, H=4, n=5000)
+    params, reqs = U.make_call(C, w, DEV)
+    so, ko, kk = C.compactor_layout(params, reqs)
+    nh = w.layers * w.kv_heads
+    ws = torch.empty(max(256, C.compactor_workspace_size(params, reqs)), dtype=torch.uint8, device=DEV)
+
+    def buffers():
+        return dict(kept_idx=torch.empty(ko[-1], dtype=torch.int32, device=DEV),
+                    kept_cnt=torch.empty(nh, dtype=torch.int32, device=DEV),
+                    k_packed=torch.empty(ko[-1], 128, dtype=torch.bfloat16, device=DEV),
+                    v_packed=torch.empty(ko[-1], 128, dtype=torch.bfloat16, device=DEV),
+                    status=torch.empty(nh, dtype=torch.int32, device=DEV),
+                    scores=torch.empty(so[-1], dtype=torch.float32, device=DEV))
+    gb, eb = buffers(), buffers()
+    C.compactor_compress(params, reqs, want_scores=True, workspace=ws, **gb)     # warm-up, eager
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        C.compactor_compress(params, reqs, want_scores=True, workspace=ws, **gb)
+    for rep in range(3):
+        # new keys and values in the same tensors, some eager work and a sync between replays
+        fresh = W.config2(DEV, seed=100 + rep, L=2, H=4, n=5000).requests[0]
+        w.requests[0].k.copy_(fresh.k)
+        w.requests[0].v.copy_(fresh.v)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        C.compactor_compress(params, reqs, want_scores=True, workspace=ws, **eb)
+        torch.cuda.synchronize()
+        for name in ("scores", "kept_idx", "kept_cnt", "status"):
+            assert torch.equal(gb[name], eb[name]), "replay %d: %s differs from the eager call" % (rep, name)
+        assert torch.equal(gb["k_packed"].view(torch.int16), eb["k_packed"].view(torch.int16))
+        assert torch.equal(gb["v_packed"].view(torch.int16), eb["v_packed"].view(torch.int16))
