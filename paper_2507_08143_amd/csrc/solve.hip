@@ -122,87 +122,22 @@ __global__ __launch_bounds__(256) void solve_exact_kernel(const SegTable T, floa
   if (tid == 0) status[sg.ghead0 + w.head] = flag;
 }
 
-// ---- sketched mode -------------------------------------------------------------------------
-// Step 1, sketch_kernel: one workgroup per (head, 32-row block I of G).  It sums the head's
-// partial Gram blocks in fp64 (split order, deterministic), forms the rows G_I (32 x 128),
-// T_I = G_I Phi (32 x k_s) and the contribution S_I = Phi_I^T T_I (k_s x k_s) to
-// S = Phi^T G Phi = sum_I S_I, both on the fp64 matrix cores.  All the O(d^2 k_s) work of the
-// factorisation step is here, spread over 4 x heads workgroups.
-template <int M>
-__global__ __launch_bounds__(256) void sketch_kernel(const SegTable T, int tiles_per_wg,
-                                                     const float *__restrict__ partials,
-                                                     const float *__restrict__ phi,
-                                                     double *__restrict__ s_parts,
-                                                     int *__restrict__ zero, long long zero_ints) {
-  constexpr int GP = D + 1, TP = M + 1;
-  __shared__ double Gs[32 * GP];
-  __shared__ double Ts[32 * TP];
-  __shared__ __attribute__((aligned(16))) float PH[D * M];
-
-  const int lhead = blockIdx.x >> 2, I = blockIdx.x & 3;
-  const int tid = threadIdx.x;
-  for (int idx = tid; idx < D * M / 4; idx += 256)
-    reinterpret_cast<float4 *>(PH)[idx] = reinterpret_cast<const float4 *>(phi)[idx];
-  zero_slice(zero, zero_ints);   // histograms that the score and selection kernels add into
-
-  // rows 32I .. 32I+31 of G from the stored upper blocks (mirror blocks read transposed)
-  int nsplit;
-  const long long pb = partial_base(T, lhead, tiles_per_wg, nsplit);
-  const int e = tid * 4, ii = e >> 5, jj = e & 31;
-#pragma unroll
-  for (int J = 0; J < 4; ++J) {
-    const int blk = J >= I ? upper_block(I, J) : upper_block(J, I);
-    const float *src = partials + pb * GRAM_PARTIAL_FLOATS + blk * 1024 + e;
-    double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
-    for (int sidx = 0; sidx < nsplit; ++sidx) {
-      const float4 v = *reinterpret_cast<const float4 *>(src + (long long)sidx * GRAM_PARTIAL_FLOATS);
-      a0 += v.x; a1 += v.y; a2 += v.z; a3 += v.w;
-    }
-    if (J >= I) {           // stored as (I,J): element (ii, jj+q) is G[32I+ii][32J+jj+q]
-      double *d = &Gs[ii * GP + 32 * J + jj];
-      d[0] = a0; d[1] = a1; d[2] = a2; d[3] = a3;
-    } else {                // stored as (J,I): element (ii, jj+q) is G[32J+ii][32I+jj+q]
-      Gs[(jj + 0) * GP + 32 * J + ii] = a0;
-      Gs[(jj + 1) * GP + 32 * J + ii] = a1;
-      Gs[(jj + 2) * GP + 32 * J + ii] = a2;
-      Gs[(jj + 3) * GP + 32 * J + ii] = a3;
-    }
-  }
-  __syncthreads();
-
-  // fp64 MFMA 16x16x4: A[i][k] sits in lane (i = l & 15, k = l >> 4), B[k][j] in lane
-  // (j = l & 15, k = l >> 4); register v of lane l of the result is D[4*v + (l >> 4)][l & 15].
-  const int wave = tid >> 6, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
-  constexpr int CT = M / 16;
-  // T_I = G_I Phi (32 x M): 2 x CT tiles, K = 128
-  for (int tile = wave; tile < 2 * CT; tile += 4) {
-    const int rt = tile / CT, ct = tile - rt * CT;
-    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll 8
-    for (int ks = 0; ks < D / 4; ++ks) {
-      const double a = Gs[(16 * rt + l16) * GP + 4 * ks + lq];
-      const double b = (double)PH[(4 * ks + lq) * M + 16 * ct + l16];
-      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
-    }
-#pragma unroll
-    for (int v = 0; v < 4; ++v) Ts[(16 * rt + 4 * v + lq) * TP + 16 * ct + l16] = acc[v];
-  }
-  __syncthreads();
-
-  // S_I = Phi_I^T T_I (M x M): CT x CT tiles, K = 32
-  double *out = s_parts + ((size_t)lhead * 4 + I) * (M * M);
-  for (int tile = wave; tile < CT * CT; tile += 4) {
-    const int at = tile / CT, bt = tile - at * CT;
-    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const double a = (double)PH[(32 * I + 4 * ks + lq) * M + 16 * at + l16];
-      const double b = Ts[(4 * ks + lq) * TP + 16 * bt + l16];
-      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
-    }
-#pragma unroll
-    for (int v = 0; v < 4; ++v) out[(16 * at + 4 * v + lq) * M + 16 * bt + l16] = acc[v];
-  }
+// ---- sketched mode, one kernel: partial Gram blocks -> S -> L -> L^{-1} -> W^T ------------------
+// One workgroup (4 waves) per head; every O(n^3)-ish piece runs on the fp64 matrix cores
+// (16x16x4 MFMA: A[i][k] in lane (i = l & 15, k = l >> 4), B[k][j] in lane (j = l & 15,
+// k = l >> 4), register v of lane l of the result is D[4v + (l >> 4)][l & 15]):
+//   1. S = Phi^T G Phi, G summed in fp64 from the head's partial blocks, 32 rows of G at a time
+//   2. blocked right-looking Cholesky of S + rho I with 16-wide panels: wave 0 factors the
+//      diagonal block in registers (the only serial part, 16 pivots) and inverts it, the panel
+//      below is L_qp = A_qp X_pp^T and the trailing blocks get A_qr -= L_qp L_rp^T
+//   3. X = L^{-1} block by block (X_qp = -X_qq sum_r L_qr X_rp), one wave per block column
+//   4. W^T = X Phi^T, split into bf16 planes
+// A pivot below PIVOT_REL of its own ridged diagonal entry is dropped: 1/L_kk := 0, which zeroes
+// column k of L, row and column k of X and row k of W^T, and flags the head.
+__device__ __forceinline__ void wave_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 __device__ __forceinline__ double readlane_f64(double x, int lane) {
@@ -211,127 +146,272 @@ __device__ __forceinline__ double readlane_f64(double x, int lane) {
   return __hiloint2double(hi, lo);
 }
 
-// Step 2, solve_wave_kernel: Cholesky and forward substitution in the registers of one wave,
-// with no barrier.  Lane i holds row i of S; a pivot or a column entry needed by every lane is
-// read with v_readlane.  The register file is walked with a sliding window so that the loops
-// over the pivot index stay rolled (small code): after step k the window has moved one column
-// to the right, register 0 always holds the pivot column.  Column k of L is parked in LDS for
-// the substitution.  Two waves per head factor the same S redundantly and each produces 64 of
-// the 128 columns of W^T = L^{-1} Phi^T (lane = channel).
-//
-// PANEL steps with a window of WIN registers: one 16-column panel of the factorisation.
-template <int WIN>
-__device__ __forceinline__ void chol_panel(double (&row)[64], double d0, int k0, int lane,
-                                           double *__restrict__ Ls, int LP, double &rsv, int &flag) {
-#pragma unroll 1
-  for (int k = k0; k < k0 + 16; ++k) {
-    const double piv = readlane_f64(row[0], k);
-    const double d0k = readlane_f64(d0, k);
-    const bool ok = piv > PIVOT_REL * d0k && piv < 1.0e300;      // false for NaN too
-    const double rs = ok ? rsqrt(piv) : 0.0;
-    rsv = (lane == k) ? rs : rsv;
-    if (!ok) flag = COMPACTOR_STATUS_PIVOT;
-    const double lk = ok ? row[0] * rs : 0.0;                    // L[lane][k] (lanes > k)
-    Ls[k * LP + lane] = lk;
-    // the column just parked is read back at wave-uniform addresses (an LDS broadcast costs a
-    // third of a pair of v_readlane here); LDS operations of one wave execute in order
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const double *lc = Ls + k * LP + k;                          // lc[j] = L[k + j][k]
-#pragma unroll
-    for (int j = 1; j < WIN; ++j) row[j - 1] = row[j] - lk * lc[j];
-  }
-}
-
-template <int WIN>
-__device__ __forceinline__ void fwd_panel(double (&v)[64], int j0, const double *__restrict__ Ls,
-                                          int LP, double rsv, uint16_t *__restrict__ wh, int M,
-                                          int ch) {
-#pragma unroll 1
-  for (int j = j0; j < j0 + 16; ++j) {
-    const double y = v[0] * readlane_f64(rsv, j);
-    float x = (float)y;
-#pragma unroll
-    for (int t = 0; t < W_TERMS; ++t) {
-      const uint16_t b = bf16_rne(x);
-      wh[(t * M + j) * D + ch] = b;
-      x -= bf16_to_f32(b);
-    }
-    const double *lc = Ls + j * LP + j;          // L[j + i][j], i = 1.. (same address in all lanes)
-#pragma unroll
-    for (int i = 1; i < WIN; ++i) v[i - 1] = v[i] - lc[i] * y;
-  }
-}
-
 template <int M>
-__global__ __launch_bounds__(64) void solve_wave_kernel(const SegTable T,
-                                                        const float *__restrict__ phi,
-                                                        float ridge_rel,
-                                                        const double *__restrict__ s_parts,
-                                                        uint16_t *__restrict__ wt,
-                                                        int32_t *__restrict__ status) {
-  constexpr int LP = 64 + 16;                    // row pitch of the parked L (doubles); the pad
-  __shared__ double Ls[M * LP];                  // absorbs the reads past column M-1 below
-  const int lhead = blockIdx.x >> 1, half = blockIdx.x & 1;
-  const int lane = threadIdx.x;
-  const bool rowlane = lane < M;
-  const double *sp = s_parts + (size_t)lhead * 4 * (M * M);
+__global__ __launch_bounds__(256, 2) void sketch_solve_kernel(const SegTable T, int tiles_per_wg,
+                                                           const float *__restrict__ partials,
+                                                           const float *__restrict__ phi,
+                                                           float ridge_rel,
+                                                           uint16_t *__restrict__ wt,
+                                                           int32_t *__restrict__ status,
+                                                           int *__restrict__ zero,
+                                                           long long zero_ints) {
+  constexpr int P = M / 16, CT = M / 16;
+  constexpr int GP = D + 1, TP = M + 1, SP = M + 1;
+  // the staging of G and T (step 1) and the matrices S, X (steps 2-4) share one region: two
+  // workgroups fit a CU, so that the serial parts of one overlap the matrix work of the other
+  constexpr int STAGE = 32 * GP + 32 * TP, FACT = 2 * M * SP;
+  __shared__ double region[STAGE > FACT ? STAGE : FACT];
+  __shared__ __attribute__((aligned(16))) float PH[D * M];
+  double *Gs = region, *Ts = region + 32 * GP;
+  double *Ss = region;                 // S, then L in its lower blocks
+  double *Xs = region + M * SP;        // L^{-1} (lower blocks)
+  __shared__ double d0_s[M], rs_s[M], col_s[64];
+  __shared__ int flag_s;
 
-  // S is symmetric: lane i reads S[j][i], contiguous across lanes, as its row entry (i, j)
-  double row[64];
+  const int lhead = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
+  for (int idx = tid; idx < D * M / 4; idx += 256)
+    reinterpret_cast<float4 *>(PH)[idx] = reinterpret_cast<const float4 *>(phi)[idx];
+  if (tid == 0) flag_s = 0;
+  zero_slice(zero, zero_ints);   // histograms that the score and selection kernels add into
+
+  // ---- 1. S = Phi^T G Phi ----
+  int nsplit;
+  const long long pb = partial_base(T, lhead, tiles_per_wg, nsplit);
+  constexpr int ST = (CT * CT + 3) / 4;          // S tiles per wave: tile = wave + 4 i
+  f64x4 sacc[ST];
 #pragma unroll
-  for (int j = 0; j < 64; ++j) row[j] = 0.0;
-#pragma unroll 1
-  for (int part = 0; part < 4; ++part) {       // one contribution at a time: M loads in flight
-    double tmp[M];
+  for (int i = 0; i < ST; ++i) sacc[i] = f64x4{0.0, 0.0, 0.0, 0.0};
+  const int e = tid * 4, ii = e >> 5, jj = e & 31;
+  // the head's 10 upper blocks of G, summed over the splits in fp64 (split order): every thread
+  // keeps its 4 elements of each block in registers, all loads of two splits in flight at a time
+  double gsum[10][4];
 #pragma unroll
-    for (int j = 0; j < M; ++j) tmp[j] = rowlane ? sp[part * M * M + j * M + lane] : 0.0;
+  for (int b = 0; b < 10; ++b)
 #pragma unroll
-    for (int j = 0; j < M; ++j) row[j] += tmp[j];
+    for (int c = 0; c < 4; ++c) gsum[b][c] = 0.0;
+  {
+    const float *src = partials + pb * GRAM_PARTIAL_FLOATS + e;
+    for (int s0 = 0; s0 < nsplit; s0 += 2) {
+      float4 v[2][10];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int b = 0; b < 10; ++b) {
+          v[u][b] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (s0 + u < nsplit)
+            v[u][b] = *reinterpret_cast<const float4 *>(src + (long long)(s0 + u) * GRAM_PARTIAL_FLOATS + b * 1024);
+        }
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int b = 0; b < 10; ++b) {
+          gsum[b][0] += v[u][b].x; gsum[b][1] += v[u][b].y;
+          gsum[b][2] += v[u][b].z; gsum[b][3] += v[u][b].w;
+        }
+    }
   }
-  double diag = 0.0;
 #pragma unroll
-  for (int j = 0; j < M; ++j) diag = (lane == j) ? row[j] : diag;
-  double tr = diag;
+  for (int I = 0; I < 4; ++I) {
+    __syncthreads();                              // Gs and Ts of the previous block are done with
+    // rows 32I .. 32I+31 of G (mirror blocks written transposed)
 #pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) tr += __shfl_xor(tr, d);
+    for (int J = 0; J < 4; ++J) {
+      const int blk = J >= I ? upper_block(I, J) : upper_block(J, I);
+      if (J >= I) {
+        double *d = &Gs[ii * GP + 32 * J + jj];
+        d[0] = gsum[blk][0]; d[1] = gsum[blk][1]; d[2] = gsum[blk][2]; d[3] = gsum[blk][3];
+      } else {
+        Gs[(jj + 0) * GP + 32 * J + ii] = gsum[blk][0];
+        Gs[(jj + 1) * GP + 32 * J + ii] = gsum[blk][1];
+        Gs[(jj + 2) * GP + 32 * J + ii] = gsum[blk][2];
+        Gs[(jj + 3) * GP + 32 * J + ii] = gsum[blk][3];
+      }
+    }
+    __syncthreads();
+    // T_I = G_I Phi (32 x M)
+    for (int tile = wave; tile < 2 * CT; tile += 4) {
+      const int rt = tile / CT, ct = tile - rt * CT;
+      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll 8
+      for (int ks = 0; ks < D / 4; ++ks) {
+        const double a = Gs[(16 * rt + l16) * GP + 4 * ks + lq];
+        const double b = (double)PH[(4 * ks + lq) * M + 16 * ct + l16];
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Ts[(16 * rt + 4 * v + lq) * TP + 16 * ct + l16] = acc[v];
+    }
+    __syncthreads();
+    // S += Phi_I^T T_I
+#pragma unroll
+    for (int i = 0; i < ST; ++i) {
+      const int tile = wave + 4 * i;
+      if (tile < CT * CT) {
+        const int at = tile / CT, bt = tile - at * CT;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const double a = (double)PH[(32 * I + 4 * ks + lq) * M + 16 * at + l16];
+          const double b = Ts[(4 * ks + lq) * TP + 16 * bt + l16];
+          sacc[i] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, sacc[i], 0, 0, 0);
+        }
+      }
+    }
+  }
+  __syncthreads();                                // S takes the place of the staging buffers
+#pragma unroll
+  for (int i = 0; i < ST; ++i) {
+    const int tile = wave + 4 * i;
+    if (tile < CT * CT) {
+      const int at = tile / CT, bt = tile - at * CT;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Ss[(16 * at + 4 * v + lq) * SP + 16 * bt + l16] = sacc[i][v];
+    }
+  }
+  __syncthreads();
+
+  // ridge: rho = ridge_rel * trace(S) / M (every thread sums in the same order)
+  double tr = 0.0;
+  for (int a = 0; a < M; ++a) tr += Ss[a * SP + a];
   const double rho = (double)ridge_rel * tr / (double)M;
-  const double d0 = diag + rho;
-#pragma unroll
-  for (int j = 0; j < M; ++j) row[j] += (lane == j) ? rho : 0.0;
-  for (int idx = lane; idx < M * LP; idx += 64) Ls[idx] = 0.0;
-
-  // right-looking Cholesky in 16-column panels; the window shrinks by 16 per panel
-  double rsv = 0.0;                              // lane k: 1 / L[k][k] (0 for a dropped pivot)
-  int flag = 0;
-  if constexpr (M >= 64) chol_panel<64>(row, d0, M - 64, lane, Ls, LP, rsv, flag);
-  if constexpr (M >= 48) chol_panel<48>(row, d0, M - 48, lane, Ls, LP, rsv, flag);
-  if constexpr (M >= 32) chol_panel<32>(row, d0, M - 32, lane, Ls, LP, rsv, flag);
-  chol_panel<16>(row, d0, M - 16, lane, Ls, LP, rsv, flag);
-  // the substitution below reads what other lanes parked in LDS: keep the order
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-  // forward substitution, column oriented, same sliding window: v -= L[:, j] * y_j
-  const int ch = 64 * half + lane;
-  double v[64];
-#pragma unroll
-  for (int q = 0; q < 16; ++q) {
-    float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (4 * q < M) f = *reinterpret_cast<const float4 *>(phi + ch * M + 4 * q);
-    v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+  __syncthreads();
+  if (tid < M) {
+    const double v = Ss[tid * SP + tid] + rho;
+    Ss[tid * SP + tid] = v;
+    d0_s[tid] = v;
   }
-  uint16_t *wh = wt + (size_t)lhead * (W_TERMS * M * D);
-  if constexpr (M >= 64) fwd_panel<64>(v, M - 64, Ls, LP, rsv, wh, M, ch);
-  if constexpr (M >= 48) fwd_panel<48>(v, M - 48, Ls, LP, rsv, wh, M, ch);
-  if constexpr (M >= 32) fwd_panel<32>(v, M - 32, Ls, LP, rsv, wh, M, ch);
-  fwd_panel<16>(v, M - 16, Ls, LP, rsv, wh, M, ch);
+  __syncthreads();
 
-  if (half == 0 && lane == 0) {
+  // ---- 2. blocked Cholesky ----
+#pragma unroll 1
+  for (int p = 0; p < P; ++p) {
+    if (wave == 0) {
+      const int base = 16 * p;
+      const bool rowlane = lane < 16;
+      double row[16], lrow[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) row[j] = rowlane ? Ss[(base + lane) * SP + base + j] : 0.0;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        const double piv = readlane_f64(row[k], k);
+        const double d0k = d0_s[base + k];
+        const bool ok = piv > PIVOT_REL * d0k && piv < 1.0e300;      // false for NaN too
+        const double rs = ok ? rsqrt(piv) : 0.0;
+        if (lane == k) rs_s[base + k] = rs;
+        if (!ok && lane == 0) flag_s = COMPACTOR_STATUS_PIVOT;
+        const double lk = (rowlane && lane >= k) ? row[k] * rs : 0.0;   // L[lane][k]
+        lrow[k] = lk;
+        wave_fence();
+        col_s[lane] = lk;
+        wave_fence();
+#pragma unroll
+        for (int j = k + 1; j < 16; ++j) row[j] -= lk * col_s[j];       // col_s[j] = L[j][k]
+      }
+      if (rowlane) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) Ss[(base + lane) * SP + base + k] = lrow[k];
+      }
+      wave_fence();
+      // X_pp = L_pp^{-1}: lane j solves column j by forward substitution
+      double x[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        double sum = (i == lane) ? 1.0 : 0.0;
+#pragma unroll
+        for (int k = 0; k < i; ++k) sum -= Ss[(base + i) * SP + base + k] * x[k];
+        x[i] = sum * rs_s[base + i];
+      }
+      if (rowlane) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Xs[(base + i) * SP + base + lane] = x[i];
+      }
+    }
+    __syncthreads();
+    // panel below the diagonal block: L_qp = A_qp X_pp^T
+    for (int q = p + 1 + wave; q < P; q += 4) {
+      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const double a = Ss[(16 * q + l16) * SP + 16 * p + 4 * ks + lq];
+        const double b = Xs[(16 * p + l16) * SP + 16 * p + 4 * ks + lq];
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Ss[(16 * q + 4 * v + lq) * SP + 16 * p + l16] = acc[v];
+    }
+    __syncthreads();
+    // trailing blocks: A_qr -= L_qp L_rp^T for p < r <= q
+    int t = 0;
+    for (int q = p + 1; q < P; ++q)
+      for (int r = p + 1; r <= q; ++r, ++t) {
+        if ((t & 3) != wave) continue;
+        f64x4 acc;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[v] = Ss[(16 * q + 4 * v + lq) * SP + 16 * r + l16];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const double a = -Ss[(16 * q + l16) * SP + 16 * p + 4 * ks + lq];
+          const double b = Ss[(16 * r + l16) * SP + 16 * p + 4 * ks + lq];
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Ss[(16 * q + 4 * v + lq) * SP + 16 * r + l16] = acc[v];
+      }
+    __syncthreads();
+  }
+
+  // ---- 3. the blocks of X = L^{-1} below the diagonal, block column `wave` ----
+  if (wave < P - 1) {
+    const int p = wave;
+    for (int q = p + 1; q < P; ++q) {
+      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+      for (int r = p; r < q; ++r) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const double a = Ss[(16 * q + l16) * SP + 16 * r + 4 * ks + lq];      // L_qr[i][k]
+          const double b = Xs[(16 * r + 4 * ks + lq) * SP + 16 * p + l16];      // X_rp[k][j]
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+        }
+      }
+      // X_qp = -X_qq acc: the result layout of acc is the B-operand layout of the next product
+      f64x4 out = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const double a = -Xs[(16 * q + l16) * SP + 16 * q + 4 * ks + lq];
+        out = __builtin_amdgcn_mfma_f64_16x16x4f64(a, acc[ks], out, 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Xs[(16 * q + 4 * v + lq) * SP + 16 * p + l16] = out[v];
+      wave_fence();            // the next block row of this column reads what was just written
+    }
+  }
+  __syncthreads();
+
+  // ---- 4. W^T = X Phi^T (M x 128), lower block triangle of X only ----
+  uint16_t *wh = wt + (size_t)lhead * (W_TERMS * M * D);
+  for (int tile = wave; tile < P * 8; tile += 4) {
+    const int mt = tile >> 3, ct = tile & 7;
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    for (int ks = 0; ks < 4 * (mt + 1); ++ks) {
+      const double a = Xs[(16 * mt + l16) * SP + 4 * ks + lq];
+      const double b = (double)PH[(16 * ct + l16) * M + 4 * ks + lq];
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int m = 16 * mt + 4 * v + lq, c = 16 * ct + l16;
+      float x = (float)acc[v];
+#pragma unroll
+      for (int tt = 0; tt < W_TERMS; ++tt) {
+        const uint16_t b = bf16_rne(x);
+        wh[(tt * M + m) * D + c] = b;
+        x -= bf16_to_f32(b);
+      }
+    }
+  }
+  if (tid == 0) {
     const Where w = locate_head(T, lhead);
-    status[T.s[w.seg].ghead0 + w.head] = flag;
+    status[T.s[w.seg].ghead0 + w.head] = flag_s;
   }
 }
 
@@ -340,17 +420,15 @@ static hipError_t launch_sketched(const SegTable &T, int tiles_per_wg, const flo
                                   const float *phi, float ridge_rel, double *s_parts,
                                   uint16_t *wt, int32_t *status, int *zero, long long zero_ints,
                                   hipStream_t st, hipEvent_t mid) {
-  hipLaunchKernelGGL((sketch_kernel<M>), dim3((unsigned)T.nheads * 4), dim3(256), 0, st, T,
-                     tiles_per_wg, partials, phi, s_parts, zero, zero_ints);
-  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  (void)s_parts;
   if (mid && hipEventRecord(mid, st) != hipSuccess) return hipErrorLaunchFailure;
-  hipLaunchKernelGGL((solve_wave_kernel<M>), dim3((unsigned)T.nheads * 2), dim3(64), 0, st, T, phi,
-                     ridge_rel, s_parts, wt, status);
+  hipLaunchKernelGGL((sketch_solve_kernel<M>), dim3((unsigned)T.nheads), dim3(256), 0, st, T,
+                     tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints);
   return hipGetLastError();
 }
 
-// Sketched mode: partial Gram blocks -> W^T in two kernels (see above).  `mid`, if not null, is
-// recorded between them (profiling).
+// Sketched mode: partial Gram blocks -> W^T in one kernel (see above).  `mid`, if not null, is
+// recorded before it (profiling: the separate reduce stage is empty in this mode).
 hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, const float *partials,
                                const float *phi, float ridge_rel, double *s_parts, uint16_t *wt,
                                int32_t *status, int *zero, long long zero_ints, hipStream_t st,
