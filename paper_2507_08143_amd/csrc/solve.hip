@@ -156,7 +156,9 @@ __global__ __launch_bounds__(256, 2) void sketch_solve_kernel(const SegTable T, 
                                                            int *__restrict__ zero,
                                                            long long zero_ints) {
   constexpr int P = M / 16, CT = M / 16;
-  constexpr int GP = D + 1, TP = M + 1, SP = M + 1;
+  // LDS pitches in doubles.  GP = 132 spreads the A-operand reads of G (16 rows x 4 k per
+  // instruction) over all banks: row stride 8 dwords mod 64, k stride 2.
+  constexpr int GP = D + 4, TP = M + 1, SP = M + 1;
   // the staging of G and T (step 1) and the matrices S, X (steps 2-4) share one region: two
   // workgroups fit a CU, so that the serial parts of one overlap the matrix work of the other
   constexpr int STAGE = 32 * GP + 32 * TP, FACT = 2 * M * SP;
@@ -229,33 +231,74 @@ __global__ __launch_bounds__(256, 2) void sketch_solve_kernel(const SegTable T, 
       }
     }
     __syncthreads();
-    // T_I = G_I Phi (32 x M)
-    for (int tile = wave; tile < 2 * CT; tile += 4) {
-      const int rt = tile / CT, ct = tile - rt * CT;
-      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll 8
-      for (int ks = 0; ks < D / 4; ++ks) {
-        const double a = Gs[(16 * rt + l16) * GP + 4 * ks + lq];
-        const double b = (double)PH[(4 * ks + lq) * M + 16 * ct + l16];
-        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
-      }
+    // T_I = G_I Phi (32 x M).  A wave runs two independent accumulation chains so that the
+    // matrix core always has a second MFMA to start: two tiles side by side, or the even and
+    // odd k-steps of a single tile.
+    {
+      const int t0 = wave, t1 = wave + 4;
+      const bool has0 = t0 < 2 * CT, two = t1 < 2 * CT;
+      if (has0) {
+        const int rt0 = t0 / CT, ct0 = t0 - rt0 * CT;
+        const int rt1 = two ? t1 / CT : rt0, ct1 = two ? t1 - (t1 / CT) * CT : ct0;
+        f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+        // chain c reads A from pa[c] + q * sa and B from pb[c] + q * sb at its step q
+        const int steps = two ? D / 4 : D / 8, sa = two ? 4 : 8, sb = (two ? 4 : 8) * M;
+        const double *pa0 = &Gs[(16 * rt0 + l16) * GP + lq];
+        const double *pa1 = two ? &Gs[(16 * rt1 + l16) * GP + lq] : pa0 + 4;
+        const float *pb0 = &PH[lq * M + 16 * ct0 + l16];
+        const float *pb1 = two ? &PH[lq * M + 16 * ct1 + l16] : pb0 + 4 * M;
+        // operands of 16 steps are fetched before their MFMAs (the scheduling barrier keeps
+        // the compiler from sinking the loads back next to their uses), so that one LDS
+        // latency is paid per 32 MFMAs and not per step
+        for (int q0 = 0; q0 < steps; q0 += 16) {
+          double a0[16], a1[16];
+          float b0[16], b1[16];
 #pragma unroll
-      for (int v = 0; v < 4; ++v) Ts[(16 * rt + 4 * v + lq) * TP + 16 * ct + l16] = acc[v];
-    }
-    __syncthreads();
-    // S += Phi_I^T T_I
+          for (int u = 0; u < 16; ++u) {
+            a0[u] = pa0[(q0 + u) * sa];
+            b0[u] = pb0[(q0 + u) * sb];
+            a1[u] = pa1[(q0 + u) * sa];
+            b1[u] = pb1[(q0 + u) * sb];
+          }
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < ST; ++i) {
-      const int tile = wave + 4 * i;
-      if (tile < CT * CT) {
-        const int at = tile / CT, bt = tile - at * CT;
+          for (int u = 0; u < 16; ++u) {
+            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0[u], (double)b0[u], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[u], (double)b1[u], acc1, 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (!two) acc0 += acc1;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const double a = (double)PH[(32 * I + 4 * ks + lq) * M + 16 * at + l16];
-          const double b = Ts[(4 * ks + lq) * TP + 16 * bt + l16];
-          sacc[i] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, sacc[i], 0, 0, 0);
+        for (int v = 0; v < 4; ++v) Ts[(16 * rt0 + 4 * v + lq) * TP + 16 * ct0 + l16] = acc0[v];
+        if (two) {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) Ts[(16 * rt1 + 4 * v + lq) * TP + 16 * ct1 + l16] = acc1[v];
         }
       }
+    }
+    __syncthreads();
+    // S += Phi_I^T T_I: the wave's tiles side by side, operands fetched ahead as above
+    {
+      float pa[8][ST];
+      double tb[8][ST];
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+        for (int i = 0; i < ST; ++i) {
+          const int tile = wave + 4 * i;
+          const int at = tile < CT * CT ? tile / CT : 0, bt = tile < CT * CT ? tile - at * CT : 0;
+          pa[ks][i] = PH[(32 * I + 4 * ks + lq) * M + 16 * at + l16];
+          tb[ks][i] = Ts[(4 * ks + lq) * TP + 16 * bt + l16];
+        }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+        for (int i = 0; i < ST; ++i)
+          if (wave + 4 * i < CT * CT)
+            sacc[i] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)pa[ks][i], tb[ks][i], sacc[i], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
   __syncthreads();                                // S takes the place of the staging buffers
@@ -291,10 +334,11 @@ __global__ __launch_bounds__(256, 2) void sketch_solve_kernel(const SegTable T, 
       double row[16], lrow[16];
 #pragma unroll
       for (int j = 0; j < 16; ++j) row[j] = rowlane ? Ss[(base + lane) * SP + base + j] : 0.0;
+      const double d0_mine = rowlane ? d0_s[base + lane] : 0.0;
 #pragma unroll
       for (int k = 0; k < 16; ++k) {
         const double piv = readlane_f64(row[k], k);
-        const double d0k = d0_s[base + k];
+        const double d0k = readlane_f64(d0_mine, k);
         const bool ok = piv > PIVOT_REL * d0k && piv < 1.0e300;      // false for NaN too
         const double rs = ok ? rsqrt(piv) : 0.0;
         if (lane == k) rs_s[base + k] = rs;
@@ -389,14 +433,7 @@ __global__ __launch_bounds__(256, 2) void sketch_solve_kernel(const SegTable T, 
 
   // ---- 4. W^T = X Phi^T (M x 128), lower block triangle of X only ----
   uint16_t *wh = wt + (size_t)lhead * (W_TERMS * M * D);
-  for (int tile = wave; tile < P * 8; tile += 4) {
-    const int mt = tile >> 3, ct = tile & 7;
-    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-    for (int ks = 0; ks < 4 * (mt + 1); ++ks) {
-      const double a = Xs[(16 * mt + l16) * SP + 4 * ks + lq];
-      const double b = (double)PH[(16 * ct + l16) * M + 4 * ks + lq];
-      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
-    }
+  auto emit = [&](int mt, int ct, const f64x4 &acc) {
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int m = 16 * mt + 4 * v + lq, c = 16 * ct + l16;
@@ -408,6 +445,22 @@ __global__ __launch_bounds__(256, 2) void sketch_solve_kernel(const SegTable T, 
         x -= bf16_to_f32(b);
       }
     }
+  };
+  // a wave takes the column tiles ct = wave and wave + 4 of every row block: two chains
+#pragma unroll
+  for (int mt = 0; mt < P; ++mt) {
+    f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+    const int ct0 = wave, ct1 = wave + 4;
+#pragma unroll
+    for (int ks = 0; ks < 4 * (mt + 1); ++ks) {
+      const double a = Xs[(16 * mt + l16) * SP + 4 * ks + lq];
+      const double b0 = (double)PH[(16 * ct0 + l16) * M + 4 * ks + lq];
+      const double b1 = (double)PH[(16 * ct1 + l16) * M + 4 * ks + lq];
+      acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b0, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b1, acc1, 0, 0, 0);
+    }
+    emit(mt, ct0, acc0);
+    emit(mt, ct1, acc1);
   }
   if (tid == 0) {
     const Where w = locate_head(T, lhead);
