@@ -5,8 +5,9 @@
 // (12 + 12 + 8 bits, LDS histograms), followed by an ordered emit: tokens above the threshold
 // key, plus the lowest-indexed tokens equal to it until k_keep is reached, written in
 // ascending token order.  Ties therefore go to the lower index, deterministically.
-// One workgroup of 1024 threads per head; heads of up to 32768 tokens read their scores once
-// and keep the keys in LDS (128 KB) for the later passes.
+// Heads of up to 32768 tokens get one workgroup of 1024 threads each, which reads the scores
+// once and keeps the keys in LDS (128 KB) for the later passes; longer heads, and selection
+// across the heads of a layer, are shared by several workgroups (second half of this file).
 #include "common.h"
 
 namespace cmp {
@@ -105,93 +106,95 @@ __device__ int radix_pass(const float *__restrict__ sp, uint32_t *keys, int n, i
   return find_digit(hist, nb, need, wsum, found);
 }
 
-// Ordered emit: tokens above the threshold key, plus the first need_eq tokens equal to it, in
-// ascending token order; 4 consecutive tokens per thread per round.
-template <bool FROM_LDS>
-__device__ void emit_kept(const float *__restrict__ sp, const uint32_t *keys, int n, int k,
-                          uint32_t thr, int need_eq, int32_t *__restrict__ out, int *wsum) {
-  const int tid = threadIdx.x;
-  int carry_gt = 0, carry_eq = 0;
-  for (int base = 0; base < n; base += 4 * SELECT_THREADS) {
-    const int i0 = base + 4 * tid;
-    uint32_t key[4];
-    int gt = 0, eq = 0;
-    if (FROM_LDS && i0 + 3 < n) {
+// Ordered emit for keys resident in LDS (n <= LDS_KEYS).  Token order is (round, wave, lane,
+// element) with 4096 tokens per round, so a token's output position is the sum of the counts of
+// the rounds before it, of the waves before it in its round, of the lanes before it in its wave
+// and of the elements before it in its lane: a wave scan per round plus one scan of the table of
+// (round, wave) counts.  Counts are packed as (above | equal << 16), at most 32768 each.
+// Every thread holds its keys in registers by then, so the key array is free to collect the
+// retained token indices in order; they leave as one coalesced run.
+__device__ void emit_kept_lds(uint32_t *keys, int n, int k, uint32_t thr, int need_eq,
+                              int32_t *__restrict__ out, unsigned *table) {
+  constexpr int NW = SELECT_THREADS / 64, R = LDS_KEYS / (4 * SELECT_THREADS);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint32_t key[R][4];
+  unsigned before[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int i0 = 4 * (r * SELECT_THREADS + tid);
+    if (4 * r * SELECT_THREADS >= n) {             // uniform: a round past the end of the head
+      before[r] = 0;
+      if (lane == 63) table[r * NW + wave] = 0;
+      continue;
+    }
+    if (i0 + 3 < n) {
       const uint4 kv = *reinterpret_cast<const uint4 *>(keys + i0);
-      key[0] = kv.x; key[1] = kv.y; key[2] = kv.z; key[3] = kv.w;
-    } else if (!FROM_LDS && i0 + 3 < n && (reinterpret_cast<uintptr_t>(sp) & 15u) == 0) {
-      const float4 f = *reinterpret_cast<const float4 *>(sp + i0);
-      key[0] = score_key(f.x); key[1] = score_key(f.y); key[2] = score_key(f.z); key[3] = score_key(f.w);
+      key[r][0] = kv.x; key[r][1] = kv.y; key[r][2] = kv.z; key[r][3] = kv.w;
     } else {
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        key[q] = i0 + q < n ? (FROM_LDS ? keys[i0 + q] : score_key(sp[i0 + q])) : 0u;
+      for (int q = 0; q < 4; ++q) key[r][q] = i0 + q < n ? keys[i0 + q] : 0u;
     }
+    unsigned mine = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const bool v = i0 + q < n;
+      mine += (v && key[r][q] > thr) ? 1u : 0u;
+      mine += (v && key[r][q] == thr) ? 0x10000u : 0u;
+    }
+    unsigned inc = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const unsigned o = __shfl_up(inc, d);
+      if (lane >= d) inc += o;
+    }
+    before[r] = inc - mine;
+    if (lane == 63) table[r * NW + wave] = inc;
+  }
+  __syncthreads();                   // all keys are in registers; the table is complete
+  if (wave == 0) {                   // exclusive scan of the R * NW entries, 2 per lane
+    constexpr int PER = (R * NW + 63) / 64;
+    unsigned v[PER], sum = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int idx = lane * PER + i;
+      v[i] = idx < R * NW ? table[idx] : 0u;
+      sum += v[i];
+    }
+    unsigned inc = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const unsigned o = __shfl_up(inc, d);
+      if (lane >= d) inc += o;
+    }
+    unsigned run = inc - sum;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int idx = lane * PER + i;
+      if (idx < R * NW) table[idx] = run;
+      run += v[i];
+    }
+  }
+  __syncthreads();
+  int32_t *stage = reinterpret_cast<int32_t *>(keys);
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int i0 = 4 * (r * SELECT_THREADS + tid);
+    if (4 * r * SELECT_THREADS >= n) break;          // uniform
+    const unsigned p = table[r * NW + wave] + before[r];
+    int pg = (int)(p & 0xffffu), pe = (int)(p >> 16);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       if (i0 + q < n) {
-        gt += key[q] > thr;
-        eq += key[q] == thr;
-      }
-    }
-    int total;
-    const int packed = block_exclusive_scan(gt | (eq << 16), wsum, &total);
-    int pg = carry_gt + (packed & 0xffff), pe = carry_eq + (packed >> 16);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (i0 + q < n) {
-        const bool is_gt = key[q] > thr, is_eq = key[q] == thr;
+        const bool is_gt = key[r][q] > thr, is_eq = key[r][q] == thr;
         const int pos = pg + min(pe, need_eq);
-        if ((is_gt || (is_eq && pe < need_eq)) && pos < k) out[pos] = i0 + q;
+        if ((is_gt || (is_eq && pe < need_eq)) && pos < k) stage[pos] = i0 + q;
         pg += is_gt;
         pe += is_eq;
       }
     }
-    carry_gt += total & 0xffff;
-    carry_eq += total >> 16;
-  }
-}
-
-// Second radix pass for heads too long for LDS: histogram of key bits 19..8 among the keys whose
-// top digit is d1, and at the same time those keys are compacted into LDS (wave ballot +
-// one LDS atomic per wave) so that the last pass need not read global memory again.
-__device__ int radix_pass2_collect(const float *__restrict__ sp, uint32_t *keys, int n, uint32_t d1,
-                                   int *need, int *hist, int *wsum, int *found, int *ncand_s,
-                                   int *ncand) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  for (int i = tid; i < 4096; i += SELECT_THREADS) hist[i] = 0;
-  if (tid == 0) *ncand_s = 0;
-  __syncthreads();
-  auto take = [&](uint32_t k, bool valid) {
-    const bool c = valid && (k >> 20) == d1;
-    const unsigned long long m = __ballot(c);
-    if (m) {
-      int base = 0;
-      if (lane == __ffsll((long long)m) - 1) base = atomicAdd(ncand_s, __popcll(m));
-      base = __shfl(base, __ffsll((long long)m) - 1);
-      if (c) {
-        atomicAdd(&hist[(k >> 8) & 0xfff], 1);
-        const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
-        if (pos < LDS_KEYS) keys[pos] = k;
-      }
-    }
-  };
-  const bool vec = (reinterpret_cast<uintptr_t>(sp) & 15u) == 0;
-  const int nv = vec ? n >> 2 : 0;
-  for (int i0 = 0; i0 < nv; i0 += SELECT_THREADS) {       // uniform trip count: ballots inside
-    const int i = i0 + tid;
-    float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < nv) f = reinterpret_cast<const float4 *>(sp)[i];
-    take(score_key(f.x), i < nv); take(score_key(f.y), i < nv);
-    take(score_key(f.z), i < nv); take(score_key(f.w), i < nv);
-  }
-  for (int i0 = 4 * nv; i0 < n; i0 += SELECT_THREADS) {
-    const int i = i0 + tid;
-    take(i < n ? score_key(sp[i]) : 0u, i < n);
   }
   __syncthreads();
-  *ncand = *ncand_s;
-  return find_digit(hist, 4096, need, wsum, found);
+  for (int j = tid; j < k; j += SELECT_THREADS) out[j] = stage[j];
 }
 
 __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T,
@@ -203,7 +206,6 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T
   __shared__ int hist[4096];
   __shared__ int wsum[SELECT_THREADS / 64];
   __shared__ int found[2];
-  __shared__ int ncand_s;
 
   const Where w = locate_block(T, blockIdx.x, 0, 1, false);
   const Seg &s = T.s[w.seg];
@@ -212,9 +214,8 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T
   int32_t *out = kept_idx + (s.kept_off + (long long)w.head * k);
   const int tid = threadIdx.x;
   if (tid == 0) kept_cnt[s.ghead0 + w.head] = k;
-  const bool small = n <= LDS_KEYS;      // one read of the scores; everything else out of LDS
-
-  // threshold key = the k-th largest, by three radix passes (12 + 12 + 8 bits)
+  // threshold key = the k-th largest, by three radix passes (12 + 12 + 8 bits); the scores are
+  // read once and their keys stay in LDS for the later passes (n <= LDS_KEYS, checked on the host)
   int need = k;
   uint32_t d1, d2, d3;
   if (hist1 != nullptr) {                // first digit already tallied by the score kernel
@@ -222,27 +223,13 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T
     for (int i = tid; i < HIST1_BINS; i += SELECT_THREADS) hist[i] = h1[i];
     __syncthreads();
     d1 = find_digit(hist, HIST1_BINS, &need, wsum, found);
-  } else if (small) {
+    d2 = radix_pass<false, true>(sp, keys, n, 8, 12, 20, d1, &need, hist, wsum, found);
+  } else {
     d1 = radix_pass<false, true>(sp, keys, n, 20, 12, 32, 0u, &need, hist, wsum, found);
-  } else {
-    d1 = radix_pass<false, false>(sp, keys, n, 20, 12, 32, 0u, &need, hist, wsum, found);
+    d2 = radix_pass<true, false>(sp, keys, n, 8, 12, 20, d1, &need, hist, wsum, found);
   }
-  if (small) {
-    if (hist1 != nullptr)
-      d2 = radix_pass<false, true>(sp, keys, n, 8, 12, 20, d1, &need, hist, wsum, found);
-    else
-      d2 = radix_pass<true, false>(sp, keys, n, 8, 12, 20, d1, &need, hist, wsum, found);
-    d3 = radix_pass<true, false>(sp, keys, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
-    emit_kept<true>(sp, keys, n, k, (d1 << 20) | (d2 << 8) | d3, need, out, wsum);
-  } else {
-    int ncand;
-    d2 = radix_pass2_collect(sp, keys, n, d1, &need, hist, wsum, found, &ncand_s, &ncand);
-    if (ncand <= LDS_KEYS)               // the candidates (top digit d1) sit in LDS
-      d3 = radix_pass<true, false>(sp, keys, ncand, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
-    else
-      d3 = radix_pass<false, false>(sp, keys, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
-    emit_kept<false>(sp, keys, n, k, (d1 << 20) | (d2 << 8) | d3, need, out, wsum);
-  }
+  d3 = radix_pass<true, false>(sp, keys, n, 0, 8, 8, (d1 << 12) | d2, &need, hist, wsum, found);
+  emit_kept_lds(keys, n, k, (d1 << 20) | (d2 << 8) | d3, need, out, reinterpret_cast<unsigned *>(hist));
 }
 
 // ---- selection by several workgroups per pool ------------------------------------------------
@@ -738,6 +725,7 @@ hipError_t launch_select_pools(const SegTable &T, const float *scores, int *hist
 hipError_t launch_select(const SegTable &T, const float *scores, const int *hist1,
                          int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st) {
   if (T.nheads <= 0) return hipSuccess;
+  if (select_needs_pools(T)) return hipErrorInvalidValue;     // longer heads: launch_select_pools
   hipLaunchKernelGGL(select_kernel, dim3((unsigned)T.nheads), dim3(SELECT_THREADS), 0, st, T,
                      scores, hist1, kept_idx, kept_cnt);
   return hipGetLastError();
