@@ -703,3 +703,25 @@ def test_compress_replays_from_a_hip_graph(C):
             assert torch.equal(gb[name], eb[name]), "replay %d: %s differs from the eager call" % (rep, name)
         assert torch.equal(gb["k_packed"].view(torch.int16), eb["k_packed"].view(torch.int16))
         assert torch.equal(gb["v_packed"].view(torch.int16), eb["v_packed"].view(torch.int16))
+
+
+def test_pooled_select_edges_and_regrouping(C):
+    _say("pooled selection: k = 1, k = n, n just past one workgroup's reach; layer scope in small head groups")
+    mk = lambda r, m: r.standard_normal(m)
+    _select_case(C, [32769, 40000, 65537], [1.0 / 32769, 1.0, 0.5], 1, 2, mk, 8)
+    _select_case(C, [32769, 40000], [1.0 / 32769, 1.0], 1, 2, mk, 9, scope=C.SCOPE_LAYER)
+    _select_case(C, [3, 2], [1.0 / 3, 1.0], 2, 2, mk, 10, scope=C.SCOPE_LAYER)
+    # fused call cut into groups of one layer each: every group's selection is still the
+    # oracle's selection of that run's scores
+    w = W.config2(DEV, L=3, H=4, n=2000)
+    params, reqs = U.make_call(C, w, DEV, group_bytes=4 * 2000 * 256)
+    params.select_scope = C.SCOPE_LAYER
+    for streams in (0, 2):
+        params.streams = streams
+        out = C.compactor_compress(params, reqs, want_scores=True)
+        torch.cuda.synchronize()
+        so, ko, kk = C.compactor_layout(params, reqs)
+        _check_layer_selection(C, out["scores"].cpu().numpy(), out["kept_idx"].cpu().numpy(),
+                               out["kept_cnt"].cpu().numpy(), ko[0], kk[0], 0, 3, 4, 2000,
+                               "grouped layer scope, streams=%d" % streams)
+        assert int(out["status"].max()) == 0
