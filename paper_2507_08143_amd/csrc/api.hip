@@ -120,7 +120,7 @@ GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bo
   GroupBytes g;
   g.partials = align_up(((size_t)gram_plan(p, T, compute_units()).nwg + T.nheads) *
                         GRAM_PARTIAL_FLOATS * sizeof(float));
-  g.g64 = align_up((size_t)T.nheads * D * D * sizeof(double));
+  g.g64 = ks > 0 ? 0 : align_up((size_t)T.nheads * D * D * sizeof(double));   // exact mode only
   g.wt = align_up((size_t)T.nheads * W_TERMS * m * D * sizeof(uint16_t));
   g.hist1 = align_up((size_t)T.nheads * HIST1_BINS * sizeof(int));
   g.sel = align_up((size_t)select_scratch(T).ints() * sizeof(int));
@@ -298,8 +298,8 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   MARK(m, COMPACTOR_STAGE_GRAM + 1);
   if (p->sketch_dim > 0) {
     hipEvent_t mid = m.ev ? static_cast<hipEvent_t>(m.ev[COMPACTOR_STAGE_REDUCE + 1]) : nullptr;
-    HIP_TRY(launch_sketch_solve(T, p->sketch_dim, rpw, partials, p->phi, p->ridge_rel, g64, wt,
-                                status, zero, zero_ints, st, mid));
+    HIP_TRY(launch_sketch_solve(T, p->sketch_dim, rpw, partials, p->phi, p->ridge_rel, wt, status,
+                                zero, zero_ints, st, mid));
   } else {
     HIP_TRY(launch_gram_reduce(T, rpw, partials, g64, zero, zero_ints, st));
     MARK(m, COMPACTOR_STAGE_REDUCE + 1);

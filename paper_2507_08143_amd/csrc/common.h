@@ -260,11 +260,10 @@ hipError_t launch_gram_reduce(const SegTable &T, int tiles_per_wg, const float *
 hipError_t launch_solve(const SegTable &T, float ridge_rel, const double *g64, uint16_t *wt,
                         int32_t *status, hipStream_t st);
 
-// Sketched mode: partial Gram blocks -> S = Phi^T G Phi (4 contributions per head in s_parts)
-// -> W^T ([term][k_s][128] per head) and status.  `mid`, if not null, is recorded between the
-// two kernels.
+// Sketched mode: partial Gram blocks -> S = Phi^T G Phi + rho I -> W^T ([term][k_s][128] per
+// head) and status, in one kernel.  `mid`, if not null, is recorded before it.
 hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, const float *partials,
-                               const float *phi, float ridge_rel, double *s_parts, uint16_t *wt,
+                               const float *phi, float ridge_rel, uint16_t *wt,
                                int32_t *status, int *zero, long long zero_ints, hipStream_t st,
                                hipEvent_t mid);
 

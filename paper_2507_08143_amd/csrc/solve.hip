@@ -470,10 +470,9 @@ __global__ __launch_bounds__(256, 2) void sketch_solve_kernel(const SegTable T, 
 
 template <int M>
 static hipError_t launch_sketched(const SegTable &T, int tiles_per_wg, const float *partials,
-                                  const float *phi, float ridge_rel, double *s_parts,
-                                  uint16_t *wt, int32_t *status, int *zero, long long zero_ints,
+                                  const float *phi, float ridge_rel, uint16_t *wt,
+                                  int32_t *status, int *zero, long long zero_ints,
                                   hipStream_t st, hipEvent_t mid) {
-  (void)s_parts;
   if (mid && hipEventRecord(mid, st) != hipSuccess) return hipErrorLaunchFailure;
   hipLaunchKernelGGL((sketch_solve_kernel<M>), dim3((unsigned)T.nheads), dim3(256), 0, st, T,
                      tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints);
@@ -483,15 +482,15 @@ static hipError_t launch_sketched(const SegTable &T, int tiles_per_wg, const flo
 // Sketched mode: partial Gram blocks -> W^T in one kernel (see above).  `mid`, if not null, is
 // recorded before it (profiling: the separate reduce stage is empty in this mode).
 hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, const float *partials,
-                               const float *phi, float ridge_rel, double *s_parts, uint16_t *wt,
+                               const float *phi, float ridge_rel, uint16_t *wt,
                                int32_t *status, int *zero, long long zero_ints, hipStream_t st,
                                hipEvent_t mid) {
   if (T.nheads <= 0) return hipSuccess;
   switch (ks) {
-    case 16: return launch_sketched<16>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, zero, zero_ints, st, mid);
-    case 32: return launch_sketched<32>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, zero, zero_ints, st, mid);
-    case 48: return launch_sketched<48>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, zero, zero_ints, st, mid);
-    case 64: return launch_sketched<64>(T, tiles_per_wg, partials, phi, ridge_rel, s_parts, wt, status, zero, zero_ints, st, mid);
+    case 16: return launch_sketched<16>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st, mid);
+    case 32: return launch_sketched<32>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st, mid);
+    case 48: return launch_sketched<48>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st, mid);
+    case 64: return launch_sketched<64>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st, mid);
     default: return hipErrorInvalidValue;
   }
 }
