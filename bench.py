@@ -307,6 +307,30 @@ def main():
             stage_ms[k_] = stage_ms.get(k_, 0.0) + v_ / a.steps
     ms_per_step_ev = (time.perf_counter() - t1) / a.steps * 1e3
 
+    # the three unfused calls on the same buffers (scores then travel through HBM once more)
+    unfused = None
+    if True:
+        scores = torch.empty(so[-1], dtype=torch.float32, device=dev)
+        ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        acc = [0.0, 0.0, 0.0]
+        for i in range(a.warmup + a.steps):
+            ev0[0].record()
+            C.compactor_score(params, reqs, scores=scores, status=bufs["status"], workspace=ws)
+            ev0[1].record()
+            C.compactor_select(params, reqs, scores, kept_idx=bufs["kept_idx"], kept_cnt=bufs["kept_cnt"],
+                               workspace=ws)
+            ev0[2].record()
+            C.compactor_compact(params, reqs, bufs["kept_idx"], bufs["kept_cnt"], bufs["k_packed"],
+                                bufs["v_packed"])
+            ev0[3].record()
+            torch.cuda.synchronize()
+            if i >= a.warmup:
+                for j in range(3):
+                    acc[j] += ev0[j].elapsed_time(ev0[j + 1]) / a.steps
+        unfused = {"score_ms": round(acc[0], 4), "select_ms": round(acc[1], 4),
+                   "compact_ms": round(acc[2], 4), "total_ms": round(sum(acc), 4)}
+        del scores
+
     sbytes, rows, kept = stage_bytes(w, kk)
     sflops = stage_flops(w, w.sketch_dim)
     dominant = max(sbytes, key=lambda s: stage_ms.get(s, 0.0))
@@ -341,6 +365,7 @@ def main():
         "mfma": {"path_TFLOP/s": sum(sflops.values()) / (ms_per_step * 1e-3) / 1e12,
                  "frac_of_bf16_peak": sum(sflops.values()) / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
         "stages": stages, "ms_per_step_with_events": ms_per_step_ev,
+        "unfused_calls": unfused,
     }
     if not a.no_cpu_baseline:
         from oracle import compactor_oracle as O
