@@ -725,3 +725,22 @@ def test_pooled_select_edges_and_regrouping(C):
                                out["kept_cnt"].cpu().numpy(), ko[0], kk[0], 0, 3, 4, 2000,
                                "grouped layer scope, streams=%d" % streams)
         assert int(out["status"].max()) == 0
+
+
+def test_sketched_scores_with_a_ridge(C):
+    _say("sketched mode with ridge_rel > 0: scores against the oracle and the closed-form sum")
+    for ks, ridge in ((48, 1e-3), (64, 0.05), (16, 1e-6)):
+        w = W.config5(DEV, L=1, H=2, n=2500)
+        w.sketch_dim, w.ridge_rel = ks, ridge
+        st, out = U.run_and_check(C, w, DEV)
+        # sum of ridge leverage scores = sum_j mu_j / (mu_j + rho), mu = eigenvalues of the factored Gram
+        phi = W.make_phi(ks=ks).double().numpy()
+        n = w.requests[0].n
+        for h in range(2):
+            K = O.bf16_bits_to_f64(W.bf16_bits(w.requests[0].k[0, h]))
+            mu = np.linalg.eigvalsh((K @ phi).T @ (K @ phi))
+            rho = float(np.float32(ridge)) * mu.sum() / ks
+            want = float(np.sum(mu / (mu + rho)))
+            got = float(out["scores"][h * n:(h + 1) * n].double().sum())
+            assert abs(got - want) <= 1e-3 * want, (ks, ridge, h, got, want)
+        _say("  k_s=%d ridge=%g: max rel err %.3g, swaps %d" % (ks, ridge, st["max_rel"], st["swaps"]))
