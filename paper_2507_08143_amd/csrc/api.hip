@@ -94,7 +94,10 @@ GramPlan gram_plan(const compactor_params_t *p, const SegTable &T, int cus) {
 // of W workgroups takes ceil(W / slots) rounds; the run length is chosen to keep the last
 // round full and the per-workgroup fixed cost (staging W^T, about 32 KB) small.
 int score_tokens_for(const compactor_params_t *p, const SegTable &T, int cus) {
-  if (p->score_tokens > 0) return (p->score_tokens + SCORE_STEP - 1) / SCORE_STEP * SCORE_STEP;
+  if (p->score_tokens > 0) {           // at most 32768: the kernel tallies in 16-bit counters
+    const int t = (p->score_tokens + SCORE_STEP - 1) / SCORE_STEP * SCORE_STEP;
+    return t > 32768 ? 32768 : t;
+  }
   const int slots = 2 * cus;
   int best = 4096;
   double best_score = -1.0;

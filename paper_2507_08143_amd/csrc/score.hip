@@ -39,8 +39,11 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
   constexpr int NSUB = 2, WTOK = 16 * NSUB, STEP = 4 * WTOK;     // tokens per wave / per WG step
   constexpr int NLD = WTOK * 16 / 64;                            // 16-B loads per lane per step
   __shared__ __attribute__((aligned(16))) uint16_t wl[W_TERMS * M * WPITCH];
-  __shared__ __attribute__((aligned(16))) uint16_t kl[4][WTOK * WPITCH];
-  __shared__ int hl[HIST1_BINS];     // first radix digit of the selection, tallied on the way out
+  // a wave stages 16 tokens at a time (its 32 tokens of a step in two halves); measured, a third
+  // workgroup per CU does not pay, the smaller staging buffer does on the long-context shapes
+  __shared__ __attribute__((aligned(16))) uint16_t kl[4][16 * WPITCH];
+  __shared__ unsigned hl[HIST1_BINS / 2];   // first radix digit of the selection, tallied on the
+                                            // way out: two 16-bit counters per word
 
   const Where w = locate_block(T, blockIdx.x, tokens_per_wg, SCORE_STEP, false);
   const Seg &s = T.s[w.seg];
@@ -69,7 +72,7 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
   load_step(0, stA);          // in flight while W^T is staged
   load_step(1, stB);
 
-  for (int i = tid; i < HIST1_BINS; i += 256) hl[i] = 0;
+  for (int i = tid; i < HIST1_BINS / 2; i += 256) hl[i] = 0;
   const uint16_t *wh = wt + (size_t)w.lhead * (W_TERMS * M * D);
   for (int cidx = tid; cidx < W_TERMS * M * 16; cidx += 256) {
     const int row = cidx >> 4, ch = cidx & 15;
@@ -87,16 +90,17 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
     // redistribute through the wave's LDS buffer: rows in, B operands out.  Lanes exchange
     // data here without a workgroup barrier (LDS operations of one wave execute in order), so
     // wave-scope fences keep the compiler from moving the reads and writes across each other.
-    wave_lds_fence();
 #pragma unroll
-    for (int i = 0; i < NLD; ++i)
-      *reinterpret_cast<uint4 *>(&kw[(ld_row + 4 * i) * WPITCH + ld_chunk * 8]) = stg[i];
-    wave_lds_fence();
+    for (int st = 0; st < NSUB; ++st) {
+      wave_lds_fence();
 #pragma unroll
-    for (int st = 0; st < NSUB; ++st)
+      for (int i = 0; i < NLD / NSUB; ++i)
+        *reinterpret_cast<uint4 *>(&kw[(ld_row + 4 * i) * WPITCH + ld_chunk * 8]) = stg[st * (NLD / NSUB) + i];
+      wave_lds_fence();
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        kb[st][kk] = *reinterpret_cast<const bf16x8 *>(&kw[(16 * st + t16) * WPITCH + 32 * kk + 8 * g]);
+        kb[st][kk] = *reinterpret_cast<const bf16x8 *>(&kw[t16 * WPITCH + 32 * kk + 8 * g]);
+    }
   };
   auto multiply = [&](int it) {
     float sums[NSUB];
@@ -134,7 +138,8 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
     if (g < 2 && tok < tok_end) {
       sp[tok] = x;
       bad |= !(fabsf(x) <= 3.0e38f);
-      atomicAdd(&hl[score_key(x) >> 20], 1);
+      const uint32_t bin = score_key(x) >> 20;
+      atomicAdd(&hl[bin >> 1], 1u << (16 * (bin & 1)));
     }
   };
 
@@ -155,7 +160,7 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
     __syncthreads();
     int *h1 = hist1 + (size_t)(w.lhead / pool_heads(T, s)) * HIST1_BINS;
     for (int i = tid; i < HIST1_BINS; i += 256) {
-      const int c = hl[i];
+      const int c = (int)((hl[i >> 1] >> (16 * (i & 1))) & 0xffffu);
       if (c) atomicAdd(&h1[i], c);
     }
   }
