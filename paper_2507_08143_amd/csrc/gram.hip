@@ -44,17 +44,17 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char *p) {
 //   wave 0: (0,0) (0,1) (0,2)   wave 1: (0,3) (1,1) (1,2)   wave 2: (1,3) (2,2)   wave 3: (2,3) (3,3)
 constexpr int GRAM_OCC = 2;         // waves per SIMD the register budget is set for
 constexpr int GRAM_TG_UNROLL = 4;   // 16-token steps unrolled together (more operands in flight)
-__global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, int tiles_per_wg,
-                                                             long long total,
-                                                             float *__restrict__ partials) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TILE_BYTES];
-
+// The body is compiled once per wave of the workgroup: which blocks a wave owns is then known
+// at compile time, and the accumulators stay in fixed registers (a run-time switch inside the
+// loop makes the compiler copy them at every join).
+template <int wave>
+__device__ __forceinline__ void gram_body(const SegTable &T, int tiles_per_wg, long long total,
+                                          float *__restrict__ partials, unsigned char *smem) {
   const long long g0 = (long long)blockIdx.x * tiles_per_wg;
   const int count = (int)min((long long)tiles_per_wg, total - g0);
   if (count <= 0) return;
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ld_row = tid >> 4, ld_chunk = tid & 15;   // loader: 16 lanes cover one 256-B row
 
   f32x16 acc[3];
@@ -95,12 +95,10 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
         const bf16x4 hi = lds_read_tr(p + cb * 64 + 4 * PITCH * 2);    // tokens 8g+4 .. 8g+7
         op[cb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
-      switch (wave) {
-        case 0: GRAM_MFMA(0, 0, 0); GRAM_MFMA(1, 0, 1); GRAM_MFMA(2, 0, 2); break;
-        case 1: GRAM_MFMA(0, 0, 3); GRAM_MFMA(1, 1, 1); GRAM_MFMA(2, 1, 2); break;
-        case 2: GRAM_MFMA(0, 1, 3); GRAM_MFMA(1, 2, 2); break;
-        default: GRAM_MFMA(0, 2, 3); GRAM_MFMA(1, 3, 3); break;
-      }
+      if constexpr (wave == 0) { GRAM_MFMA(0, 0, 0); GRAM_MFMA(1, 0, 1); GRAM_MFMA(2, 0, 2); }
+      if constexpr (wave == 1) { GRAM_MFMA(0, 0, 3); GRAM_MFMA(1, 1, 1); GRAM_MFMA(2, 1, 2); }
+      if constexpr (wave == 2) { GRAM_MFMA(0, 1, 3); GRAM_MFMA(1, 2, 2); }
+      if constexpr (wave == 3) { GRAM_MFMA(0, 2, 3); GRAM_MFMA(1, 3, 3); }
     }
   };
 #undef GRAM_MFMA
@@ -158,6 +156,19 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
     }
   }
   if (dirty) flush(T.s[C.seg].lhead0 + C.hh);
+}
+
+__global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, int tiles_per_wg,
+                                                             long long total,
+                                                             float *__restrict__ partials) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TILE_BYTES];
+  // every wave passes the same workgroup barriers, each in its own copy of the loop
+  switch (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) {
+    case 0: gram_body<0>(T, tiles_per_wg, total, partials, smem); break;
+    case 1: gram_body<1>(T, tiles_per_wg, total, partials, smem); break;
+    case 2: gram_body<2>(T, tiles_per_wg, total, partials, smem); break;
+    default: gram_body<3>(T, tiles_per_wg, total, partials, smem); break;
+  }
 }
 
 // Order in which the waves own the upper blocks, as (I, J) per stored block number.
