@@ -47,7 +47,8 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
 
   const Where w = locate_block(T, blockIdx.x, tokens_per_wg, SCORE_STEP, false);
   const Seg &s = T.s[w.seg];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int t16 = lane & 15, g = lane >> 4;
   const int n = s.n;
   const int tok_begin = w.tile * w.chunk;
@@ -57,14 +58,24 @@ __global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tok
   const uint16_t *kp = head_ptr(s.k_score, s, w.head);
   const int ld_row = lane >> 4, ld_chunk = lane & 15;            // loader: 16 lanes per row
 
+  // this lane's piece of its first row; later rows are wave-uniform offsets away
+  const uint16_t *lane_base =
+      kp + (long long)(tok_begin + wave * WTOK + ld_row) * stride_t + ld_chunk * 8;
+  const long long row4 = 4 * stride_t, step_stride = (long long)STEP * stride_t;
   auto load_step = [&](int it, uint4 (&stg)[NLD]) {
     const int base = tok_begin + it * STEP + wave * WTOK + ld_row;
+    const uint16_t *p = lane_base + it * step_stride;
+    // wave-uniform: all 32 rows of the wave exist (every step but a head's last)
+    if (it < nsteps && tok_begin + it * STEP + (wave + 1) * WTOK <= tok_end) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int tok = base + 4 * i;
-      stg[i] = make_uint4(0, 0, 0, 0);
-      if (it < nsteps && tok < tok_end)
-        stg[i] = load_stream16(kp + (long long)tok * stride_t + ld_chunk * 8);
+      for (int i = 0; i < NLD; ++i) stg[i] = load_stream16(p + i * row4);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int tok = base + 4 * i;
+        stg[i] = make_uint4(0, 0, 0, 0);
+        if (it < nsteps && tok < tok_end) stg[i] = load_stream16(p + i * row4);
+      }
     }
   };
 
