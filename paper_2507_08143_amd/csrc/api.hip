@@ -94,14 +94,14 @@ GramPlan gram_plan(const compactor_params_t *p, const SegTable &T, int cus) {
 // of W workgroups takes ceil(W / slots) rounds; the run length is chosen to keep the last
 // round full and the per-workgroup fixed cost (staging W^T, about 32 KB) small.
 int score_tokens_for(const compactor_params_t *p, const SegTable &T, int cus) {
-  if (p->score_tokens > 0) {           // at most 32768: the kernel tallies in 16-bit counters
+  if (p->score_tokens > 0) {           // at most SCORE_MAX_TOKENS: a workgroup's scores wait in LDS
     const int t = (p->score_tokens + SCORE_STEP - 1) / SCORE_STEP * SCORE_STEP;
-    return t > 32768 ? 32768 : t;
+    return t > SCORE_MAX_TOKENS ? SCORE_MAX_TOKENS : t;
   }
   const int slots = 2 * cus;
-  int best = 4096;
+  int best = SCORE_MAX_TOKENS;
   double best_score = -1.0;
-  for (int c = 4096; c >= 1024; c -= SCORE_STEP) {
+  for (int c = SCORE_MAX_TOKENS; c >= 1024; c -= SCORE_STEP) {
     const double w = (double)total_blocks(T, c, SCORE_STEP, false);
     const double rounds = ceil(w / slots);
     const double score = w / (rounds * slots) * (c * 256.0) / (c * 256.0 + 32768.0);

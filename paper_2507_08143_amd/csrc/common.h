@@ -23,6 +23,7 @@ constexpr int W_TERMS = CMP_W_TERMS;  // W^T is carried as a sum of this many bf
 constexpr int GRAM_PARTIAL_FLOATS = 10 * 32 * 32;   // upper blocks of one partial Gram matrix
 constexpr int GRAM_TILE = 64;         // rows staged in LDS per step of the Gram kernel
 constexpr int SCORE_STEP = 128;       // tokens a score workgroup multiplies per step
+constexpr int SCORE_MAX_TOKENS = 4096;   // most tokens a score workgroup takes (their scores wait in LDS)
 constexpr int SELECT_THREADS = 1024;
 constexpr int GATHER_ROWS = 64;       // kept rows per gather workgroup
 
