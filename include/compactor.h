@@ -94,7 +94,8 @@ typedef struct compactor_params {
                              many bytes so that the second pass over a group's keys hits the
                              last-level cache; 0 = library default */
   int32_t gram_wgs;       /* tuning: workgroups of the persistent Gram kernel and target tokens */
-  int32_t score_tokens;   /* per workgroup of the score kernel; 0 = chosen by the library */
+  int32_t score_tokens;   /* per workgroup of the score kernel (at most 4096; larger values are
+                             clamped); 0 = chosen by the library */
   int32_t streams;        /* concurrency: 0 or 1 = every kernel on the caller's stream.  2..4 = head
                              groups are spread over that many lanes (the caller's stream plus
                              helper streams that the library creates once per device and keeps),
