@@ -14,6 +14,9 @@
  *   select   per-head top-ceil(r*N) of s (Sec. 3.3, "KV selection")
  *   compact  gather of the retained K/V rows into a packed cache
  *   compress the three fused on one stream
+ * and, beyond that path: the attention-based scores a themselves (Sec. 3.2), head-adaptive
+ * selection across the heads of a layer (Sec. 3.3), a paged destination for the compaction,
+ * and the Hadamard right-sketch of App. D.
  *
  * General conventions
  *   - Every pointer marked "device" is GPU memory owned by the caller; every
