@@ -146,6 +146,13 @@ __device__ __forceinline__ const uint16_t *head_ptr(const uint16_t *base, const 
   return base + (long long)l * s.stride_l + (long long)h * s.stride_h;
 }
 
+// Inside a stored 32x32 block of a partial Gram matrix the elements are in MFMA accumulator
+// order: float4 number f (0..255) holds rows row0 .. row0+3 of one column.
+__host__ __device__ __forceinline__ void partial_quad(int f, int &row0, int &col) {
+  row0 = 8 * (f >> 6) + 4 * ((f >> 5) & 1);
+  col = f & 31;
+}
+
 // Stored order of the 10 upper 32x32 blocks of a partial Gram matrix.
 __host__ __device__ __forceinline__ int upper_block(int I, int J) {
   return I * 4 - (I * (I - 1)) / 2 + (J - I);

@@ -112,7 +112,9 @@ __device__ __forceinline__ void gram_body(const SegTable &T, int tiles_per_wg, l
   // 32x32 accumulator layout: register v of lane l is element (8*(v>>2) + 4*(l>>5) + (v&3), l&31).
   const int nblk = wave < 2 ? 3 : 2;
   const int first = wave == 0 ? 0 : (wave == 1 ? 3 : (wave == 2 ? 6 : 8));
-  const int col = lane & 31, rsub = 4 * (lane >> 5);
+  // A block is stored in accumulator order: float4 number 64*q + lane of a block holds rows
+  // 8q + 4*(lane>>5) .. +3 of column lane & 31, so a flush is 16-byte stores, 1 KB per wave
+  // instruction (see partial_quad in common.h for the readers).
   auto flush = [&](int lhead) {
     float *out = partials + ((size_t)blockIdx.x + lhead) * GRAM_PARTIAL_FLOATS;
 #pragma unroll
@@ -120,9 +122,10 @@ __device__ __forceinline__ void gram_body(const SegTable &T, int tiles_per_wg, l
       if (b < nblk) {
         float *ob = out + (first + b) * GBLK;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          ob[(8 * (v >> 2) + rsub + (v & 3)) * 32 + col] = acc[b][v];
-          acc[b][v] = 0.f;
+        for (int q = 0; q < 4; ++q) {
+          *reinterpret_cast<float4 *>(ob + (64 * q + lane) * 4) =
+              make_float4(acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]);
+          acc[b][4 * q] = acc[b][4 * q + 1] = acc[b][4 * q + 2] = acc[b][4 * q + 3] = 0.f;
         }
       }
     }
@@ -189,8 +192,9 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const SegTable T, int 
   zero_slice(zero, zero_ints);   // histograms that the score and selection kernels add into
   int nsplit;
   const long long pb = partial_base(T, lhead, tiles_per_wg, nsplit);
-  const int e = threadIdx.x * 4;                 // 4 consecutive elements of the block
-  const int ii = e >> 5, jj = e & 31;
+  const int e = threadIdx.x * 4;                 // this thread's float4 of the block
+  int row0, col;
+  partial_quad(threadIdx.x, row0, col);          // it holds rows row0 .. row0+3 of column col
   double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
   for (int sidx = 0; sidx < nsplit; ++sidx) {
     const float4 p = *reinterpret_cast<const float4 *>(partials + (pb + sidx) * (10 * GBLK) +
@@ -199,13 +203,14 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const SegTable T, int 
   }
   const int I = kBlockI[blk], J = kBlockJ[blk];
   double *G = g64 + (size_t)lhead * (D * D);
-  double *o = G + (32 * I + ii) * D + 32 * J + jj;
-  o[0] = a0; o[1] = a1; o[2] = a2; o[3] = a3;
+  double *o = G + (32 * I + row0) * D + 32 * J + col;
+  o[0] = a0; o[D] = a1; o[2 * D] = a2; o[3 * D] = a3;
   if (I != J) {
-    tile[ii][jj] = a0; tile[ii][jj + 1] = a1; tile[ii][jj + 2] = a2; tile[ii][jj + 3] = a3;
+    tile[row0][col] = a0; tile[row0 + 1][col] = a1; tile[row0 + 2][col] = a2; tile[row0 + 3][col] = a3;
     __syncthreads();
-    double *m = G + (32 * J + ii) * D + 32 * I + jj;      // element (jrow = ii, icol = jj..)
-    m[0] = tile[jj][ii]; m[1] = tile[jj + 1][ii]; m[2] = tile[jj + 2][ii]; m[3] = tile[jj + 3][ii];
+    double *m = G + (32 * J + row0) * D + 32 * I + col;   // G[32J + r][32I + c] = block[c][r]
+    m[0] = tile[col][row0]; m[D] = tile[col][row0 + 1]; m[2 * D] = tile[col][row0 + 2];
+    m[3 * D] = tile[col][row0 + 3];
   }
 }
 

@@ -184,7 +184,9 @@ __global__ __launch_bounds__(256, 2) void sketch_solve_kernel(const SegTable T, 
   f64x4 sacc[ST];
 #pragma unroll
   for (int i = 0; i < ST; ++i) sacc[i] = f64x4{0.0, 0.0, 0.0, 0.0};
-  const int e = tid * 4, ii = e >> 5, jj = e & 31;
+  const int e = tid * 4;
+  int row0, col;
+  partial_quad(tid, row0, col);   // this thread's float4 of a block: rows row0..+3 of column col
   // the head's 10 upper blocks of G, summed over the splits in fp64 (split order): every thread
   // keeps its 4 elements of each block in registers, all loads of two splits in flight at a time
   double gsum[10][4];
@@ -220,14 +222,12 @@ __global__ __launch_bounds__(256, 2) void sketch_solve_kernel(const SegTable T, 
 #pragma unroll
     for (int J = 0; J < 4; ++J) {
       const int blk = J >= I ? upper_block(I, J) : upper_block(J, I);
-      if (J >= I) {
-        double *d = &Gs[ii * GP + 32 * J + jj];
+      if (J >= I) {          // stored as (I,J): element (r, c) is G[32I + r][32J + c]
+#pragma unroll
+        for (int c = 0; c < 4; ++c) Gs[(row0 + c) * GP + 32 * J + col] = gsum[blk][c];
+      } else {               // stored as (J,I): element (r, c) is G[32I + c][32J + r]
+        double *d = &Gs[col * GP + 32 * J + row0];
         d[0] = gsum[blk][0]; d[1] = gsum[blk][1]; d[2] = gsum[blk][2]; d[3] = gsum[blk][3];
-      } else {
-        Gs[(jj + 0) * GP + 32 * J + ii] = gsum[blk][0];
-        Gs[(jj + 1) * GP + 32 * J + ii] = gsum[blk][1];
-        Gs[(jj + 2) * GP + 32 * J + ii] = gsum[blk][2];
-        Gs[(jj + 3) * GP + 32 * J + ii] = gsum[blk][3];
       }
     }
     __syncthreads();
