@@ -744,3 +744,32 @@ def test_sketched_scores_with_a_ridge(C):
             got = float(out["scores"][h * n:(h + 1) * n].double().sum())
             assert abs(got - want) <= 1e-3 * want, (ks, ridge, h, got, want)
         _say("  k_s=%d ridge=%g: max rel err %.3g, swaps %d" % (ks, ridge, st["max_rel"], st["swaps"]))
+
+
+def test_fused_path_on_strided_views(C):
+    """K and V as views into larger buffers: token stride 384 elements, layer and head strides
+    swapped (the cache stored [H, L, n, 3d])."""
+    _say("fused compress on strided K/V views (stride_t = 384, [H, L] storage order)")
+    L, H, n = 2, 3, 1500
+    g = torch.Generator(device=DEV)
+    g.manual_seed(77)
+    base = W.config2(DEV, L=L, H=H, n=n)
+    big_k = torch.randn(H, L, n, 384, generator=g, device=DEV).to(torch.bfloat16)
+    big_v = torch.randn(H, L, n, 384, generator=g, device=DEV).to(torch.bfloat16)
+    big_k[..., 128:256] = base.requests[0].k.permute(1, 0, 2, 3)
+    big_v[..., 256:384] = base.requests[0].v.permute(1, 0, 2, 3)
+    k = big_k[..., 128:256].permute(1, 0, 2, 3)        # [L, H, n, 128] view, nothing contiguous
+    v = big_v[..., 256:384].permute(1, 0, 2, 3)
+    assert k.stride() == (n * 384, L * n * 384, 384, 1)
+    w = W.Workload("strided_views", L, H, [W.Request(k, v, 0.37)])
+    st, out = U.run_and_check(C, w, DEV)
+    _say("  max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+    # the same bits as the contiguous tensors give
+    w2 = W.Workload("contiguous", L, H, [W.Request(k.contiguous(), v.contiguous(), 0.37)])
+    p2, r2 = U.make_call(C, w2, DEV)
+    ref = C.compactor_compress(p2, r2, want_scores=True)
+    torch.cuda.synchronize()
+    for name in ("scores", "kept_idx"):
+        assert torch.equal(out[name], ref[name]), name
+    assert torch.equal(out["k_packed"].view(torch.int16), ref["k_packed"].view(torch.int16))
+    assert torch.equal(out["v_packed"].view(torch.int16), ref["v_packed"].view(torch.int16))
