@@ -115,6 +115,85 @@ def test_argument_errors_are_reported_on_the_host(B):
     assert B.compactor_version().count(".") == 1
 
 
+def test_widened_entry_points_check_their_arguments_on_the_host(B):
+    global B_mod
+    B_mod = B
+    good = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 0, None)
+    reqs = (B._Request * 1)(_req(n=100, ratio=0.5))
+
+    # paged compaction: the pool's geometry and the length of each page table
+    def paged(pool, tab_len, in_place=0, kept_idx=0x3000):
+        tabs = (B._PageTable * 1)(B._PageTable(0x7000, tab_len))
+        return B._lib.compactor_compact_paged(C.byref(good), reqs, 1, kept_idx, 0x4000, C.byref(pool),
+                                              tabs, in_place, None)
+
+    def pool(k=0x100000, v=0x200000, page_stride=4 * 16 * 128, layer_stride=2 * 16 * 128,
+             head_stride=128, slot_stride=2 * 128, page_size=16, num_pages=64):
+        return B._PagePool(k, v, page_stride, layer_stride, head_stride, slot_stride, page_size, num_pages)
+
+    assert paged(pool(), 3) == B.EINVAL          # 50 kept rows need 4 pages of 16
+    assert paged(pool(), 4, in_place=1) == B.EINVAL  # read in place: all 100 tokens, 7 pages
+    assert paged(pool(k=0), 4) == B.EINVAL
+    assert paged(pool(page_size=0), 4) == B.EINVAL
+    assert paged(pool(num_pages=0), 4) == B.EINVAL
+    assert paged(pool(slot_stride=64), 4) == B.EINVAL
+    assert paged(pool(page_stride=-8), 4) == B.EINVAL
+    assert paged(pool(k=0x100008), 4) == B.EALIGN
+    assert paged(pool(head_stride=132), 4) == B.EALIGN
+    assert paged(pool(), 4, kept_idx=0) == B.EINVAL
+    layer = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 1, None)
+    tabs = (B._PageTable * 1)(B._PageTable(0x7000, 4))       # a head may take 2 * 50 rows: 7 pages
+    assert B._lib.compactor_compact_paged(C.byref(layer), reqs, 1, 0x3000, 0x4000, C.byref(pool()),
+                                          tabs, 0, None) == B.EINVAL
+
+    # the SRHT builder reads its column list on the host
+    signs = (C.c_uint8 * 128)(*([1, 0] * 64))
+    cols_t = C.c_int32 * 48
+
+    def srht(ks, cols, phi=0x8000, sg=signs):
+        return B._lib.compactor_srht_phi(ks, sg, cols, phi, None)
+
+    ok_cols = cols_t(*range(48))
+    assert srht(40, ok_cols) == B.EUNSUPPORTED
+    assert srht(48, ok_cols, phi=0) == B.EINVAL
+    assert srht(48, ok_cols, phi=0x8004) == B.EALIGN
+    assert srht(48, cols_t(*([5] + list(range(1, 48))))) == B.EINVAL     # column 5 twice
+    assert srht(48, cols_t(*([128] + list(range(1, 48))))) == B.EINVAL   # out of range
+    assert srht(48, cols_t(*([-1] + list(range(1, 48))))) == B.EINVAL
+    assert srht(48, None) == B.EINVAL
+
+    # attention scores
+    def attn(p, r, out=0x3000, ws=0x10000, wsb=1 << 40):
+        return B._lib.compactor_attention_scores(C.byref(p), (B._AttnRequest * 1)(r), 1, out, ws, wsb, None)
+
+    def areq(q=0x1000, k=0x2000, qst=128, kst=128, n=300):
+        return B._AttnRequest(q, k, 8 * n * qst, n * qst, qst, 2 * n * kst, n * kst, kst, n)
+
+    def apar(layers=2, kv=2, qh=8, d=128, chunk=256, pool_=7, scale=0.088):
+        return B._AttnParams(layers, kv, qh, d, chunk, pool_, scale)
+
+    need = C.c_size_t(0)
+    assert B._lib.compactor_attention_workspace_size(C.byref(apar()), (B._AttnRequest * 1)(areq()), 1,
+                                                     C.byref(need)) == 0
+    assert need.value >= 2 * 2 * 300 * 4 and need.value % 256 == 0
+    assert attn(apar(qh=3), areq()) == B.EINVAL           # query heads not a multiple of KV heads
+    assert attn(apar(qh=1), areq()) == B.EINVAL
+    assert attn(apar(d=64), areq()) == B.EUNSUPPORTED
+    assert attn(apar(chunk=128), areq()) == B.EUNSUPPORTED
+    assert attn(apar(pool_=4), areq()) == B.EINVAL        # pooling windows are odd
+    assert attn(apar(pool_=65), areq()) == B.EINVAL
+    assert attn(apar(scale=-1.0), areq()) == B.EINVAL
+    assert attn(apar(), areq(n=0)) == B.EINVAL
+    assert attn(apar(), areq(q=0)) == B.EINVAL
+    assert attn(apar(), areq(qst=64)) == B.EINVAL
+    assert attn(apar(), areq(kst=132)) == B.EALIGN
+    assert attn(apar(), areq(k=0x2008)) == B.EALIGN
+    assert attn(apar(), areq(), out=0) == B.EINVAL
+    assert attn(apar(), areq(), ws=0) == B.EWORKSPACE
+    assert attn(apar(), areq(), wsb=256) == B.EWORKSPACE
+    assert attn(apar(), areq(), ws=0x10010) == B.EALIGN
+
+
 def test_default_params(B):
     p = B.compactor_default_params(32, 8)
     assert (p.layers, p.kv_heads, p.head_dim, p.sketch_dim) == (32, 8, 128, 48)
