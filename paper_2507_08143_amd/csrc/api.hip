@@ -138,6 +138,7 @@ template <class F>
 int for_each_group(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
                    long long group_rows, bool local_scores, F &&fn) {
   const int LH = p->layers * p->kv_heads;
+  if ((long long)nreq * LH > 0x7fffffffll) return COMPACTOR_EINVAL;   // heads are numbered in int
   long long score_off = 0, kept_off = 0;
   int b = 0, h = 0;
   while (b < nreq) {

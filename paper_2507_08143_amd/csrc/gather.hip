@@ -279,6 +279,7 @@ hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, const int32
   }
   const long long nb = total_blocks(T, GATHER_ROWS, GATHER_ROWS, true);
   if (nb <= 0) return hipSuccess;
+  if (nb > 0x7fffffffll) return hipErrorInvalidValue;
   hipLaunchKernelGGL(gather_kernel, dim3((unsigned)nb), dim3(256), 0, st, T, kept_idx, k_packed,
                      v_packed);
   return hipGetLastError();

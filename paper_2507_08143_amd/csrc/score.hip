@@ -31,11 +31,9 @@ __device__ __forceinline__ void wave_lds_fence() {
 // MFMA B-operand arrangement; two steps of loads are in flight while a third is multiplied.
 // Nothing in the loop needs a workgroup barrier: a wave only reads what it wrote itself.
 template <int M>
-__global__ __launch_bounds__(256, 2) void score_kernel(const SegTable T, int tokens_per_wg,
-                                                       const uint16_t *__restrict__ wt,
-                                                       float *__restrict__ scores,
-                                                       int32_t *__restrict__ status,
-                                                       int *__restrict__ hist1) {
+__global__ __launch_bounds__(256, M > 64 ? 1 : 2) void score_kernel(
+    const SegTable T, int tokens_per_wg, const uint16_t *__restrict__ wt, float *__restrict__ scores,
+    int32_t *__restrict__ status, int *__restrict__ hist1) {
   constexpr int NSUB = 2, WTOK = 16 * NSUB, STEP = 4 * WTOK;     // tokens per wave / per WG step
   constexpr int NLD = WTOK * 16 / 64;                            // 16-B loads per lane per step
   __shared__ __attribute__((aligned(16))) uint16_t wl[W_TERMS * M * WPITCH];
@@ -196,6 +194,7 @@ static hipError_t launch_m(const SegTable &T, int tokens_per_wg, const uint16_t 
                            float *scores, int32_t *status, int *hist1, hipStream_t st) {
   const long long nb = total_blocks(T, tokens_per_wg, SCORE_STEP, false);
   if (nb <= 0) return hipSuccess;
+  if (nb > 0x7fffffffll) return hipErrorInvalidValue;
   hipLaunchKernelGGL((score_kernel<M>), dim3((unsigned)nb), dim3(256), 0, st, T, tokens_per_wg, wt,
                      scores, status, hist1);
   return hipGetLastError();

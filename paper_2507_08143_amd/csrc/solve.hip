@@ -147,14 +147,10 @@ __device__ __forceinline__ double readlane_f64(double x, int lane) {
 }
 
 template <int M>
-__global__ __launch_bounds__(256, 2) void sketch_solve_kernel(const SegTable T, int tiles_per_wg,
-                                                           const float *__restrict__ partials,
-                                                           const float *__restrict__ phi,
-                                                           float ridge_rel,
-                                                           uint16_t *__restrict__ wt,
-                                                           int32_t *__restrict__ status,
-                                                           int *__restrict__ zero,
-                                                           long long zero_ints) {
+__global__ __launch_bounds__(256, M > 48 ? 1 : 2) void sketch_solve_kernel(
+    const SegTable T, int tiles_per_wg, const float *__restrict__ partials,
+    const float *__restrict__ phi, float ridge_rel, uint16_t *__restrict__ wt,
+    int32_t *__restrict__ status, int *__restrict__ zero, long long zero_ints) {
   constexpr int P = M / 16, CT = M / 16;
   // LDS pitches in doubles.  GP = 132 spreads the A-operand reads of G (16 rows x 4 k per
   // instruction) over all banks: row stride 8 dwords mod 64, k stride 2.
