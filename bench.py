@@ -58,6 +58,11 @@ def parse():
     ap.add_argument("--allow-flagged", action="store_true",
                     help="do not fail when a head reports a status flag (kernel experiments only)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
+    ap.add_argument("--cpu-threads", type=int, default=0,
+                    help="cap the oracle leg's BLAS threads (0 = the host's default, all cores)")
+    ap.add_argument("--flush-cache", action="store_true",
+                    help="also time steps one by one, each after a 512 MiB fill that evicts the "
+                         "last-level cache (cold_ms_per_step); matters for workloads that fit in it")
     return ap.parse_args()
 
 
@@ -88,15 +93,15 @@ def stage_flops(w, ks):
     return {"gram": 2.0 * 128 * 128 * rows, "score": 2.0 * 128 * m * rows}
 
 
-def cpu_baseline(W, O, w, phi, budget_s):
+def cpu_baseline(W, O, w, phi, budget_s, threads=0):
     """The oracle as it stands on the host cores, on as many heads of the workload as fit the
     time budget (at least one), scaled linearly to all heads (heads are independent)."""
     import numpy as np
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count() or 1
+    from threadpoolctl import threadpool_info, threadpool_limits
+    if threads > 0:
+        with threadpool_limits(limits=threads):
+            return cpu_baseline(W, O, w, phi, budget_s)
+    cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     LH = w.layers * w.kv_heads
     phi_np = phi.double().cpu().numpy() if phi is not None else None
     t_total, done, head_rows = 0.0, 0, 0
@@ -298,14 +303,33 @@ def main():
     assert a.allow_flagged or int(bufs["status"].max()) == 0, "a head was flagged during the benchmark"
 
     # the same steps again with per-stage HIP events on the launch stream
-    stage_ms = {}
+    stage_ms, step_ms = {}, []
     t1 = time.perf_counter()
     for _ in range(a.steps):
         step(params_ev)
         torch.cuda.synchronize()
-        for k_, v_ in ev.elapsed_ms().items():
+        per = ev.elapsed_ms()
+        step_ms.append(sum(per.values()))
+        for k_, v_ in per.items():
             stage_ms[k_] = stage_ms.get(k_, 0.0) + v_ / a.steps
     ms_per_step_ev = (time.perf_counter() - t1) / a.steps * 1e3
+    ms_median_ev = sorted(step_ms)[len(step_ms) // 2]   # first to last stage event, per step
+
+    # cold steps: the last-level cache (256 MB) is overwritten before each one
+    cold_ms = None
+    if a.flush_cache:
+        junk = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        acc = []
+        for _ in range(a.steps):
+            junk.fill_(1)
+            e0.record()
+            step(params)
+            e1.record()
+            torch.cuda.synchronize()
+            acc.append(e0.elapsed_time(e1))
+        cold_ms = sorted(acc)[len(acc) // 2]
+        del junk
 
     # the three unfused calls on the same buffers (scores then travel through HBM once more)
     unfused = None
@@ -361,15 +385,20 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant)) if not a.layers else None},
         "path_hbm": {"algorithmic_bytes": total_bytes,
                      "achieved_GB/s": total_bytes / (ms_per_step * 1e-3) / 1e9,
-                     "frac_of_8TB/s": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                     "frac_of_8TB/s": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     # what a path whose second pass over K hit a cache would have to move
+                     "one_pass_K_bytes": total_bytes - sbytes["gram"]},
         "mfma": {"path_TFLOP/s": sum(sflops.values()) / (ms_per_step * 1e-3) / 1e12,
                  "frac_of_bf16_peak": sum(sflops.values()) / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
         "stages": stages, "ms_per_step_with_events": ms_per_step_ev,
+        "ms_per_step_median_of_event_spans": ms_median_ev,
         "unfused_calls": unfused,
     }
+    if cold_ms is not None:
+        out["cold_ms_per_step"] = cold_ms
     if not a.no_cpu_baseline:
         from oracle import compactor_oracle as O
-        out["cpu_baseline"] = cpu_baseline(W, O, w, phi, a.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(W, O, w, phi, a.cpu_seconds, a.cpu_threads)
     print(json.dumps(out))
 
 
