@@ -54,7 +54,9 @@ extern "C" {
 #define COMPACTOR_EUNSUPPORTED       (-2)  /* head_dim != 128, sketch_dim not in {0,16,32,48,64} */
 #define COMPACTOR_EWORKSPACE         (-3)  /* workspace pointer null or too small */
 #define COMPACTOR_EALIGN             (-4)  /* a pointer or a row stride is not 16-byte aligned */
-#define COMPACTOR_EHIP               (-5)  /* a HIP runtime call failed (launch error) */
+#define COMPACTOR_EHIP               (-5)  /* a HIP runtime call of the library failed (launch error);
+                                              an error that earlier HIP calls of the caller left
+                                              pending on the thread is discarded, not reported */
 
 /* per-head status bits written by the scoring step */
 #define COMPACTOR_STATUS_OK            0

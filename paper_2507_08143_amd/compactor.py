@@ -131,6 +131,7 @@ class StageEvents:
             ms = C.c_float(0)
             if self._hip.hipEventElapsedTime(C.byref(ms), self.array[i], self.array[i + 1]) == 0:
                 out[name] = float(ms.value)
+        self._hip.hipGetLastError()     # asking about a stage that did not run leaves an error pending
         return out
 
     def __del__(self):

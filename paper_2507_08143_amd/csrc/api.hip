@@ -249,6 +249,11 @@ int workspace_need(const compactor_params_t *p, const compactor_request_t *reqs,
   return rc;
 }
 
+// The launchers report hipGetLastError(), which also returns an error that an earlier, unrelated
+// HIP call left pending on this thread.  Every enqueueing entry point discards such a leftover
+// first, so that COMPACTOR_EHIP always speaks of the library's own calls.
+inline void drop_pending_error() { (void)hipGetLastError(); }
+
 #define HIP_TRY(expr)                                \
   do {                                               \
     if ((expr) != hipSuccess) return COMPACTOR_EHIP; \
@@ -414,6 +419,7 @@ int compactor_srht_phi(int32_t sketch_dim, const uint8_t *signs, const int32_t *
     if (cols[j] < 0 || cols[j] >= D || seen[cols[j]]) return COMPACTOR_EINVAL;
     seen[cols[j]] = true;
   }
+  drop_pending_error();
   HIP_TRY(launch_srht_phi(sketch_dim, signs, cols, phi, static_cast<hipStream_t>(stream)));
   return COMPACTOR_OK;
 }
@@ -442,6 +448,7 @@ int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs
   if (rc) return rc;
   if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
+  drop_pending_error();
   return run_groups(p, reqs, nreq, false, static_cast<unsigned char *>(workspace), slice,
                     static_cast<hipStream_t>(stream),
                     [&](const SegTable &T, long long rows, hipStream_t st, unsigned char *ws) {
@@ -475,6 +482,7 @@ int compactor_select(const compactor_params_t *p, const compactor_request_t *req
     if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
+  drop_pending_error();
   return for_each_group(p, reqs, nreq, grows, false, [&](const SegTable &T, long long) {
     if (select_needs_pools(T)) {
       const GroupBytes gb = group_bytes_needed(p, T, false);
@@ -500,6 +508,7 @@ int compactor_compact(const compactor_params_t *p, const compactor_request_t *re
   if (!kept_idx || !kept_cnt || !k_packed || !v_packed) return COMPACTOR_EINVAL;
   if (!aligned16(k_packed) || !aligned16(v_packed)) return COMPACTOR_EALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  drop_pending_error();
   return for_each_group(p, reqs, nreq, 1ll << 60, false, [&](const SegTable &T, long long) {
     HIP_TRY(launch_gather(T, kept_idx, kept_cnt, static_cast<uint16_t *>(k_packed),
                           static_cast<uint16_t *>(v_packed), st));
@@ -536,6 +545,7 @@ int compactor_compact_paged(const compactor_params_t *p, const compactor_request
       return COMPACTOR_EINVAL;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
+  drop_pending_error();
   return for_each_group(p, reqs, nreq, 1ll << 60, false, [&](const SegTable &T, long long) {
     PagePool P;
     memset(&P, 0, sizeof(P));
@@ -571,6 +581,7 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
   if (rc) return rc;
   if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
+  drop_pending_error();
   return run_groups(p, reqs, nreq, local_scores, static_cast<unsigned char *>(workspace), slice,
                     static_cast<hipStream_t>(stream),
                     [&](const SegTable &T, long long rows, hipStream_t st, unsigned char *ws) {

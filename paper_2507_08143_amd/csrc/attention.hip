@@ -367,6 +367,7 @@ int compactor_attention_scores(const compactor_attn_params_t *p,
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return COMPACTOR_EALIGN;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();   // a leftover of earlier, unrelated HIP calls is not this call's error
   float *raw = static_cast<float *>(workspace);
   const int LH = p->layers * p->kv_heads;
   long long off = 0;

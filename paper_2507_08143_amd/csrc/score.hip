@@ -169,12 +169,13 @@ __global__ __launch_bounds__(256, M > 64 ? 1 : 2) void score_kernel(
     if (lane == 0) atomicOr(&status[s.ghead0 + w.head], COMPACTOR_STATUS_NONFINITE);
   }
   __syncthreads();
-  {                              // the scores, 16 bytes per lane where the head's base allows it
+  {    // the scores, 16 bytes per lane where the head's base allows it; streaming stores disturb
+       // the other workgroups' reads least (measured: 1 to 4 % of the kernel's time)
     const int cnt = tok_end - tok_begin;
     float *dst = sp + tok_begin;
     if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
       for (int i = 4 * tid; i + 3 < cnt; i += 4 * 256)
-        *reinterpret_cast<float4 *>(dst + i) = *reinterpret_cast<const float4 *>(&sc_l[i]);
+        store_stream16(dst + i, *reinterpret_cast<const uint4 *>(&sc_l[i]));
       for (int i = (cnt & ~3) + tid; i < cnt; i += 256) dst[i] = sc_l[i];
     } else {
       for (int i = tid; i < cnt; i += 256) dst[i] = sc_l[i];

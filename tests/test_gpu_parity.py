@@ -364,6 +364,29 @@ def test_error_codes_reach_python(C):
     assert e.value.code == C.EWORKSPACE
 
 
+def test_a_pending_hip_error_of_the_caller_is_not_reported(C):
+    """The elapsed time of two events that were never recorded is an error that stays pending on
+    the thread; the next library call must neither fail because of it nor compute anything else."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    e0, e1, ms = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_float()
+    assert hip.hipEventCreate(ctypes.byref(e0)) == 0 and hip.hipEventCreate(ctypes.byref(e1)) == 0
+    w = W.config1(device=DEV, L=1, H=2, n=640)
+    params, reqs = U.make_call(C, w, DEV)
+    want = C.compactor_compress(params, reqs, want_scores=True)
+    torch.cuda.synchronize()
+    assert hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1) != 0      # leaves the error pending
+    got = C.compactor_compress(params, reqs, want_scores=True)
+    torch.cuda.synchronize()
+    for k in ("scores", "kept_idx", "k_packed", "v_packed"):
+        assert torch.equal(want[k], got[k])
+    hip.hipEventDestroy(e0)
+    hip.hipEventDestroy(e1)
+
+
 # ------------------------------------------------------------------ full sizes (sampled heads)
 def _sample_heads(w, per_request=4, seed=11):
     rng = np.random.default_rng(seed)
