@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--paged", action="store_true",
                     help="time the compaction stage with a paged destination (and in place)")
     ap.add_argument("--page-size", type=int, default=16, help="slots per page for --paged")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture one step in a HIP graph and time its replays (graph_ms_per_step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--allow-flagged", action="store_true",
                     help="do not fail when a head reports a status flag (kernel experiments only)")
@@ -331,6 +333,21 @@ def main():
         cold_ms = sorted(acc)[len(acc) // 2]
         del junk
 
+    # one step captured in a HIP graph and replayed (the call only launches kernels, so it can be)
+    graph_ms = None
+    if a.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(params)
+        for _ in range(a.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(a.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t2) / a.steps * 1e3
+
     # the three unfused calls on the same buffers (scores then travel through HBM once more)
     unfused = None
     if True:
@@ -396,6 +413,8 @@ def main():
     }
     if cold_ms is not None:
         out["cold_ms_per_step"] = cold_ms
+    if graph_ms is not None:
+        out["graph_ms_per_step"] = graph_ms
     if not a.no_cpu_baseline:
         from oracle import compactor_oracle as O
         out["cpu_baseline"] = cpu_baseline(W, O, w, phi, a.cpu_seconds, a.cpu_threads)
