@@ -154,6 +154,23 @@ def _check(rc: int):
         raise CompactorError(rc)
 
 
+def _require(cond: bool, what: str):
+    """The C boundary takes plain pointers and cannot see a tensor's size, type or device: what it
+    cannot check is checked here, before anything reaches the GPU."""
+    if not cond:
+        raise ValueError("compactor: " + what)
+
+
+def _out(t: Optional[torch.Tensor], numel: int, dtype, name: str):
+    """A caller-supplied output (or flat input) buffer: right type, dense, large enough, on the GPU."""
+    if t is None:
+        return
+    _require(t.dtype == dtype, "%s must be %s, got %s" % (name, dtype, t.dtype))
+    _require(t.is_contiguous(), "%s must be contiguous" % name)
+    _require(t.numel() >= numel, "%s holds %d elements, %d needed" % (name, t.numel(), numel))
+    _require(t.is_cuda, "%s must live on the GPU" % name)
+
+
 SCOPE_HEAD, SCOPE_LAYER = 0, 1
 
 
@@ -173,10 +190,15 @@ class Params:
     streams: int = 0                                # 2..4 = spread head groups over helper streams
     select_scope: int = 0                           # SCOPE_HEAD, or SCOPE_LAYER (head-adaptive)
 
-    def c(self) -> _Params:
+    def c(self, on_gpu: bool = True) -> _Params:
         phi = 0
-        if self.phi is not None:
-            assert self.phi.dtype == torch.float32 and self.phi.is_contiguous()
+        if self.phi is not None and self.sketch_dim > 0:
+            _require(self.phi.dtype == torch.float32 and self.phi.is_contiguous(),
+                     "phi must be a contiguous float32 tensor")
+            _require(tuple(self.phi.shape) == (self.head_dim, self.sketch_dim),
+                     "phi must have shape [head_dim, sketch_dim] = [%d, %d], got %s"
+                     % (self.head_dim, self.sketch_dim, tuple(self.phi.shape)))
+            _require(self.phi.is_cuda or not on_gpu, "phi must live on the GPU")
             phi = self.phi.data_ptr()
         ev = C.cast(self.stage_events.array, C.c_void_p) if self.stage_events is not None else None
         return _Params(self.layers, self.kv_heads, self.head_dim, self.sketch_dim, phi,
@@ -192,14 +214,26 @@ class Request:
     k_cache: Optional[torch.Tensor] = None     # bf16, same shape and strides; None = k_score
     attn: Optional[torch.Tensor] = None        # fp32 [L, H, n] contiguous
 
-    def c(self) -> _Request:
+    def c(self, params: Optional["Params"] = None, on_gpu: bool = True) -> _Request:
         k = self.k_score
-        assert k.dtype == torch.bfloat16 and k.dim() == 4 and k.stride(3) == 1
-        for t in (self.v_cache, self.k_cache):
+        _require(k.dtype == torch.bfloat16 and k.dim() == 4 and k.stride(3) == 1,
+                 "k_score must be a bfloat16 tensor [L, H, n, d] with d contiguous")
+        if params is not None:
+            _require(k.shape[0] == params.layers and k.shape[1] == params.kv_heads and
+                     k.shape[3] == params.head_dim,
+                     "k_score has shape %s, the parameters say [%d, %d, n, %d]"
+                     % (tuple(k.shape), params.layers, params.kv_heads, params.head_dim))
+        for name, t in (("v_cache", self.v_cache), ("k_cache", self.k_cache)):
             if t is not None:
-                assert t.dtype == torch.bfloat16 and t.shape == k.shape and t.stride() == k.stride()
+                _require(t.dtype == torch.bfloat16 and t.shape == k.shape and t.stride() == k.stride(),
+                         "%s must be bfloat16 with the shape and strides of k_score" % name)
+                _require(t.is_cuda or not on_gpu, "%s must live on the GPU" % name)
         if self.attn is not None:
-            assert self.attn.dtype == torch.float32 and self.attn.is_contiguous()
+            _require(self.attn.dtype == torch.float32 and self.attn.is_contiguous() and
+                     self.attn.numel() >= k.shape[0] * k.shape[1] * k.shape[2],
+                     "attn must be a contiguous float32 tensor of L*H*n elements")
+            _require(self.attn.is_cuda or not on_gpu, "attn must live on the GPU")
+        _require(k.is_cuda or not on_gpu, "k_score must live on the GPU")
         return _Request(k.data_ptr(),
                         self.k_cache.data_ptr() if self.k_cache is not None else 0,
                         self.v_cache.data_ptr() if self.v_cache is not None else 0,
@@ -207,9 +241,10 @@ class Request:
                         k.stride(0), k.stride(1), k.stride(2), k.shape[2], self.ratio)
 
 
-def _marshal(params: Params, reqs: Sequence[Request]):
-    arr = (_Request * len(reqs))(*[r.c() for r in reqs])
-    return C.byref(params.c()), arr, len(reqs)
+def _marshal(params: Params, reqs: Sequence[Request], on_gpu: bool = True):
+    _require(len(reqs) >= 1, "at least one request is needed")
+    arr = (_Request * len(reqs))(*[r.c(params, on_gpu) for r in reqs])
+    return C.byref(params.c(on_gpu)), arr, len(reqs)
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -255,8 +290,9 @@ def compactor_srht_phi(sketch_dim: int, signs, cols, device, stream=None) -> tor
     (nonzero = -1); cols: sketch_dim distinct rows of the Hadamard matrix."""
     sg = (C.c_uint8 * 128)(*[1 if int(x) else 0 for x in signs])
     cl = (C.c_int32 * len(cols))(*[int(x) for x in cols])
+    _require(len(signs) == 128 and len(cols) == sketch_dim,
+             "signs must hold 128 values and cols sketch_dim values")
     phi = torch.empty(128, sketch_dim, dtype=torch.float32, device=device)
-    assert len(signs) == 128 and len(cols) == sketch_dim
     with torch.cuda.device(phi.device):
         _check(_lib.compactor_srht_phi(sketch_dim, sg, cl, _ptr(phi), _stream(stream)))
     return phi
@@ -264,14 +300,14 @@ def compactor_srht_phi(sketch_dim: int, signs, cols, device, stream=None) -> tor
 
 def compactor_layout(params: Params, reqs: Sequence[Request]):
     """-> (score_off[nreq+1], kept_off[nreq+1], k_keep[nreq]) as Python lists."""
-    pp, arr, n = _marshal(params, reqs)
+    pp, arr, n = _marshal(params, reqs, on_gpu=False)      # a host helper: sizes only
     so, ko, kk = (C.c_int64 * (n + 1))(), (C.c_int64 * (n + 1))(), (C.c_int32 * n)()
     _check(_lib.compactor_layout(pp, arr, n, so, ko, kk))
     return list(so), list(ko), list(kk)
 
 
 def compactor_workspace_size(params: Params, reqs: Sequence[Request]) -> int:
-    pp, arr, n = _marshal(params, reqs)
+    pp, arr, n = _marshal(params, reqs, on_gpu=False)
     out = C.c_size_t(0)
     _check(_lib.compactor_workspace_size(pp, arr, n, C.byref(out)))
     return int(out.value)
@@ -295,6 +331,9 @@ def compactor_score(params: Params, reqs: Sequence[Request], scores=None, status
         status = torch.empty(len(reqs) * params.layers * params.kv_heads, dtype=torch.int32, device=dev)
     workspace = _workspace(params, reqs, workspace)
     pp, arr, n = _marshal(params, reqs)
+    _out(scores, so[-1], torch.float32, "scores")
+    _out(status, n * params.layers * params.kv_heads, torch.int32, "status")
+    _out(workspace, 0, torch.uint8, "workspace")
     _check(_lib.compactor_score(pp, arr, n, _ptr(scores), _ptr(status), _ptr(workspace),
                                 workspace.numel(), _stream(stream)))
     return scores, status
@@ -313,6 +352,11 @@ def compactor_select(params: Params, reqs: Sequence[Request], scores: torch.Tens
     if workspace is None:
         nbytes = max(256, compactor_workspace_size(params, reqs))
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    so, _, _ = compactor_layout(params, reqs)
+    _out(scores, so[-1], torch.float32, "scores")
+    _out(kept_idx, ko[-1], torch.int32, "kept_idx")
+    _out(kept_cnt, n * params.layers * params.kv_heads, torch.int32, "kept_cnt")
+    _out(workspace, 0, torch.uint8, "workspace")
     _check(_lib.compactor_select(pp, arr, n, _ptr(scores), _ptr(kept_idx), _ptr(kept_cnt),
                                  _ptr(workspace), workspace.numel(), _stream(stream)))
     return kept_idx, kept_cnt
@@ -328,6 +372,10 @@ def compactor_compact(params: Params, reqs: Sequence[Request], kept_idx: torch.T
     if v_packed is None:
         v_packed = torch.empty(ko[-1], params.head_dim, dtype=torch.bfloat16, device=dev)
     pp, arr, n = _marshal(params, reqs)
+    _out(kept_idx, ko[-1], torch.int32, "kept_idx")
+    _out(kept_cnt, n * params.layers * params.kv_heads, torch.int32, "kept_cnt")
+    _out(k_packed, ko[-1] * params.head_dim, torch.bfloat16, "k_packed")
+    _out(v_packed, ko[-1] * params.head_dim, torch.bfloat16, "v_packed")
     _check(_lib.compactor_compact(pp, arr, n, _ptr(kept_idx), _ptr(kept_cnt), _ptr(k_packed),
                                   _ptr(v_packed), _stream(stream)))
     return k_packed, v_packed
@@ -339,15 +387,27 @@ def compactor_compact_paged(params: Params, reqs: Sequence[Request], kept_idx: t
     """Retained rows into a paged cache.  k_pages / v_pages: bf16 views indexed
     [page, layer, slot, head, channel] (any strides, channel contiguous, the same for both);
     tables[b]: int32 device tensor, physical page of each logical page of request b."""
-    assert k_pages.dtype == torch.bfloat16 and v_pages.dtype == torch.bfloat16
-    assert k_pages.dim() == 5 and k_pages.stride(4) == 1 and v_pages.stride() == k_pages.stride()
+    _require(k_pages.dtype == torch.bfloat16 and v_pages.dtype == torch.bfloat16,
+             "k_pages and v_pages must be bfloat16")
+    _require(k_pages.dim() == 5 and k_pages.stride(4) == 1 and v_pages.shape == k_pages.shape and
+             v_pages.stride() == k_pages.stride(),
+             "k_pages and v_pages must be [page, layer, slot, head, channel] views of equal shape and "
+             "strides, channel contiguous")
+    _require(k_pages.shape[1] == params.layers and k_pages.shape[3] == params.kv_heads and
+             k_pages.shape[4] == params.head_dim,
+             "the page pool has shape %s, the parameters say [pages, %d, slots, %d, %d]"
+             % (tuple(k_pages.shape), params.layers, params.kv_heads, params.head_dim))
+    _require(k_pages.is_cuda and v_pages.is_cuda, "the page pool must live on the GPU")
     pool = _PagePool(k_pages.data_ptr(), v_pages.data_ptr(), k_pages.stride(0), k_pages.stride(1),
                      k_pages.stride(3), k_pages.stride(2), k_pages.shape[2], k_pages.shape[0])
     for t in tables:
-        assert t.dtype == torch.int32 and t.is_contiguous()
+        _out(t, 0, torch.int32, "a block table")
     tabs = (_PageTable * len(tables))(*[_PageTable(t.data_ptr(), t.numel()) for t in tables])
     pp, arr, n = _marshal(params, reqs)
-    assert len(tables) == n
+    _require(len(tables) == n, "one block table per request is needed")
+    _, ko, _ = compactor_layout(params, reqs)
+    _out(kept_idx, ko[-1], torch.int32, "kept_idx")
+    _out(kept_cnt, n * params.layers * params.kv_heads, torch.int32, "kept_cnt")
     _check(_lib.compactor_compact_paged(pp, arr, n, _ptr(kept_idx), _ptr(kept_cnt), C.byref(pool),
                                         tabs, 1 if in_place else 0, _stream(stream)))
 
@@ -373,6 +433,13 @@ def compactor_compress(params: Params, reqs: Sequence[Request], want_scores: boo
         status = torch.empty(nh, dtype=torch.int32, device=dev)
     workspace = _workspace(params, reqs, workspace)
     pp, arr, n = _marshal(params, reqs)
+    _out(scores, so[-1], torch.float32, "scores")
+    _out(kept_idx, ko[-1], torch.int32, "kept_idx")
+    _out(kept_cnt, nh, torch.int32, "kept_cnt")
+    _out(k_packed, ko[-1] * params.head_dim, torch.bfloat16, "k_packed")
+    _out(v_packed, ko[-1] * params.head_dim, torch.bfloat16, "v_packed")
+    _out(status, nh, torch.int32, "status")
+    _out(workspace, 0, torch.uint8, "workspace")
     _check(_lib.compactor_compress(pp, arr, n, _ptr(scores), _ptr(kept_idx), _ptr(kept_cnt),
                                    _ptr(k_packed), _ptr(v_packed), _ptr(status), _ptr(workspace),
                                    workspace.numel(), _stream(stream)))
@@ -400,17 +467,26 @@ class AttnRequest:
     q: torch.Tensor             # bf16 [L, Hq, n, d]
     k: torch.Tensor             # bf16 [L, H, n, d]
 
-    def c(self) -> _AttnRequest:
+    def c(self, params: Optional["AttnParams"] = None) -> _AttnRequest:
         q, k = self.q, self.k
-        assert q.dtype == torch.bfloat16 and k.dtype == torch.bfloat16
-        assert q.dim() == 4 and k.dim() == 4 and q.stride(3) == 1 and k.stride(3) == 1
-        assert q.shape[2] == k.shape[2]
+        _require(q.dtype == torch.bfloat16 and k.dtype == torch.bfloat16, "q and k must be bfloat16")
+        _require(q.dim() == 4 and k.dim() == 4 and q.stride(3) == 1 and k.stride(3) == 1,
+                 "q and k must be [L, heads, n, d] with d contiguous")
+        _require(q.shape[2] == k.shape[2], "q and k must cover the same tokens")
+        if params is not None:
+            _require(tuple(q.shape[:2]) == (params.layers, params.q_heads) and
+                     tuple(k.shape[:2]) == (params.layers, params.kv_heads) and
+                     q.shape[3] == params.head_dim and k.shape[3] == params.head_dim,
+                     "q %s / k %s do not match the parameters [%d, %d | %d, n, %d]"
+                     % (tuple(q.shape), tuple(k.shape), params.layers, params.q_heads,
+                        params.kv_heads, params.head_dim))
+        _require(q.is_cuda and k.is_cuda, "q and k must live on the GPU")
         return _AttnRequest(q.data_ptr(), k.data_ptr(), q.stride(0), q.stride(1), q.stride(2),
                             k.stride(0), k.stride(1), k.stride(2), k.shape[2])
 
 
 def compactor_attention_workspace_size(params: AttnParams, reqs: Sequence[AttnRequest]) -> int:
-    arr = (_AttnRequest * len(reqs))(*[r.c() for r in reqs])
+    arr = (_AttnRequest * len(reqs))(*[r.c(params) for r in reqs])
     out = C.c_size_t(0)
     _check(_lib.compactor_attention_workspace_size(C.byref(params.c()), arr, len(reqs), C.byref(out)))
     return int(out.value)
@@ -426,7 +502,9 @@ def compactor_attention_scores(params: AttnParams, reqs: Sequence[AttnRequest], 
     if workspace is None:
         workspace = torch.empty(max(256, compactor_attention_workspace_size(params, reqs)),
                                 dtype=torch.uint8, device=dev)
-    arr = (_AttnRequest * len(reqs))(*[r.c() for r in reqs])
+    arr = (_AttnRequest * len(reqs))(*[r.c(params) for r in reqs])
+    _out(attn, total, torch.float32, "attn")
+    _out(workspace, 0, torch.uint8, "workspace")
     _check(_lib.compactor_attention_scores(C.byref(params.c()), arr, len(reqs), _ptr(attn),
                                            _ptr(workspace), workspace.numel(), _stream(stream)))
     return attn

@@ -58,15 +58,13 @@ def test_calibrated_ratio_matches_oracle(B):
     assert abs(B.compactor_calibrated_ratio(1.0, np.log(2.0), 0.0, 0.5) - np.log2(1.5)) < 1e-14
 
 
-def _req(n=100, ratio=0.5, ptr=0x1000, stride_t=128):
-    return B_mod._Request(ptr, 0, ptr, 0, 8 * n * stride_t, n * stride_t, stride_t, n, ratio)
+def _req(B, n=100, ratio=0.5, ptr=0x1000, stride_t=128):
+    return B._Request(ptr, 0, ptr, 0, 8 * n * stride_t, n * stride_t, stride_t, n, ratio)
 
 
 def test_layout_offsets(B):
-    global B_mod
-    B_mod = B
     p = B._Params(3, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, 0, None)
-    reqs = (B._Request * 3)(_req(100, 0.5), _req(7, 1.0), _req(1000, 0.25))
+    reqs = (B._Request * 3)(_req(B, 100, 0.5), _req(B, 7, 1.0), _req(B, 1000, 0.25))
     so, ko, kk = (C.c_int64 * 4)(), (C.c_int64 * 4)(), (C.c_int32 * 3)()
     assert B._lib.compactor_layout(C.byref(p), reqs, 3, so, ko, kk) == 0
     assert list(kk) == [50, 7, 250]
@@ -75,10 +73,8 @@ def test_layout_offsets(B):
 
 
 def test_argument_errors_are_reported_on_the_host(B):
-    global B_mod
-    B_mod = B
     good = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 0, None)
-    reqs = (B._Request * 1)(_req())
+    reqs = (B._Request * 1)(_req(B))
     nbytes = C.c_size_t(0)
     assert B._lib.compactor_workspace_size(C.byref(good), reqs, 1, C.byref(nbytes)) == 0
     assert nbytes.value > 0
@@ -96,12 +92,12 @@ def test_argument_errors_are_reported_on_the_host(B):
     assert score(bad_scope, reqs) == B.EINVAL
     neg_ridge = B._Params(2, 2, 128, 48, 0x2000, -1.0, 0.3, 0, 0, 0, 0, 0, None)
     assert score(neg_ridge, reqs) == B.EINVAL
-    assert score(good, (B._Request * 1)(_req(ratio=0.0))) == B.EINVAL
-    assert score(good, (B._Request * 1)(_req(ratio=1.5))) == B.EINVAL
-    assert score(good, (B._Request * 1)(_req(n=0))) == B.EINVAL
-    assert score(good, (B._Request * 1)(_req(ptr=0x1004))) == B.EALIGN
-    assert score(good, (B._Request * 1)(_req(stride_t=132))) == B.EALIGN
-    assert score(good, (B._Request * 1)(_req(stride_t=64))) == B.EINVAL
+    assert score(good, (B._Request * 1)(_req(B, ratio=0.0))) == B.EINVAL
+    assert score(good, (B._Request * 1)(_req(B, ratio=1.5))) == B.EINVAL
+    assert score(good, (B._Request * 1)(_req(B, n=0))) == B.EINVAL
+    assert score(good, (B._Request * 1)(_req(B, ptr=0x1004))) == B.EALIGN
+    assert score(good, (B._Request * 1)(_req(B, stride_t=132))) == B.EALIGN
+    assert score(good, (B._Request * 1)(_req(B, stride_t=64))) == B.EINVAL
     assert score(good, reqs, scores=0) == B.EINVAL
     assert score(good, reqs, ws=0) == B.EWORKSPACE
     assert score(good, reqs, wsb=16) == B.EWORKSPACE
@@ -116,10 +112,8 @@ def test_argument_errors_are_reported_on_the_host(B):
 
 
 def test_widened_entry_points_check_their_arguments_on_the_host(B):
-    global B_mod
-    B_mod = B
     good = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 0, None)
-    reqs = (B._Request * 1)(_req(n=100, ratio=0.5))
+    reqs = (B._Request * 1)(_req(B, n=100, ratio=0.5))
 
     # paged compaction: the pool's geometry and the length of each page table
     def paged(pool, tab_len, in_place=0, kept_idx=0x3000):
@@ -198,3 +192,40 @@ def test_default_params(B):
     p = B.compactor_default_params(32, 8)
     assert (p.layers, p.kv_heads, p.head_dim, p.sketch_dim) == (32, 8, 128, 48)
     assert abs(p.lambda_blend - 0.3) < 1e-7 and p.ridge_rel == 0.0 and p.streams == 0
+
+
+def test_binding_checks_what_the_pointers_cannot_say(B):
+    """Sizes, types and devices of tensors are invisible to the C boundary: the binding refuses a
+    wrong one with a ValueError before any library call (CPU tensors suffice to show it)."""
+    import torch
+    L, H, n = 2, 2, 64
+    k = torch.zeros(L, H, n, 128, dtype=torch.bfloat16)
+    v = torch.zeros_like(k)
+    phi = torch.zeros(128, 48)
+    p = B.Params(L, H, phi=phi)
+    ok = [B.Request(k_score=k, v_cache=v, ratio=0.5)]
+    so, ko, kk = B.compactor_layout(p, ok)                 # host helpers take CPU tensors
+    assert (so, ko, kk) == ([0, L * H * n], [0, L * H * 32], [32])
+    assert B.compactor_workspace_size(p, ok) > 0
+
+    def refused(fn, needle):
+        with pytest.raises(ValueError) as e:
+            fn()
+        assert needle in str(e.value), str(e.value)
+
+    refused(lambda: B.compactor_layout(p, []), "at least one request")
+    refused(lambda: B.compactor_layout(p, [B.Request(k.float(), v, 0.5)]), "bfloat16")
+    refused(lambda: B.compactor_layout(p, [B.Request(k, v[:, :, :32], 0.5)]), "v_cache")
+    refused(lambda: B.compactor_layout(p, [B.Request(k[:1], v[:1], 0.5)]), "the parameters say")
+    refused(lambda: B.compactor_layout(p, [B.Request(k.transpose(2, 3), v.transpose(2, 3), 0.5)]), "d contiguous")
+    refused(lambda: B.compactor_layout(B.Params(L, H, phi=torch.zeros(128, 32)), ok), "phi must have shape")
+    refused(lambda: B.compactor_layout(p, [B.Request(k, v, 0.5, attn=torch.zeros(L * H * n - 1))]), "attn")
+    # entry points that launch refuse CPU tensors and short or mistyped outputs
+    refused(lambda: B.compactor_compress(p, ok, kept_idx=torch.zeros(5, dtype=torch.int32)), "GPU")
+    refused(lambda: B.compactor_select(p, ok, torch.zeros(L * H * n), kept_idx=torch.zeros(3, dtype=torch.int32),
+                                       kept_cnt=torch.zeros(L * H, dtype=torch.int32),
+                                       workspace=torch.zeros(256, dtype=torch.uint8)), "GPU")
+    aq = torch.zeros(L, 4 * H, n, 128, dtype=torch.bfloat16)
+    ap = B.AttnParams(L, H, 4 * H)
+    refused(lambda: B.compactor_attention_workspace_size(ap, [B.AttnRequest(aq[:, :3], k)]), "do not match")
+    refused(lambda: B.compactor_attention_workspace_size(ap, [B.AttnRequest(aq[:, :, :10], k)]), "same tokens")

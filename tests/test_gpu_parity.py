@@ -547,10 +547,13 @@ def test_attention_scores_low_rank_keys_and_blend_end_to_end(C):
 def test_attention_error_codes(C):
     k = torch.zeros(1, 1, 64, 128, dtype=torch.bfloat16, device=DEV)
     q = torch.zeros(1, 3, 64, 128, dtype=torch.bfloat16, device=DEV)
-    for bad in (C.AttnParams(1, 2, 3), C.AttnParams(1, 1, 3, pool=4)):
-        with pytest.raises(C.CompactorError) as e:
-            C.compactor_attention_scores(bad, [C.AttnRequest(q, k)])
+    k2 = torch.zeros(1, 2, 64, 128, dtype=torch.bfloat16, device=DEV)
+    for bad, kk in ((C.AttnParams(1, 2, 3), k2), (C.AttnParams(1, 1, 3, pool=4), k)):
+        with pytest.raises(C.CompactorError) as e:       # 3 query heads over 2 kv heads; even window
+            C.compactor_attention_scores(bad, [C.AttnRequest(q, kk)])
         assert e.value.code == C.EINVAL
+    with pytest.raises(ValueError):                      # tensors that contradict the parameters
+        C.compactor_attention_scores(C.AttnParams(1, 2, 4), [C.AttnRequest(q, k)])
     with pytest.raises(C.CompactorError) as e:
         C.compactor_attention_scores(C.AttnParams(1, 1, 3, chunk=128), [C.AttnRequest(q, k)])
     assert e.value.code == C.EUNSUPPORTED
