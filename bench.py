@@ -284,11 +284,25 @@ def main():
         paged_mode(a, torch, C, W, w, reqs, params, bufs, dev)
         return
 
+    copy_rates = None
     if a.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
         torch.neg(src, out=dst)           # one elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
+        # the same two plain copies timed: what this GPU sustains on a dense read + write stream,
+        # the pattern of the compaction stage without its indirection
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        copy_rates = {}
+        for name, fn in (("torch_neg_GB/s", lambda: torch.neg(src, out=dst)),
+                         ("torch_copy_GB/s", lambda: dst.copy_(src))):
+            fn()
+            e0.record()
+            for _ in range(10):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            copy_rates[name] = round(10 * 2.0 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
         del src, dst
 
     for _ in range(a.warmup):
@@ -415,6 +429,8 @@ def main():
         out["cold_ms_per_step"] = cold_ms
     if graph_ms is not None:
         out["graph_ms_per_step"] = graph_ms
+    if copy_rates is not None:
+        out["plain_copy_1GiB"] = copy_rates
     if not a.no_cpu_baseline:
         from oracle import compactor_oracle as O
         out["cpu_baseline"] = cpu_baseline(W, O, w, phi, a.cpu_seconds, a.cpu_threads)

@@ -25,7 +25,8 @@ constexpr int GRAM_TILE = 64;         // rows staged in LDS per step of the Gram
 constexpr int SCORE_STEP = 128;       // tokens a score workgroup multiplies per step
 constexpr int SCORE_MAX_TOKENS = 4096;   // most tokens a score workgroup takes (their scores wait in LDS)
 constexpr int SELECT_THREADS = 1024;
-constexpr int GATHER_ROWS = 64;       // kept rows per gather workgroup
+constexpr int GATHER_THREADS = 128;   // a gather workgroup: 8 groups of 16 lanes, one row each
+constexpr int GATHER_ROWS = 16;       // kept rows per gather workgroup (2 per 16-lane group)
 
 // One contiguous head range of one request, as seen by one launch.
 struct Seg {

@@ -2,27 +2,56 @@
 // into a dense packed cache (paper Sec. 3: the compressed cache consists of the retained
 // key/value pairs).  Pure copy, bit exact: 16 lanes move one 256-byte row with 16-byte
 // accesses, four rows per wave instruction, K and V in the same pass.
+//
+// Small workgroups with few rows per lane do best on this read + write stream (measured on the
+// benchmark's shape with random retained sets: 128 threads x 2 rows per 16-lane group 6.1 TB/s,
+// 256 x 4 5.7 TB/s, 256 x 8 2.8 TB/s): a workgroup is 2 waves and moves GATHER_ROWS = 16 rows.
 #include "common.h"
 
 namespace cmp {
 
-__global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
+constexpr int GATHER_GROUPS = GATHER_THREADS / 16;        // 16-lane groups, one row each per pass
+constexpr int GATHER_PASSES = GATHER_ROWS / GATHER_GROUPS;
+static_assert(GATHER_ROWS % GATHER_GROUPS == 0, "whole passes");
+
+// Workgroup -> (segment, head, tile of GATHER_ROWS retained rows).  The gather launches many small
+// workgroups, so this avoids the 64-bit divisions of the general block locator.
+__device__ __forceinline__ Where locate_rows(const SegTable &T, unsigned blk) {
+  Where w{0, 0, 0, 0, GATHER_ROWS};
+  unsigned base = 0;
+  for (int i = 0; i < T.nseg; ++i) {
+    const unsigned bph = ((unsigned)T.s[i].k_keep + GATHER_ROWS - 1) / GATHER_ROWS;
+    const unsigned nb = bph * (unsigned)T.s[i].head_count;
+    if (blk < base + nb || i == T.nseg - 1) {
+      const unsigned local = blk - base, hh = local / bph;
+      w.seg = i;
+      w.head = T.s[i].head_begin + (int)hh;
+      w.lhead = T.s[i].lhead0 + (int)hh;
+      w.tile = (int)(local - hh * bph);
+      return w;
+    }
+    base += nb;
+  }
+  return w;
+}
+
+__global__ __launch_bounds__(GATHER_THREADS) void gather_kernel(const SegTable T,
                                                      const int32_t *__restrict__ kept_idx,
                                                      uint16_t *__restrict__ k_packed,
                                                      uint16_t *__restrict__ v_packed) {
-  const Where w = locate_block(T, blockIdx.x, GATHER_ROWS, GATHER_ROWS, true);
+  const Where w = locate_rows(T, blockIdx.x);
   const Seg &s = T.s[w.seg];
   const int k = s.k_keep;
   const long long row0 = s.kept_off + (long long)w.head * k;      // first packed row of the head
   const int32_t *idx = kept_idx + row0;
   const uint16_t *ksrc = head_ptr(s.k_cache ? s.k_cache : s.k_score, s, w.head);
   const uint16_t *vsrc = head_ptr(s.v_cache, s, w.head);
-  const int chunk = threadIdx.x & 15, sub = threadIdx.x >> 4;     // 16 rows per pass
+  const int chunk = threadIdx.x & 15, sub = threadIdx.x >> 4;     // GATHER_GROUPS rows per pass
 
-  uint4 kv[GATHER_ROWS / 16], vv[GATHER_ROWS / 16];
+  uint4 kv[GATHER_PASSES], vv[GATHER_PASSES];
 #pragma unroll
-  for (int p = 0; p < GATHER_ROWS / 16; ++p) {
-    const int j = w.tile * GATHER_ROWS + p * 16 + sub;
+  for (int p = 0; p < GATHER_PASSES; ++p) {
+    const int j = w.tile * GATHER_ROWS + p * GATHER_GROUPS + sub;
     kv[p] = make_uint4(0, 0, 0, 0);
     vv[p] = make_uint4(0, 0, 0, 0);
     if (j < k) {
@@ -35,8 +64,8 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
     }
   }
 #pragma unroll
-  for (int p = 0; p < GATHER_ROWS / 16; ++p) {
-    const int j = w.tile * GATHER_ROWS + p * 16 + sub;
+  for (int p = 0; p < GATHER_PASSES; ++p) {
+    const int j = w.tile * GATHER_ROWS + p * GATHER_GROUPS + sub;
     if (j < k) {
       const long long off = (row0 + j) * D + chunk * 8;
       store_stream16(k_packed + off, kv[p]);
@@ -47,8 +76,8 @@ __global__ __launch_bounds__(256) void gather_kernel(const SegTable T,
 
 // Layer scope: the retained rows of a layer's heads are packed one head after the other, head h
 // holding kept_cnt[h] rows (ragged; the counts of a layer add up to H * k_keep).  A workgroup
-// takes 64 rows of a layer's region and looks every row's head up in the counts.
-__global__ __launch_bounds__(256) void gather_layer_kernel(const SegTable T,
+// takes GATHER_ROWS rows of a layer's region and looks every row's head up in the counts.
+__global__ __launch_bounds__(GATHER_THREADS) void gather_layer_kernel(const SegTable T,
                                                            const int32_t *__restrict__ kept_idx,
                                                            const int32_t *__restrict__ kept_cnt,
                                                            uint16_t *__restrict__ k_packed,
@@ -77,10 +106,10 @@ __global__ __launch_bounds__(256) void gather_layer_kernel(const SegTable T,
   const int32_t *cnt = kept_cnt + s.ghead0 + head0;
   const int chunk = threadIdx.x & 15, sub = threadIdx.x >> 4;
 
-  uint4 kv[GATHER_ROWS / 16], vv[GATHER_ROWS / 16];
+  uint4 kv[GATHER_PASSES], vv[GATHER_PASSES];
 #pragma unroll
-  for (int p = 0; p < GATHER_ROWS / 16; ++p) {
-    const int j = tile * GATHER_ROWS + p * 16 + sub;
+  for (int p = 0; p < GATHER_PASSES; ++p) {
+    const int j = tile * GATHER_ROWS + p * GATHER_GROUPS + sub;
     kv[p] = make_uint4(0, 0, 0, 0);
     vv[p] = make_uint4(0, 0, 0, 0);
     if (j < rows) {
@@ -99,8 +128,8 @@ __global__ __launch_bounds__(256) void gather_layer_kernel(const SegTable T,
     }
   }
 #pragma unroll
-  for (int p = 0; p < GATHER_ROWS / 16; ++p) {
-    const int j = tile * GATHER_ROWS + p * 16 + sub;
+  for (int p = 0; p < GATHER_PASSES; ++p) {
+    const int j = tile * GATHER_ROWS + p * GATHER_GROUPS + sub;
     if (j < rows) {
       const long long off = (row0 + j) * D + chunk * 8;
       store_stream16(k_packed + off, kv[p]);
@@ -122,8 +151,8 @@ __device__ __forceinline__ long long page_slot(const PagePool &P, int seg, int l
 }
 
 // Retained rows from the dense source tensors into pages: retained token j of a head goes to
-// logical slot j of that head.  Workgroups are dealt as in the dense gathers (64 rows each).
-__global__ __launch_bounds__(256) void gather_paged_kernel(const SegTable T, const PagePool P,
+// logical slot j of that head.  Workgroups are dealt as in the dense gathers.
+__global__ __launch_bounds__(GATHER_THREADS) void gather_paged_kernel(const SegTable T, const PagePool P,
                                                            const int32_t *__restrict__ kept_idx,
                                                            const int32_t *__restrict__ kept_cnt) {
   int seg = 0, head0 = 0, tile = 0, rows = 0;       // head0: the head, or the layer's first head
@@ -143,7 +172,7 @@ __global__ __launch_bounds__(256) void gather_paged_kernel(const SegTable T, con
       base += nb;
     }
   } else {
-    const Where w = locate_block(T, blockIdx.x, GATHER_ROWS, GATHER_ROWS, true);
+    const Where w = locate_rows(T, blockIdx.x);
     seg = w.seg; head0 = w.head; tile = w.tile; rows = T.s[w.seg].k_keep;
   }
   const Seg &s = T.s[seg];
@@ -152,11 +181,11 @@ __global__ __launch_bounds__(256) void gather_paged_kernel(const SegTable T, con
   const int chunk = threadIdx.x & 15, sub = threadIdx.x >> 4;
   const int layer = head0 / s.H;
 
-  uint4 kv[GATHER_ROWS / 16], vv[GATHER_ROWS / 16];
-  long long dst[GATHER_ROWS / 16];
+  uint4 kv[GATHER_PASSES], vv[GATHER_PASSES];
+  long long dst[GATHER_PASSES];
 #pragma unroll
-  for (int p = 0; p < GATHER_ROWS / 16; ++p) {
-    const int j = tile * GATHER_ROWS + p * 16 + sub;
+  for (int p = 0; p < GATHER_PASSES; ++p) {
+    const int j = tile * GATHER_ROWS + p * GATHER_GROUPS + sub;
     dst[p] = -1;
     kv[p] = make_uint4(0, 0, 0, 0);
     vv[p] = make_uint4(0, 0, 0, 0);
@@ -181,7 +210,7 @@ __global__ __launch_bounds__(256) void gather_paged_kernel(const SegTable T, con
     }
   }
 #pragma unroll
-  for (int p = 0; p < GATHER_ROWS / 16; ++p) {
+  for (int p = 0; p < GATHER_PASSES; ++p) {
     if (dst[p] >= 0) {
       store_stream16(P.k + dst[p] + chunk * 8, kv[p]);
       store_stream16(P.v + dst[p] + chunk * 8, vv[p]);
@@ -259,7 +288,7 @@ hipError_t launch_gather_paged(const SegTable &T, const PagePool &P, const int32
   }
   if (nb <= 0) return hipSuccess;
   if (nb > 0x7fffffffll) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(gather_paged_kernel, dim3((unsigned)nb), dim3(256), 0, st, T, P, kept_idx,
+  hipLaunchKernelGGL(gather_paged_kernel, dim3((unsigned)nb), dim3(GATHER_THREADS), 0, st, T, P, kept_idx,
                      kept_cnt);
   return hipGetLastError();
 }
@@ -273,14 +302,14 @@ hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, const int32
             (T.s[i].head_count / T.s[i].H);
     if (nb <= 0) return hipSuccess;
     if (nb > 0x7fffffffll) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(gather_layer_kernel, dim3((unsigned)nb), dim3(256), 0, st, T, kept_idx,
+    hipLaunchKernelGGL(gather_layer_kernel, dim3((unsigned)nb), dim3(GATHER_THREADS), 0, st, T, kept_idx,
                        kept_cnt, k_packed, v_packed);
     return hipGetLastError();
   }
   const long long nb = total_blocks(T, GATHER_ROWS, GATHER_ROWS, true);
   if (nb <= 0) return hipSuccess;
   if (nb > 0x7fffffffll) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(gather_kernel, dim3((unsigned)nb), dim3(256), 0, st, T, kept_idx, k_packed,
+  hipLaunchKernelGGL(gather_kernel, dim3((unsigned)nb), dim3(GATHER_THREADS), 0, st, T, kept_idx, k_packed,
                      v_packed);
   return hipGetLastError();
 }
