@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 # scale factors read off a 1 GiB copy kernel): profiles/compress_config2_hbm_traffic.txt.
 # Only the default workload has been profiled; other workloads report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("config2_llama31_8b_n32768", "gather"): 2.592e9,
+    ("config2_llama31_8b_n32768", "gather"): 2.607e9,
     ("config2_llama31_8b_n32768", "gram"): 2.169e9,
     ("config2_llama31_8b_n32768", "score"): 2.232e9,
 }
