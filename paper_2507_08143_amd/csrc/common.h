@@ -75,15 +75,19 @@ struct Where {
 // head are as even as the step allows.  per_block <= 0 means one block per head.
 __host__ __device__ __forceinline__ int chunk_of(int units, int per_block, int step) {
   if (per_block <= 0) return units > 0 ? units : 1;
-  const long long splits = ((long long)units + per_block - 1) / per_block;
-  const long long even = (units + splits - 1) / (splits > 0 ? splits : 1);
-  const long long c = (even + step - 1) / step * step;
-  return (int)(c > 0 ? c : step);
+  // 32-bit unsigned arithmetic (units < 2^31 - 64, per_block and step small): every workgroup
+  // of a launch evaluates this once per segment
+  const unsigned u = units > 0 ? (unsigned)units : 0u, pb = (unsigned)per_block, st = (unsigned)step;
+  const unsigned splits = (u + pb - 1) / pb;
+  const unsigned even = (u + splits - 1) / (splits > 0 ? splits : 1u);
+  const unsigned c = (even + st - 1) / st * st;
+  return (int)(c > 0 ? c : st);
 }
 __host__ __device__ __forceinline__ int blocks_per_head(int units, int per_block, int step) {
   if (per_block <= 0) return 1;
-  const int c = chunk_of(units, per_block, step);
-  return (int)(((long long)units + c - 1) / c);
+  const unsigned c = (unsigned)chunk_of(units, per_block, step);
+  const unsigned u = units > 0 ? (unsigned)units : 0u;
+  return (int)((u + c - 1) / c);
 }
 
 __device__ __forceinline__ Where locate_block(const SegTable &T, int blk, int per_block, int step,
