@@ -36,7 +36,7 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char *p) {
 // (workgroup, head) intersection yields one partial Gram matrix, stored in slot
 // workgroup + head (unique, because along the tile sequence workgroup and head only grow).
 // All workgroups are resident at once and do the same amount of streaming, so there is no
-// tail, and the partials are written when a head ends, spread over the run of the kernel.
+// tail; the partials leave at the end of a workgroup's run where possible.
 //
 // The 10 upper blocks are split over the 4 waves of a workgroup (3, 3, 2, 2): every wave sees
 // all tokens of the tile but owns its blocks outright, so no cross-wave reduction is needed and
@@ -115,26 +115,47 @@ __device__ __forceinline__ void gram_body(const SegTable &T, int tiles_per_wg, l
   // A block is stored in accumulator order: float4 number 64*q + lane of a block holds rows
   // 8q + 4*(lane>>5) .. +3 of column lane & 31, so a flush is 16-byte stores, 1 KB per wave
   // instruction (see partial_quad in common.h for the readers).
-  auto flush = [&](int lhead) {
-    float *out = partials + ((size_t)blockIdx.x + lhead) * GRAM_PARTIAL_FLOATS;
+  // Writes in the middle of the read stream are costly on this memory system (a few tens of MB of
+  // them slow a 2 GB read pass by 7 %), so a partial that is finished before the workgroup's run
+  // ends is parked in LDS (each wave its own blocks, no barrier needed) and leaves with the last
+  // one; only a workgroup that crosses more than one head boundary writes mid-run, with
+  // streaming stores.
+  float *park = reinterpret_cast<float *>(smem + 2 * TILE_BYTES);
+  int parked_lhead = -1;
+  enum { TO_GLOBAL, TO_GLOBAL_STREAM, TO_LDS };
+  auto flush = [&](int lhead, int how) {
+    float *out = how == TO_LDS ? park
+                               : partials + ((size_t)blockIdx.x + lhead) * GRAM_PARTIAL_FLOATS;
 #pragma unroll
     for (int b = 0; b < 3; ++b) {
       if (b < nblk) {
         float *ob = out + (first + b) * GBLK;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          *reinterpret_cast<float4 *>(ob + (64 * q + lane) * 4) =
-              make_float4(acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]);
+          const float4 v = make_float4(acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]);
+          if (how == TO_GLOBAL_STREAM)
+            store_stream16(ob + (64 * q + lane) * 4, make_uint4(__float_as_uint(v.x), __float_as_uint(v.y),
+                                                                 __float_as_uint(v.z), __float_as_uint(v.w)));
+          else
+            *reinterpret_cast<float4 *>(ob + (64 * q + lane) * 4) = v;
           acc[b][4 * q] = acc[b][4 * q + 1] = acc[b][4 * q + 2] = acc[b][4 * q + 3] = 0.f;
         }
       }
     }
   };
   bool dirty = false;
-  auto finish_tile = [&]() {       // after a tile has been multiplied
+  auto finish_tile = [&](bool last_of_run) {       // after a tile has been multiplied
     dirty = true;
     if (C.tile + 1 == C.tph) {
-      flush(T.s[C.seg].lhead0 + C.hh);
+      const int lhead = T.s[C.seg].lhead0 + C.hh;
+      if (last_of_run) {
+        flush(lhead, TO_GLOBAL);
+      } else if (parked_lhead < 0) {
+        flush(lhead, TO_LDS);
+        parked_lhead = lhead;
+      } else {
+        flush(lhead, TO_GLOBAL_STREAM);
+      }
       dirty = false;
     }
     cursor_next<GRAM_TILE>(T, C);
@@ -149,22 +170,36 @@ __device__ __forceinline__ void gram_body(const SegTable &T, int tiles_per_wg, l
     __syncthreads();
     load_tile(t + 2, stA);
     compute_tile(smem);
-    finish_tile();
+    finish_tile(t + 1 == count);
     if (t + 1 < count) {
       store_tile(smem + TILE_BYTES, stB);
       __syncthreads();
       load_tile(t + 3, stB);
       compute_tile(smem + TILE_BYTES);
-      finish_tile();
+      finish_tile(t + 2 == count);
     }
   }
-  if (dirty) flush(T.s[C.seg].lhead0 + C.hh);
+  if (dirty) flush(T.s[C.seg].lhead0 + C.hh, TO_GLOBAL);
+  if (parked_lhead >= 0) {         // the parked partial: every lane copies what it wrote itself
+    float *out = partials + ((size_t)blockIdx.x + parked_lhead) * GRAM_PARTIAL_FLOATS;
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+      if (b < nblk) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int o = (first + b) * GBLK + (64 * q + lane) * 4;
+          *reinterpret_cast<float4 *>(out + o) = *reinterpret_cast<const float4 *>(park + o);
+        }
+      }
+    }
+  }
 }
 
 __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, int tiles_per_wg,
                                                              long long total,
                                                              float *__restrict__ partials) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TILE_BYTES];
+  // two key tiles and room for one parked partial Gram matrix
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * TILE_BYTES + GRAM_PARTIAL_FLOATS * 4];
   // every wave passes the same workgroup barriers, each in its own copy of the loop
   switch (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) {
     case 0: gram_body<0>(T, tiles_per_wg, total, partials, smem); break;
