@@ -169,17 +169,23 @@ __global__ __launch_bounds__(256, M > 64 ? 1 : 2) void score_kernel(
     if (lane == 0) atomicOr(&status[s.ghead0 + w.head], COMPACTOR_STATUS_NONFINITE);
   }
   __syncthreads();
-  {    // the scores, 16 bytes per lane where the head's base allows it; streaming stores disturb
-       // the other workgroups' reads least (measured: 1 to 4 % of the kernel's time)
+  {    // the scores leave as 16-byte streaming stores (they disturb the other workgroups' reads
+       // least: 1 to 4 % of the kernel's time against plain stores); a head whose scores do not
+       // start on a 16-byte boundary (odd n) gets up to 3 single stores in front
     const int cnt = tok_end - tok_begin;
     float *dst = sp + tok_begin;
-    if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+    const int mis = (int)((reinterpret_cast<uintptr_t>(dst) >> 2) & 3u);
+    const int lead = min(cnt, mis ? 4 - mis : 0);
+    if (tid < lead) dst[tid] = sc_l[tid];
+    if (lead == 0) {
       for (int i = 4 * tid; i + 3 < cnt; i += 4 * 256)
         store_stream16(dst + i, *reinterpret_cast<const uint4 *>(&sc_l[i]));
-      for (int i = (cnt & ~3) + tid; i < cnt; i += 256) dst[i] = sc_l[i];
     } else {
-      for (int i = tid; i < cnt; i += 256) dst[i] = sc_l[i];
+      for (int i = lead + 4 * tid; i + 3 < cnt; i += 4 * 256)
+        store_stream16(dst + i, make_uint4(__float_as_uint(sc_l[i]), __float_as_uint(sc_l[i + 1]),
+                                           __float_as_uint(sc_l[i + 2]), __float_as_uint(sc_l[i + 3])));
     }
+    for (int i = lead + ((cnt - lead) & ~3) + tid; i < cnt; i += 256) dst[i] = sc_l[i];
   }
   if (hist1 != nullptr) {        // integer adds: the per-head histogram is order independent
     int *h1 = hist1 + (size_t)(w.lhead / pool_heads(T, s)) * HIST1_BINS;
