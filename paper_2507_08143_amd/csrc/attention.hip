@@ -234,11 +234,15 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
     }
   }
 
-  // column sums: add over the 32 query lanes of each half, average over the query heads
+  // column sums: add over the 32 query lanes of each half, average over the query heads.  After
+  // the reduction every lane of a half holds the sum of key 8*(v>>2) + 4*lh + (v&3) of its tile;
+  // lane l32 keeps the one whose key number is l32, so that a tile's 32 sums leave as one
+  // 128-byte store instead of 32 single ones (small stores between streaming reads are costly).
   const float inv_g = 1.f / (float)s.G;
   float *out = raw + s.out_off + (long long)head * n;
 #pragma unroll
-  for (int kt = 0; kt < 2; ++kt)
+  for (int kt = 0; kt < 2; ++kt) {
+    float mine = 0.f;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       float x = pacc[kt][v];
@@ -247,9 +251,11 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
       x += __shfl_xor(x, 4);
       x += __shfl_xor(x, 8);
       x += __shfl_xor(x, 16);
-      const int key = key_of(kt, v);
-      if (l32 == 0 && key < n) out[key] = x * inv_g;
+      if (l32 == 8 * (v >> 2) + 4 * lh + (v & 3)) mine = x;
     }
+    const int key = c0 + 64 * wave + 32 * kt + l32;
+    if (lh == ((l32 >> 2) & 1) && key < n) out[key] = mine * inv_g;
+  }
 }
 
 __global__ __launch_bounds__(256, 2) void attn_colsum_kernel(const AttnTable T,
