@@ -81,23 +81,35 @@ __device__ int radix_pass(const float *__restrict__ sp, uint32_t *keys, int n, i
   auto tally = [&](uint32_t k) {
     if (hi_shift >= 32 || (k >> hi_shift) == prefix) atomicAdd(&hist[(k >> shift) & (nb - 1)], 1);
   };
-  // 16-byte accesses where the head's scores (or the LDS keys) allow it, scalars for the rest
-  const bool vec = FROM_LDS || (reinterpret_cast<uintptr_t>(sp) & 15u) == 0;
-  const int nv = vec ? n >> 2 : 0;
+  // 16-byte accesses: the LDS keys are aligned by token; scores in global memory are read from
+  // the first 16-byte boundary on, the `lead` tokens in front of it (and the tail) one by one
+  const int lead = FROM_LDS ? 0 : min(n, (int)((4u - ((reinterpret_cast<uintptr_t>(sp) >> 2) & 3u)) & 3u));
+  const int nv = (n - lead) >> 2;
+  if (tid < lead) {
+    const uint32_t k = score_key(sp[tid]);
+    if (STORE) keys[tid] = k;
+    tally(k);
+  }
 #pragma unroll 4
   for (int i = tid; i < nv; i += SELECT_THREADS) {
     uint4 k4;
     if (FROM_LDS) {
       k4 = reinterpret_cast<const uint4 *>(keys)[i];
     } else {
-      const float4 f = reinterpret_cast<const float4 *>(sp)[i];
+      const float4 f = reinterpret_cast<const float4 *>(sp + lead)[i];
       k4 = make_uint4(score_key(f.x), score_key(f.y), score_key(f.z), score_key(f.w));
-      if (STORE) reinterpret_cast<uint4 *>(keys)[i] = k4;
+      if (STORE) {
+        if (lead == 0) {
+          reinterpret_cast<uint4 *>(keys)[i] = k4;
+        } else {
+          uint32_t *kd = keys + lead + 4 * i;
+          kd[0] = k4.x; kd[1] = k4.y; kd[2] = k4.z; kd[3] = k4.w;
+        }
+      }
     }
     tally(k4.x); tally(k4.y); tally(k4.z); tally(k4.w);
   }
-#pragma unroll 4
-  for (int i = 4 * nv + tid; i < n; i += SELECT_THREADS) {
+  for (int i = lead + 4 * nv + tid; i < n; i += SELECT_THREADS) {
     const uint32_t k = FROM_LDS ? keys[i] : score_key(sp[i]);
     if (STORE) keys[i] = k;
     tally(k);
