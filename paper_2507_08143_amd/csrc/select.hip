@@ -290,14 +290,16 @@ __device__ __forceinline__ SelWhere sel_locate(const SegTable &T, int blk) {
 // exists.  Every load is issued before any key is used.
 __device__ __forceinline__ unsigned load_chunk_keys(const float *__restrict__ sp, const SelWhere &q,
                                                     uint32_t (&key)[SEL_ROUNDS][4]) {
-  const bool aligned = (reinterpret_cast<uintptr_t>(sp + q.tok_begin) & 15u) == 0;   // uniform
+  // one 16-byte load per 4 tokens also where a head's scores start off a 16-byte boundary (odd
+  // n): global memory takes vector loads at any 4-byte address
+  typedef float f32x4_any __attribute__((ext_vector_type(4), aligned(4)));
   float f[SEL_ROUNDS][4];
   unsigned valid = 0;
 #pragma unroll
   for (int r = 0; r < SEL_ROUNDS; ++r) {
     const int i0 = q.tok_begin + 4 * (r * SELECT_THREADS + (int)threadIdx.x);
-    if (aligned && i0 + 3 < q.tok_end) {
-      const float4 v = *reinterpret_cast<const float4 *>(sp + i0);
+    if (i0 + 3 < q.tok_end) {
+      const f32x4_any v = *reinterpret_cast<const f32x4_any *>(sp + i0);
       f[r][0] = v.x; f[r][1] = v.y; f[r][2] = v.z; f[r][3] = v.w;
       valid |= 0xfu << (4 * r);
     } else {
