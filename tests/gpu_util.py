@@ -82,9 +82,13 @@ def check_selection_valid(scores: np.ndarray, kept: np.ndarray, k: int, what="")
         assert np.flatnonzero(mask & (s == kept_min)).max() < np.flatnonzero(~mask & (s == ev_max)).min(), what
 
 
-def run_and_check(C, w: W.Workload, device, heads=None, group_bytes=0, kept_tol_scale=1.0):
-    """Fused compress on the whole workload; oracle on `heads` (list of (b,l,h)) or all."""
+def run_and_check(C, w: W.Workload, device, heads=None, group_bytes=0, kept_tol_scale=1.0, tune=None):
+    """Fused compress on the whole workload; oracle on `heads` (list of (b,l,h)) or all.
+    tune: launch-shape overrides (fields of Params such as gram_wgs) that must not change results
+    beyond the tolerance."""
     params, reqs = make_call(C, w, device, group_bytes)
+    for name, value in (tune or {}).items():
+        setattr(params, name, value)
     out = C.compactor_compress(params, reqs, want_scores=True)
     torch.cuda.synchronize()
     so, ko, kk = C.compactor_layout(params, reqs)

@@ -219,6 +219,17 @@ def test_ragged_token_counts(C, n):
         _say("  max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
 
 
+@pytest.mark.parametrize("gram_wgs", [1, 2, 5, 12])
+def test_gram_partitions_that_cross_heads(C, gram_wgs):
+    """The Gram kernel deals 64-row tiles out evenly, across head boundaries.  One workgroup for
+    six heads of 11 tiles crosses five boundaries (one partial parked in LDS, four written mid-run);
+    5 workgroups of 14 tiles cross one or two; 12 cross none or one.  All must match the oracle."""
+    _say("Gram partition with %d workgroup(s) over 6 heads of 700 tokens" % gram_wgs)
+    w = W.config2(DEV, L=2, H=3, n=700)
+    st, _ = U.run_and_check(C, w, DEV, tune={"gram_wgs": gram_wgs})
+    _say("  max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+
+
 def test_config2_small(C):
     _say("config 2 shape, 2 layers x 8 heads, n=6000")
     st, _ = U.run_and_check(C, W.config2(device=DEV, L=2, H=8, n=6000), DEV)
