@@ -41,7 +41,6 @@ def parse():
     ap.add_argument("--group-mb", type=float, default=0.0, help="head-group size in MiB (0 = library default)")
     ap.add_argument("--gram-wgs", type=int, default=0, help="tuning override (0 = library's choice)")
     ap.add_argument("--score-tokens", type=int, default=0, help="tuning override (0 = library's choice)")
-    ap.add_argument("--streams", type=int, default=0, help="stream lanes (0 = library default)")
     ap.add_argument("--scope", choices=["head", "layer"], default="head",
                     help="selection pool: per head (the headline metric) or head-adaptive per layer")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -57,8 +56,6 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="also capture one step in a HIP graph and time its replays (graph_ms_per_step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--allow-flagged", action="store_true",
-                    help="do not fail when a head reports a status flag (kernel experiments only)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
     ap.add_argument("--cpu-threads", type=int, default=0,
                     help="cap the oracle leg's BLAS threads (0 = the host's default, all cores)")
@@ -258,7 +255,6 @@ def main():
     mk = lambda events: C.Params(w.layers, w.kv_heads, sketch_dim=w.sketch_dim, phi=phi,
                                  ridge_rel=w.ridge_rel, group_bytes=group_bytes, stage_events=events,
                                  gram_wgs=a.gram_wgs, score_tokens=a.score_tokens,
-                                 streams=(1 if events is not None else a.streams),
                                  select_scope=(C.SCOPE_LAYER if a.scope == "layer" else C.SCOPE_HEAD))
     params, params_ev = mk(None), mk(ev)
     reqs = [C.Request(k_score=r.k, v_cache=r.v, ratio=r.ratio) for r in w.requests]
@@ -316,7 +312,7 @@ def main():
     ms_per_step = dt / a.steps * 1e3
     tokens = w.tokens
     value = tokens / (dt / a.steps)
-    assert a.allow_flagged or int(bufs["status"].max()) == 0, "a head was flagged during the benchmark"
+    assert int(bufs["status"].max()) == 0, "a head was flagged during the benchmark"
 
     # the same steps again with per-stage HIP events on the launch stream
     stage_ms, step_ms = {}, []

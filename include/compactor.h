@@ -23,9 +23,7 @@
  *     pointer marked "host" is ordinary host memory owned by the caller.  The
  *     library never allocates, frees or synchronises: all work is enqueued on
  *     the stream that is passed in (a hipStream_t cast to void*, NULL = the
- *     default stream), or on helper streams ordered after and before it (see
- *     compactor_params_t.streams), and outputs are valid once that stream has
- *     drained.
+ *     default stream), and outputs are valid once that stream has drained.
  *   - Keys and values are bfloat16 (raw 16-bit patterns), head_dim contiguous.
  *   - Heads are numbered request-major: head g = (sum of L*H of earlier
  *     requests) + layer*H + kv_head.  All per-head outputs use this order and
@@ -35,9 +33,7 @@
  *     the outputs untouched.  Numerical trouble inside a head never aborts: it
  *     is reported in that head's status word (see COMPACTOR_STATUS_*).
  *   - Thread safety: concurrent calls are safe when they use distinct workspaces
- *     and output buffers.  The only process-wide state is the per-device set of
- *     helper streams used when params.streams > 1; calls that use it are
- *     serialised while they enqueue.
+ *     and output buffers; the library keeps no state between calls.
  */
 #ifndef COMPACTOR_H
 #define COMPACTOR_H
@@ -95,18 +91,14 @@ typedef struct compactor_params {
                              K^T K in exact mode).  0 is Algorithm 1 as printed. */
   float   lambda_blend;   /* lambda of Eq. "scoring" (paper default 0.3); used only where
                              attn != NULL */
-  int64_t group_bytes;    /* tuning: heads are processed in groups whose keys total about this
-                             many bytes so that the second pass over a group's keys hits the
-                             last-level cache; 0 = library default */
+  int64_t group_bytes;    /* heads are processed in groups whose keys total about this many bytes,
+                             one launch sequence per group: bounds the workspace (sized for the
+                             largest group).  0 = one group.  Not a speed knob: on MI355X a second
+                             pass that finds a group's keys in the last-level cache is no faster
+                             than one that streams them from HBM. */
   int32_t gram_wgs;       /* tuning: workgroups of the persistent Gram kernel and target tokens */
   int32_t score_tokens;   /* per workgroup of the score kernel (at most 4096; larger values are
                              clamped); 0 = chosen by the library */
-  int32_t streams;        /* concurrency: 0 or 1 = every kernel on the caller's stream.  2..4 = head
-                             groups are spread over that many lanes (the caller's stream plus
-                             helper streams that the library creates once per device and keeps),
-                             forked from and joined back into the caller's stream by events, so
-                             that latency-bound kernels of one group run beside streaming kernels
-                             of another.  The workspace grows to one slice per lane. */
   int32_t select_scope;   /* COMPACTOR_SCOPE_HEAD (default): every head keeps its own top k_keep.
                              COMPACTOR_SCOPE_LAYER: head-adaptive selection (Sec. 3.3, retain the
                              top scores "across all heads"; the paper's experiments, Sec. 4): the
@@ -142,8 +134,10 @@ void compactor_default_params(compactor_params_t *p, int32_t layers, int32_t kv_
 
 /* k_keep = clamp(ceil(r*N), 1, N) (Sec. 3: "top-k with k = ceil(r N)").  r is widened to
  * double and the product shrunk by (1 - 2^-23) before the ceiling, so that a float32 ratio whose
- * product with N is an integer on paper does not round up to the next integer.
- * Returns 0 for n <= 0. host. */
+ * product with N is an integer on paper (r = 0.001f, N = 1000) does not round up to the next
+ * integer.  The price: a product that lies less than r*N*2^-23 above an integer is taken for
+ * that integer, so for an arbitrary float ratio k_keep is ceil(r*N) - 1 in about 2 of 1000
+ * (r, N) pairs and ceil(r*N) otherwise.  Returns 0 for n <= 0. host. */
 int32_t compactor_keep_count(int32_t n, float ratio);
 
 /* Element offsets of each request inside the flat output buffers. host.
@@ -170,7 +164,9 @@ int compactor_srht_phi(int32_t sketch_dim, const uint8_t *signs, const int32_t *
 
 /* Bytes of device workspace that score / select / compress need for this batch. host.
  * The workspace must be 256-byte aligned; its contents are scratch (no state is kept
- * between calls). */
+ * between calls).  The size depends on the number of compute units of the current HIP device
+ * (it sets the number of partial Gram matrices): ask with the device current that will run the
+ * call.  Where no device can be queried the size for 256 compute units (MI355X) is returned. */
 int compactor_workspace_size(const compactor_params_t *p, const compactor_request_t *reqs,
                              int32_t nreq, size_t *bytes);
 

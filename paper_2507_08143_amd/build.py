@@ -42,7 +42,7 @@ def _run(cmd):
 
 def build(verbose: bool = False, jobs: int = 6, extra_flags=(), lib: str = LIB,
           build_dir: str = BUILD) -> str:
-    """Compile every source and link `lib`.  extra_flags (e.g. -DCMP_W_TERMS=2) and a different
+    """Compile every source and link `lib`.  extra_flags and a different
     output path serve experiments; the defaults give the product library."""
     os.makedirs(build_dir, exist_ok=True)
     objs = [os.path.join(build_dir, s.replace(".hip", ".o")) for s in SOURCES]

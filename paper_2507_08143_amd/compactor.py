@@ -39,7 +39,7 @@ class _Params(C.Structure):
     _fields_ = [("layers", C.c_int32), ("kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("sketch_dim", C.c_int32), ("phi", C.c_void_p), ("ridge_rel", C.c_float),
                 ("lambda_blend", C.c_float), ("group_bytes", C.c_int64),
-                ("gram_wgs", C.c_int32), ("score_tokens", C.c_int32), ("streams", C.c_int32),
+                ("gram_wgs", C.c_int32), ("score_tokens", C.c_int32),
                 ("select_scope", C.c_int32), ("stage_events", C.c_void_p)]
 
 
@@ -187,7 +187,6 @@ class Params:
     stage_events: Optional["StageEvents"] = None   # profiling aid (see the header)
     gram_wgs: int = 0                              # tuning knobs, 0 = library's choice
     score_tokens: int = 0
-    streams: int = 0                                # 2..4 = spread head groups over helper streams
     select_scope: int = 0                           # SCOPE_HEAD, or SCOPE_LAYER (head-adaptive)
 
     def c(self, on_gpu: bool = True) -> _Params:
@@ -203,7 +202,7 @@ class Params:
         ev = C.cast(self.stage_events.array, C.c_void_p) if self.stage_events is not None else None
         return _Params(self.layers, self.kv_heads, self.head_dim, self.sketch_dim, phi,
                        self.ridge_rel, self.lambda_blend, self.group_bytes, self.gram_wgs,
-                       self.score_tokens, self.streams, self.select_scope, ev)
+                       self.score_tokens, self.select_scope, ev)
 
 
 @dataclass
@@ -281,8 +280,7 @@ def compactor_default_params(layers: int, kv_heads: int) -> Params:
     p = _Params()
     _lib.compactor_default_params(C.byref(p), layers, kv_heads)
     return Params(p.layers, p.kv_heads, p.sketch_dim, None, p.ridge_rel, p.lambda_blend,
-                  p.group_bytes, p.head_dim, None, p.gram_wgs, p.score_tokens, p.streams,
-                  p.select_scope)
+                  p.group_bytes, p.head_dim, None, p.gram_wgs, p.score_tokens, p.select_scope)
 
 
 def compactor_srht_phi(sketch_dim: int, signs, cols, device, stream=None) -> torch.Tensor:
@@ -313,10 +311,14 @@ def compactor_workspace_size(params: Params, reqs: Sequence[Request]) -> int:
     return int(out.value)
 
 
-def _workspace(params, reqs, workspace):
+def _workspace(params, reqs, workspace, stream=None):
     if workspace is None:
         nbytes = max(256, compactor_workspace_size(params, reqs))
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=_device(reqs))
+        if stream is not None:
+            # the block is used on `stream`, not on the stream torch allocated it for: tell the
+            # allocator, or it may hand the block out again while the kernels still run
+            workspace.record_stream(stream)
     return workspace
 
 
@@ -329,7 +331,7 @@ def compactor_score(params: Params, reqs: Sequence[Request], scores=None, status
         scores = torch.empty(so[-1], dtype=torch.float32, device=dev)
     if status is None:
         status = torch.empty(len(reqs) * params.layers * params.kv_heads, dtype=torch.int32, device=dev)
-    workspace = _workspace(params, reqs, workspace)
+    workspace = _workspace(params, reqs, workspace, stream)
     pp, arr, n = _marshal(params, reqs)
     _out(scores, so[-1], torch.float32, "scores")
     _out(status, n * params.layers * params.kv_heads, torch.int32, "status")
@@ -349,9 +351,7 @@ def compactor_select(params: Params, reqs: Sequence[Request], scores: torch.Tens
     if kept_cnt is None:
         kept_cnt = torch.empty(len(reqs) * params.layers * params.kv_heads, dtype=torch.int32, device=dev)
     pp, arr, n = _marshal(params, reqs)
-    if workspace is None:
-        nbytes = max(256, compactor_workspace_size(params, reqs))
-        workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    workspace = _workspace(params, reqs, workspace, stream)
     so, _, _ = compactor_layout(params, reqs)
     _out(scores, so[-1], torch.float32, "scores")
     _out(kept_idx, ko[-1], torch.int32, "kept_idx")
@@ -431,7 +431,7 @@ def compactor_compress(params: Params, reqs: Sequence[Request], want_scores: boo
         v_packed = torch.empty(ko[-1], params.head_dim, dtype=torch.bfloat16, device=dev)
     if status is None:
         status = torch.empty(nh, dtype=torch.int32, device=dev)
-    workspace = _workspace(params, reqs, workspace)
+    workspace = _workspace(params, reqs, workspace, stream)
     pp, arr, n = _marshal(params, reqs)
     _out(scores, so[-1], torch.float32, "scores")
     _out(kept_idx, ko[-1], torch.int32, "kept_idx")
@@ -502,6 +502,8 @@ def compactor_attention_scores(params: AttnParams, reqs: Sequence[AttnRequest], 
     if workspace is None:
         workspace = torch.empty(max(256, compactor_attention_workspace_size(params, reqs)),
                                 dtype=torch.uint8, device=dev)
+        if stream is not None:
+            workspace.record_stream(stream)
     arr = (_AttnRequest * len(reqs))(*[r.c(params) for r in reqs])
     _out(attn, total, torch.float32, "attn")
     _out(workspace, 0, torch.uint8, "workspace")

@@ -3,8 +3,6 @@
 #include <math.h>
 #include <string.h>
 
-#include <mutex>
-
 #include "common.h"
 
 using namespace cmp;
@@ -32,7 +30,7 @@ int check_params(const compactor_params_t *p, bool scoring) {
     if (!(p->ridge_rel >= 0.f) || !isfinite(p->ridge_rel)) return COMPACTOR_EINVAL;
     if (!isfinite(p->lambda_blend)) return COMPACTOR_EINVAL;
   }
-  if (p->group_bytes < 0 || p->gram_wgs < 0 || p->score_tokens < 0 || p->streams < 0)
+  if (p->group_bytes < 0 || p->gram_wgs < 0 || p->score_tokens < 0)
     return COMPACTOR_EINVAL;
   if (p->select_scope != COMPACTOR_SCOPE_HEAD && p->select_scope != COMPACTOR_SCOPE_LAYER)
     return COMPACTOR_EINVAL;
@@ -182,70 +180,27 @@ int for_each_group(const compactor_params_t *p, const compactor_request_t *reqs,
   return COMPACTOR_OK;
 }
 
-constexpr int MAX_LANES = 4;          // concurrent stream lanes (the caller's stream + 3 helpers)
-constexpr int GROUPS_PER_LANE = 2;    // default pipeline depth when the caller names no group size
-
-int lanes_of(const compactor_params_t *p) {
-  const int l = p->streams > 0 ? p->streams : 1;
-  return l > MAX_LANES ? MAX_LANES : l;
-}
-
-// Key rows per head group.  An explicit group_bytes wins; otherwise a single-lane call is one
-// group and a multi-lane call gets GROUPS_PER_LANE groups per lane, so that the latency-bound
-// kernels of one group (factorisation, selection) run beside the streaming kernels of others.
-long long group_rows_of(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq) {
+// Key rows per head group: an explicit group_bytes wins, otherwise the whole call is one group.
+long long group_rows_of(const compactor_params_t *p) {
   if (p->group_bytes > 0) {
     const long long r = p->group_bytes / (D * 2);
     return r < 1 ? 1 : r;
   }
-  const int lanes = lanes_of(p);
-  if (lanes <= 1) return DEFAULT_GROUP_BYTES / (D * 2);
-  long long total = 0;
-  for (int b = 0; b < nreq; ++b) total += (long long)reqs[b].n * p->layers * p->kv_heads;
-  const long long r = (total + lanes * GROUPS_PER_LANE - 1) / (lanes * GROUPS_PER_LANE);
-  return r < 1 ? 1 : r;
+  return DEFAULT_GROUP_BYTES / (D * 2);
 }
 
-// Helper streams and fork/join events, one set per device, created on first use and kept for
-// the life of the process.  Enqueueing through the pool is serialised by its mutex.
-struct LanePool {
-  std::mutex mu;
-  bool ready = false;
-  hipStream_t helper[MAX_LANES - 1];
-  hipEvent_t fork;
-  hipEvent_t join[MAX_LANES - 1];
-};
-constexpr int MAX_DEVICES = 16;
-LanePool g_pools[MAX_DEVICES];
-
-LanePool *lane_pool() {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
-  LanePool *lp = &g_pools[dev];
-  std::lock_guard<std::mutex> lock(lp->mu);
-  if (!lp->ready) {
-    for (int i = 0; i < MAX_LANES - 1; ++i) {
-      if (hipStreamCreateWithFlags(&lp->helper[i], hipStreamNonBlocking) != hipSuccess) return nullptr;
-      if (hipEventCreateWithFlags(&lp->join[i], hipEventDisableTiming) != hipSuccess) return nullptr;
-    }
-    if (hipEventCreateWithFlags(&lp->fork, hipEventDisableTiming) != hipSuccess) return nullptr;
-    lp->ready = true;
-  }
-  return lp;
-}
-
-// Bytes one lane needs (the largest group); a call needs lanes_of(p) such slices.
+// Bytes of workspace a call needs: what its largest head group needs (groups run one after the
+// other on the stream and reuse the workspace).
 int workspace_need(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
-                   bool local_scores, size_t *slice, size_t *bytes) {
+                   bool local_scores, size_t *bytes) {
   size_t need = 0;
-  const int rc = for_each_group(p, reqs, nreq, group_rows_of(p, reqs, nreq), local_scores,
+  const int rc = for_each_group(p, reqs, nreq, group_rows_of(p), local_scores,
                                 [&](const SegTable &T, long long) {
                                   const size_t t = group_bytes_needed(p, T, local_scores).total();
                                   if (t > need) need = t;
                                   return COMPACTOR_OK;
                                 });
-  if (slice) *slice = need;
-  *bytes = need * lanes_of(p);
+  *bytes = need;
   return rc;
 }
 
@@ -322,37 +277,58 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   return COMPACTOR_OK;
 }
 
-// Runs fn(T, rows, stream, workspace slice) for every head group.  With one lane everything is
-// enqueued on the caller's stream.  With several lanes group g goes to lane g % lanes: lane 0
-// is the caller's stream, the others are the pool's helper streams, forked from the caller's
-// stream by an event before the first group and joined back into it after the last, so that
-// for the caller the call still behaves as work enqueued on its own stream.
-template <class F>
-int run_groups(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
-               bool local_scores, unsigned char *ws, size_t slice, hipStream_t user, F &&fn) {
-  const int lanes = lanes_of(p);
-  const long long grows = group_rows_of(p, reqs, nreq);
-  if (lanes <= 1)
-    return for_each_group(p, reqs, nreq, grows, local_scores,
-                          [&](const SegTable &T, long long rows) { return fn(T, rows, user, ws); });
-  LanePool *lp = lane_pool();
-  if (!lp) return COMPACTOR_EHIP;
-  std::lock_guard<std::mutex> lock(lp->mu);
-  HIP_TRY(hipEventRecord(lp->fork, user));
-  for (int i = 0; i < lanes - 1; ++i) HIP_TRY(hipStreamWaitEvent(lp->helper[i], lp->fork, 0));
-  int g = 0;
-  const int rc = for_each_group(p, reqs, nreq, grows, local_scores,
-                                [&](const SegTable &T, long long rows) {
-    const int lane = g++ % lanes;
-    hipStream_t st = lane == 0 ? user : lp->helper[lane - 1];
-    return fn(T, rows, st, ws + (size_t)lane * slice);
+// Argument checks of the fused call (everything but the workspace).
+int check_compress(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                   const int32_t *kept_idx, const int32_t *kept_cnt, const void *k_packed,
+                   const void *v_packed, const int32_t *status) {
+  int rc = check_params(p, true);
+  if (rc) return rc;
+  rc = check_requests(reqs, nreq, NEED_SCORE | NEED_PACK);
+  if (rc) return rc;
+  rc = check_scope(p, reqs, nreq);
+  if (rc) return rc;
+  if (!kept_idx || !kept_cnt || !k_packed || !v_packed || !status) return COMPACTOR_EINVAL;
+  if (!aligned16(k_packed) || !aligned16(v_packed)) return COMPACTOR_EALIGN;
+  return COMPACTOR_OK;
+}
+
+// score -> select -> gather of every head group on `st`, scratch in [workspace, +workspace_bytes).
+int enqueue_compress(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
+                     float *scores, int32_t *kept_idx, int32_t *kept_cnt, void *k_packed,
+                     void *v_packed, int32_t *status, void *workspace, size_t workspace_bytes,
+                     hipStream_t st) {
+  const bool local_scores = scores == nullptr;
+  size_t need;
+  const int rc = workspace_need(p, reqs, nreq, local_scores, &need);
+  if (rc) return rc;
+  if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
+  drop_pending_error();
+  unsigned char *ws = static_cast<unsigned char *>(workspace);
+  return for_each_group(p, reqs, nreq, group_rows_of(p), local_scores,
+                        [&](const SegTable &T, long long rows) {
+    float *sc = scores;
+    const GroupBytes gb = group_bytes_needed(p, T, true);
+    if (local_scores)
+      sc = reinterpret_cast<float *>(ws + gb.partials + gb.g64 + gb.wt + gb.hist1 + gb.sel);
+    const int *hist1 = nullptr;
+    const int rc2 = enqueue_score(p, T, rows, sc, status, ws, st, &hist1);
+    if (rc2) return rc2;
+    const Marks m{p->stage_events, st};
+    if (select_needs_pools(T)) {
+      int *hist_base = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt);
+      int *sel = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt + gb.hist1);
+      HIP_TRY(launch_select_pools(T, sc, hist_base, hist1 != nullptr, sel, true, kept_idx, kept_cnt,
+                                  st));
+    } else {
+      HIP_TRY(launch_select(T, sc, hist1, kept_idx, kept_cnt, st));
+    }
+    MARK(m, COMPACTOR_STAGE_SELECT + 1);
+    HIP_TRY(launch_gather(T, kept_idx, kept_cnt, static_cast<uint16_t *>(k_packed),
+                          static_cast<uint16_t *>(v_packed), st));
+    MARK(m, COMPACTOR_STAGE_GATHER + 1);
+    return (int)COMPACTOR_OK;
   });
-  // join even after a failed enqueue, so that the helpers never outlive the call unobserved
-  for (int i = 0; i < lanes - 1; ++i) {
-    if (hipEventRecord(lp->join[i], lp->helper[i]) != hipSuccess) return COMPACTOR_EHIP;
-    if (hipStreamWaitEvent(user, lp->join[i], 0) != hipSuccess) return COMPACTOR_EHIP;
-  }
-  return rc;
 }
 
 }  // namespace
@@ -373,7 +349,6 @@ void compactor_default_params(compactor_params_t *p, int32_t layers, int32_t kv_
   p->group_bytes = 0;
   p->gram_wgs = 0;
   p->score_tokens = 0;
-  p->streams = 0;
   p->select_scope = COMPACTOR_SCOPE_HEAD;
   p->stage_events = nullptr;
 }
@@ -432,7 +407,7 @@ int compactor_workspace_size(const compactor_params_t *p, const compactor_reques
   rc = check_requests(reqs, nreq, 0);
   if (rc) return rc;
   // sized for the fused call that keeps its scores in the workspace, the largest user
-  return workspace_need(p, reqs, nreq, true, nullptr, bytes);
+  return workspace_need(p, reqs, nreq, true, bytes);
 }
 
 int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
@@ -443,17 +418,18 @@ int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs
   rc = check_requests(reqs, nreq, NEED_SCORE);
   if (rc) return rc;
   if (!scores || !status) return COMPACTOR_EINVAL;
-  size_t need, slice;
-  rc = workspace_need(p, reqs, nreq, false, &slice, &need);
+  size_t need;
+  rc = workspace_need(p, reqs, nreq, false, &need);
   if (rc) return rc;
   if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
   drop_pending_error();
-  return run_groups(p, reqs, nreq, false, static_cast<unsigned char *>(workspace), slice,
-                    static_cast<hipStream_t>(stream),
-                    [&](const SegTable &T, long long rows, hipStream_t st, unsigned char *ws) {
-                      return enqueue_score(p, T, rows, scores, status, ws, st, nullptr);
-                    });
+  unsigned char *ws = static_cast<unsigned char *>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  return for_each_group(p, reqs, nreq, group_rows_of(p), false,
+                        [&](const SegTable &T, long long rows) {
+                          return enqueue_score(p, T, rows, scores, status, ws, st, nullptr);
+                        });
 }
 
 int compactor_select(const compactor_params_t *p, const compactor_request_t *reqs, int32_t nreq,
@@ -467,7 +443,7 @@ int compactor_select(const compactor_params_t *p, const compactor_request_t *req
   if (rc) return rc;
   if (!scores || !kept_idx || !kept_cnt) return COMPACTOR_EINVAL;
   // only a pooled selection (long heads, layer scope) uses the workspace: its histograms
-  const long long grows = group_rows_of(p, reqs, nreq);
+  const long long grows = group_rows_of(p);
   size_t need = 0;
   rc = for_each_group(p, reqs, nreq, grows, false, [&](const SegTable &T, long long) {
     if (select_needs_pools(T)) {
@@ -567,46 +543,10 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
                        float *scores, int32_t *kept_idx, int32_t *kept_cnt, void *k_packed,
                        void *v_packed, int32_t *status, void *workspace, size_t workspace_bytes,
                        void *stream) {
-  int rc = check_params(p, true);
+  const int rc = check_compress(p, reqs, nreq, kept_idx, kept_cnt, k_packed, v_packed, status);
   if (rc) return rc;
-  rc = check_requests(reqs, nreq, NEED_SCORE | NEED_PACK);
-  if (rc) return rc;
-  rc = check_scope(p, reqs, nreq);
-  if (rc) return rc;
-  if (!kept_idx || !kept_cnt || !k_packed || !v_packed || !status) return COMPACTOR_EINVAL;
-  if (!aligned16(k_packed) || !aligned16(v_packed)) return COMPACTOR_EALIGN;
-  const bool local_scores = scores == nullptr;
-  size_t need, slice;
-  rc = workspace_need(p, reqs, nreq, local_scores, &slice, &need);
-  if (rc) return rc;
-  if (!workspace || workspace_bytes < need) return COMPACTOR_EWORKSPACE;
-  if (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)) return COMPACTOR_EALIGN;
-  drop_pending_error();
-  return run_groups(p, reqs, nreq, local_scores, static_cast<unsigned char *>(workspace), slice,
-                    static_cast<hipStream_t>(stream),
-                    [&](const SegTable &T, long long rows, hipStream_t st, unsigned char *ws) {
-    float *sc = scores;
-    const GroupBytes gb = group_bytes_needed(p, T, true);
-    if (local_scores)
-      sc = reinterpret_cast<float *>(ws + gb.partials + gb.g64 + gb.wt + gb.hist1 + gb.sel);
-    const int *hist1 = nullptr;
-    const int rc2 = enqueue_score(p, T, rows, sc, status, ws, st, &hist1);
-    if (rc2) return rc2;
-    const Marks m{p->stage_events, st};
-    if (select_needs_pools(T)) {
-      int *hist_base = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt);
-      int *sel = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt + gb.hist1);
-      HIP_TRY(launch_select_pools(T, sc, hist_base, hist1 != nullptr, sel, true, kept_idx, kept_cnt,
-                                  st));
-    } else {
-      HIP_TRY(launch_select(T, sc, hist1, kept_idx, kept_cnt, st));
-    }
-    MARK(m, COMPACTOR_STAGE_SELECT + 1);
-    HIP_TRY(launch_gather(T, kept_idx, kept_cnt, static_cast<uint16_t *>(k_packed),
-                          static_cast<uint16_t *>(v_packed), st));
-    MARK(m, COMPACTOR_STAGE_GATHER + 1);
-    return (int)COMPACTOR_OK;
-  });
+  return enqueue_compress(p, reqs, nreq, scores, kept_idx, kept_cnt, k_packed, v_packed, status,
+                          workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 double compactor_calibrated_ratio(double nll, double alpha, double beta, double tau) {

@@ -12,12 +12,9 @@ namespace cmp {
 constexpr int D = 128;            // head_dim, the only supported value
 constexpr int MAX_SEG = 24;       // segments (request x head range) per launch
 constexpr int KS_MAX = 128;       // largest factored order (exact mode)
-#ifndef CMP_W_TERMS
-#define CMP_W_TERMS 2
-#endif
-constexpr int W_TERMS = CMP_W_TERMS;  // W^T is carried as a sum of this many bf16 planes:
-                                      // 2 planes keep 16 mantissa bits (measured score error
-                                      // <= 5e-5 relative against a 1e-3 bound), 3 planes all 24
+constexpr int W_TERMS = 2;        // W^T is carried as a sum of this many bf16 planes:
+                                  // 2 planes keep 16 mantissa bits (measured score error
+                                  // <= 5e-5 relative against a 1e-3 bound), 3 planes all 24
 
 // Launch-time tile sizes.
 constexpr int GRAM_PARTIAL_FLOATS = 10 * 32 * 32;   // upper blocks of one partial Gram matrix

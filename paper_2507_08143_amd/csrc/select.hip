@@ -259,10 +259,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T
 // The chunk kernels are held to 64 registers so that two 1024-thread workgroups share a CU.
 // Four launches: hist2, hist3, scan, emit.  Each finds one digit of the threshold (every
 // workgroup of a pool for itself, from a few KB in L2) and passes it on in the pool's state.
-#ifndef CMP_SEL_CHUNK
-#define CMP_SEL_CHUNK 32768
-#endif
-constexpr int SEL_CHUNK = CMP_SEL_CHUNK;   // tokens per workgroup (chunks never cross heads)
+constexpr int SEL_CHUNK = 32768;         // tokens per workgroup (chunks never cross heads)
 constexpr int SEL_ROUNDS = SEL_CHUNK / (4 * SELECT_THREADS);   // 4-token groups per thread
 constexpr int SEL_REC = 260;             // ints per chunk record: [0] keys above the 24-bit
                                          // prefix, [4 + b] keys equal to it with low byte b

@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(B):
 def test_struct_layouts_match_the_header(B):
     # sizes the C compiler gives for the two structs of the header (x86-64 ABI)
     assert C.sizeof(B._Request) == 4 * 8 + 3 * 8 + 4 + 4
-    assert C.sizeof(B._Params) == 4 * 4 + 8 + 4 + 4 + 8 + 4 + 4 + 4 + 4 + 8
+    assert C.sizeof(B._Params) == 4 * 4 + 8 + 4 + 4 + 8 + 4 + 4 + 4 + 4 + 8   # incl. 4 bytes of padding
 
 
 def test_keep_count_matches_oracle(B):
@@ -49,6 +49,31 @@ def test_keep_count_matches_oracle(B):
         n = int(rng.integers(1, 200000))
         r = float(np.float32(rng.uniform(1e-4, 1.0)))
         assert B.compactor_keep_count(n, r) == O.keep_count(n, r)
+
+
+def test_keep_count_against_the_plain_ceiling(B):
+    """k = ceil(r N) of the paper's overview, with r the float32 that crosses the boundary: the
+    library (and the oracle) shrink the product by 2^-23 before the ceiling.  Decimal ratios whose
+    product is an integer on paper then give that integer; for arbitrary float ratios the count is
+    the plain ceiling except where the product lies within r N 2^-23 above an integer, and then it
+    is one less."""
+    import math
+    for n, r, want in [(1000, 0.001, 1), (1000, 0.3, 300), (50, 0.1, 5), (10000000, 0.1, 1000000),
+                       (32768, 0.3, 9831), (49907, 0.39685819, 19806)]:
+        assert B.compactor_keep_count(n, r) == want
+    rng = np.random.default_rng(3)
+    less = 0
+    for _ in range(20000):
+        n = int(rng.integers(8192, 65537))
+        r = float(np.float32(rng.uniform(0.2, 0.6)))
+        x = r * n
+        plain = max(1, min(n, math.ceil(x)))
+        got = B.compactor_keep_count(n, r)
+        assert got in (plain, plain - 1)
+        if got != plain:
+            assert x - math.floor(x) <= x * 2.0 ** -23
+            less += 1
+    assert less <= 100          # about 0.2 % of arbitrary pairs
 
 
 def test_calibrated_ratio_matches_oracle(B):
@@ -63,7 +88,7 @@ def _req(B, n=100, ratio=0.5, ptr=0x1000, stride_t=128):
 
 
 def test_layout_offsets(B):
-    p = B._Params(3, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, 0, None)
+    p = B._Params(3, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, None)
     reqs = (B._Request * 3)(_req(B, 100, 0.5), _req(B, 7, 1.0), _req(B, 1000, 0.25))
     so, ko, kk = (C.c_int64 * 4)(), (C.c_int64 * 4)(), (C.c_int32 * 3)()
     assert B._lib.compactor_layout(C.byref(p), reqs, 3, so, ko, kk) == 0
@@ -73,7 +98,7 @@ def test_layout_offsets(B):
 
 
 def test_argument_errors_are_reported_on_the_host(B):
-    good = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 0, None)
+    good = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, None)
     reqs = (B._Request * 1)(_req(B))
     nbytes = C.c_size_t(0)
     assert B._lib.compactor_workspace_size(C.byref(good), reqs, 1, C.byref(nbytes)) == 0
@@ -82,15 +107,15 @@ def test_argument_errors_are_reported_on_the_host(B):
     def score(p, r, scores=0x3000, status=0x4000, ws=0x10000, wsb=1 << 40):
         return B._lib.compactor_score(C.byref(p), r, 1, scores, status, ws, wsb, None)
 
-    bad_dim = B._Params(2, 2, 64, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 0, None)
+    bad_dim = B._Params(2, 2, 64, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, None)
     assert score(bad_dim, reqs) == B.EUNSUPPORTED
-    bad_ks = B._Params(2, 2, 128, 40, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 0, None)
+    bad_ks = B._Params(2, 2, 128, 40, 0x2000, 0.0, 0.3, 0, 0, 0, 0, None)
     assert score(bad_ks, reqs) == B.EUNSUPPORTED
-    no_phi = B._Params(2, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, 0, None)
+    no_phi = B._Params(2, 2, 128, 48, 0, 0.0, 0.3, 0, 0, 0, 0, None)
     assert score(no_phi, reqs) == B.EINVAL
-    bad_scope = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 7, None)
+    bad_scope = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 7, None)
     assert score(bad_scope, reqs) == B.EINVAL
-    neg_ridge = B._Params(2, 2, 128, 48, 0x2000, -1.0, 0.3, 0, 0, 0, 0, 0, None)
+    neg_ridge = B._Params(2, 2, 128, 48, 0x2000, -1.0, 0.3, 0, 0, 0, 0, None)
     assert score(neg_ridge, reqs) == B.EINVAL
     assert score(good, (B._Request * 1)(_req(B, ratio=0.0))) == B.EINVAL
     assert score(good, (B._Request * 1)(_req(B, ratio=1.5))) == B.EINVAL
@@ -112,7 +137,7 @@ def test_argument_errors_are_reported_on_the_host(B):
 
 
 def test_widened_entry_points_check_their_arguments_on_the_host(B):
-    good = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 0, None)
+    good = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, None)
     reqs = (B._Request * 1)(_req(B, n=100, ratio=0.5))
 
     # paged compaction: the pool's geometry and the length of each page table
@@ -135,7 +160,7 @@ def test_widened_entry_points_check_their_arguments_on_the_host(B):
     assert paged(pool(k=0x100008), 4) == B.EALIGN
     assert paged(pool(head_stride=132), 4) == B.EALIGN
     assert paged(pool(), 4, kept_idx=0) == B.EINVAL
-    layer = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 0, 1, None)
+    layer = B._Params(2, 2, 128, 48, 0x2000, 0.0, 0.3, 0, 0, 0, 1, None)
     tabs = (B._PageTable * 1)(B._PageTable(0x7000, 4))       # a head may take 2 * 50 rows: 7 pages
     assert B._lib.compactor_compact_paged(C.byref(layer), reqs, 1, 0x3000, 0x4000, C.byref(pool()),
                                           tabs, 0, None) == B.EINVAL
@@ -191,7 +216,7 @@ def test_widened_entry_points_check_their_arguments_on_the_host(B):
 def test_default_params(B):
     p = B.compactor_default_params(32, 8)
     assert (p.layers, p.kv_heads, p.head_dim, p.sketch_dim) == (32, 8, 128, 48)
-    assert abs(p.lambda_blend - 0.3) < 1e-7 and p.ridge_rel == 0.0 and p.streams == 0
+    assert abs(p.lambda_blend - 0.3) < 1e-7 and p.ridge_rel == 0.0 and p.group_bytes == 0
 
 
 def test_binding_checks_what_the_pointers_cannot_say(B):

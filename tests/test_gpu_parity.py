@@ -331,7 +331,7 @@ def test_separate_calls_equal_fused_call(C):
     torch.cuda.synchronize()
     assert torch.equal(fused["scores"].view(torch.int32), again["scores"].view(torch.int32))
     assert torch.equal(fused["kept_idx"], again["kept_idx"])
-    # head groups (one launch sequence per group) and helper-stream lanes
+    # head groups (one launch sequence per group)
     params_g, _ = U.make_call(C, w, DEV, group_bytes=2 * 1024 * 1024)
     grouped = C.compactor_compress(params_g, reqs, want_scores=True)
     grouped_nosc = C.compactor_compress(params_g, reqs, want_scores=False)
@@ -339,13 +339,6 @@ def test_separate_calls_equal_fused_call(C):
     _same_up_to_rounding(C, w, params, reqs, fused, grouped, "grouped")
     assert torch.equal(grouped["kept_idx"], grouped_nosc["kept_idx"])
     assert torch.equal(grouped["k_packed"].view(torch.int16), grouped_nosc["k_packed"].view(torch.int16))
-    for lanes in (2, 4):
-        params_s, _ = U.make_call(C, w, DEV)
-        params_s.streams = lanes
-        multi = C.compactor_compress(params_s, reqs, want_scores=True)
-        torch.cuda.synchronize()
-        _same_up_to_rounding(C, w, params, reqs, fused, multi, "%d lanes" % lanes)
-        assert torch.equal(fused["status"], multi["status"])
 
 
 def test_degenerate_inputs_are_flagged_not_fatal(C):
@@ -753,15 +746,13 @@ def test_pooled_select_edges_and_regrouping(C):
     w = W.config2(DEV, L=3, H=4, n=2000)
     params, reqs = U.make_call(C, w, DEV, group_bytes=4 * 2000 * 256)
     params.select_scope = C.SCOPE_LAYER
-    for streams in (0, 2):
-        params.streams = streams
-        out = C.compactor_compress(params, reqs, want_scores=True)
-        torch.cuda.synchronize()
-        so, ko, kk = C.compactor_layout(params, reqs)
-        _check_layer_selection(C, out["scores"].cpu().numpy(), out["kept_idx"].cpu().numpy(),
-                               out["kept_cnt"].cpu().numpy(), ko[0], kk[0], 0, 3, 4, 2000,
-                               "grouped layer scope, streams=%d" % streams)
-        assert int(out["status"].max()) == 0
+    out = C.compactor_compress(params, reqs, want_scores=True)
+    torch.cuda.synchronize()
+    so, ko, kk = C.compactor_layout(params, reqs)
+    _check_layer_selection(C, out["scores"].cpu().numpy(), out["kept_idx"].cpu().numpy(),
+                           out["kept_cnt"].cpu().numpy(), ko[0], kk[0], 0, 3, 4, 2000,
+                           "grouped layer scope")
+    assert int(out["status"].max()) == 0
 
 
 def test_sketched_scores_with_a_ridge(C):
