@@ -33,7 +33,8 @@
  *     the outputs untouched.  Numerical trouble inside a head never aborts: it
  *     is reported in that head's status word (see COMPACTOR_STATUS_*).
  *   - Thread safety: concurrent calls are safe when they use distinct workspaces
- *     and output buffers; the library keeps no state between calls.
+ *     and output buffers; the library keeps no state between calls (but see
+ *     compactor_compress_static, whose scratch is shared per GPU).
  */
 #ifndef COMPACTOR_H
 #define COMPACTOR_H
@@ -48,7 +49,8 @@ extern "C" {
 #define COMPACTOR_OK                   0
 #define COMPACTOR_EINVAL             (-1)  /* null pointer, n <= 0, ratio outside (0,1], ... */
 #define COMPACTOR_EUNSUPPORTED       (-2)  /* head_dim != 128, sketch_dim not in {0,16,32,48,64} */
-#define COMPACTOR_EWORKSPACE         (-3)  /* workspace pointer null or too small */
+#define COMPACTOR_EWORKSPACE         (-3)  /* workspace pointer null or too small; or the batch needs
+                                              more scratch than compactor_compress_static has */
 #define COMPACTOR_EALIGN             (-4)  /* a pointer or a row stride is not 16-byte aligned */
 #define COMPACTOR_EHIP               (-5)  /* a HIP runtime call of the library failed (launch error);
                                               an error that earlier HIP calls of the caller left
@@ -247,6 +249,25 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
                        float *scores, int32_t *kept_idx, int32_t *kept_cnt,
                        void *k_packed, void *v_packed, int32_t *status,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* compactor_compress without a workspace argument, for callers that cannot allocate device memory
+ * or obtain a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The scratch that compactor_compress takes as `workspace` lives in a buffer of
+ * COMPACTOR_STATIC_SCRATCH_BYTES that is part of the library's device image: every GPU the
+ * library runs on holds its own copy from the first use until the process ends.  The call
+ * allocates and frees nothing (no hipMalloc, no hipFree, no allocating library routine); inputs
+ * and outputs are the caller's, as in compactor_compress, and the results are the same bits.
+ * A batch whose scratch (compactor_workspace_size; pass scores != NULL to keep the scores out of
+ * it) exceeds COMPACTOR_STATIC_SCRATCH_BYTES is refused with COMPACTOR_EWORKSPACE before anything
+ * is enqueued; params.group_bytes bounds the scratch of a large batch.  All calls on one GPU share
+ * that GPU's buffer: calls that overlap in time on one GPU (two streams, two threads) race on it
+ * and must be serialised by the caller.  The buffer keeps the last call's contents; whatever has
+ * to start at zero is cleared by the call's own kernels.  The first call on a device looks the
+ * buffer's address up (no stream work): make it outside a graph capture. */
+#define COMPACTOR_STATIC_SCRATCH_BYTES (64u << 20)
+int compactor_compress_static(const compactor_params_t *p, const compactor_request_t *reqs,
+                              int32_t nreq, float *scores, int32_t *kept_idx, int32_t *kept_cnt,
+                              void *k_packed, void *v_packed, int32_t *status, void *stream);
 
 /* ---- attention-based scores (Sec. 3.2, "Attention-Based Scoring") ------------------------- */
 

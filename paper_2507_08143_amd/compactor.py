@@ -92,6 +92,8 @@ _lib.compactor_compact_paged.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_vo
 _lib.compactor_compress.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                     C.c_void_p]
+_lib.compactor_compress_static.argtypes = [_PP, _RP, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.compactor_calibrated_ratio.argtypes = [C.c_double] * 4
 _lib.compactor_calibrated_ratio.restype = C.c_double
 _lib.compactor_error_string.argtypes = [C.c_int]
@@ -100,7 +102,8 @@ _lib.compactor_version.restype = C.c_char_p
 
 EXPORTS = ["compactor_default_params", "compactor_keep_count", "compactor_layout",
            "compactor_workspace_size", "compactor_srht_phi", "compactor_score", "compactor_select",
-           "compactor_compact", "compactor_compact_paged", "compactor_compress", "compactor_calibrated_ratio",
+           "compactor_compact", "compactor_compact_paged", "compactor_compress", "compactor_compress_static",
+           "compactor_calibrated_ratio",
            "compactor_error_string", "compactor_version",
            "compactor_attention_workspace_size", "compactor_attention_scores"]
 
@@ -445,6 +448,30 @@ def compactor_compress(params: Params, reqs: Sequence[Request], want_scores: boo
                                    workspace.numel(), _stream(stream)))
     return {"scores": scores, "kept_idx": kept_idx, "kept_cnt": kept_cnt, "k_packed": k_packed,
             "v_packed": v_packed, "status": status, "workspace": workspace}
+
+
+STATIC_SCRATCH_BYTES = 64 << 20      # COMPACTOR_STATIC_SCRATCH_BYTES of the header
+
+
+def compactor_compress_static(params: Params, reqs: Sequence[Request], scores, kept_idx, kept_cnt,
+                              k_packed, v_packed, status, stream=None):
+    """compactor_compress on the library's own static scratch: every buffer is the caller's (none
+    is allocated here, `scores` may be None) and no workspace is passed."""
+    so, ko, _ = compactor_layout(params, reqs)
+    nh = len(reqs) * params.layers * params.kv_heads
+    pp, arr, n = _marshal(params, reqs)
+    _out(scores, so[-1], torch.float32, "scores")
+    for t, name in ((kept_idx, "kept_idx"), (kept_cnt, "kept_cnt"), (k_packed, "k_packed"),
+                    (v_packed, "v_packed"), (status, "status")):
+        _require(t is not None, "%s must be supplied" % name)
+    _out(kept_idx, ko[-1], torch.int32, "kept_idx")
+    _out(kept_cnt, nh, torch.int32, "kept_cnt")
+    _out(k_packed, ko[-1] * params.head_dim, torch.bfloat16, "k_packed")
+    _out(v_packed, ko[-1] * params.head_dim, torch.bfloat16, "v_packed")
+    _out(status, nh, torch.int32, "status")
+    _check(_lib.compactor_compress_static(pp, arr, n, _ptr(scores), _ptr(kept_idx), _ptr(kept_cnt),
+                                          _ptr(k_packed), _ptr(v_packed), _ptr(status),
+                                          _stream(stream)))
 
 
 @dataclass

@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "common.h"
 
 using namespace cmp;
@@ -274,6 +276,31 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   MARK(m, COMPACTOR_STAGE_SCORE + 1);
   HIP_TRY(launch_blend(T, p->lambda_blend, scores, st));
   MARK(m, COMPACTOR_STAGE_BLEND + 1);
+  return COMPACTOR_OK;
+}
+
+// Scratch of compactor_compress_static: part of the device image, one copy per GPU.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the device address it yields
+// (per device) is what kernels, and everything else that touches the memory, are given.
+constexpr size_t STATIC_SCRATCH_BYTES = COMPACTOR_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[MAX_DEVICES];      // device address of `scratch` on each GPU, once looked up
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+int static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return COMPACTOR_EHIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr)
+      return COMPACTOR_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
   return COMPACTOR_OK;
 }
 
@@ -549,6 +576,23 @@ int compactor_compress(const compactor_params_t *p, const compactor_request_t *r
                           workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
+int compactor_compress_static(const compactor_params_t *p, const compactor_request_t *reqs,
+                              int32_t nreq, float *scores, int32_t *kept_idx, int32_t *kept_cnt,
+                              void *k_packed, void *v_packed, int32_t *status, void *stream) {
+  int rc = check_compress(p, reqs, nreq, kept_idx, kept_cnt, k_packed, v_packed, status);
+  if (rc) return rc;
+  size_t need;
+  rc = workspace_need(p, reqs, nreq, scores == nullptr, &need);
+  if (rc) return rc;
+  if (need > STATIC_SCRATCH_BYTES) return COMPACTOR_EWORKSPACE;
+  drop_pending_error();
+  void *ptr = nullptr;
+  rc = static_scratch(&ptr);
+  if (rc) return rc;
+  return enqueue_compress(p, reqs, nreq, scores, kept_idx, kept_cnt, k_packed, v_packed, status,
+                          ptr, STATIC_SCRATCH_BYTES, static_cast<hipStream_t>(stream));
+}
+
 double compactor_calibrated_ratio(double nll, double alpha, double beta, double tau) {
   const double b = alpha * nll + beta;
   double r = (b == 0.0) ? tau : 1.0 + log(tau * (1.0 - exp(-b)) + exp(-b)) / b;
@@ -562,7 +606,7 @@ const char *compactor_error_string(int code) {
     case COMPACTOR_OK: return "ok";
     case COMPACTOR_EINVAL: return "invalid argument";
     case COMPACTOR_EUNSUPPORTED: return "unsupported shape (head_dim must be 128; sketch_dim 0, 16, 32, 48 or 64)";
-    case COMPACTOR_EWORKSPACE: return "workspace missing or too small";
+    case COMPACTOR_EWORKSPACE: return "workspace missing or too small (or the batch needs more than the static scratch)";
     case COMPACTOR_EALIGN: return "pointer or stride not 16-byte aligned";
     case COMPACTOR_EHIP: return "HIP runtime error";
     default: return "unknown error";
