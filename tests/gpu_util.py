@@ -48,21 +48,42 @@ def check_scores(got: np.ndarray, want: np.ndarray, what=""):
     return float(np.max(err / np.maximum(np.abs(want), 1e-12)))
 
 
+def blend_bound(o: np.ndarray, lam: float) -> np.ndarray:
+    """How far the blended score s = z(a) + lam z(o) may move when every o_i moves by at most
+    eps_i = RTOL o_i + ATOL (a is the same on both sides).  With mu, sd the mean and population
+    standard deviation of o: the mean moves by at most mean(eps) <= RTOL mu + ATOL; sd is the
+    root-mean-square of o - mu, so it moves by at most the root-mean-square of the perturbation,
+    <= RTOL sqrt(sd^2 + mu^2) + ATOL; hence
+      |dz_i| <= (eps_i + mean eps) / sd + |z_i| dsd / sd
+             <= RTOL [ (o_i + mu) / sd + |z_i| sqrt(1 + (mu/sd)^2) ] + ATOL (2 + |z_i|) / sd,
+    to first order.  1e-5 is added for the fp32 rounding of s itself (|s| stays below ~50)."""
+    mu, sd = float(o.mean()), float(o.std())
+    z = (o - mu) / sd
+    return lam * (RTOL * ((o + mu) / sd + np.abs(z) * np.sqrt(1.0 + (mu / sd) ** 2)) +
+                  ATOL * (2.0 + np.abs(z)) / sd) + 1e-5
+
+
 def check_kept(got_kept: np.ndarray, want_kept: np.ndarray, want_scores: np.ndarray, what="",
-               tol_scale=1.0):
+               tol_scale=1.0, bound=None):
     """Kept sets must agree except for swaps among tokens whose oracle score lies within the
-    score tolerance of the oracle's threshold score.  Returns the number of swapped tokens."""
+    score tolerance of the oracle's threshold score: |s_i - thr| <= tol_i + tol_thr, where tol is
+    RTOL |s| + ATOL for leverage scores, or `bound` (per token) when given.  Returns the number of
+    swapped tokens."""
     assert got_kept.dtype == np.int32 and len(got_kept) == len(want_kept), what
     assert np.all(np.diff(got_kept) > 0), what + ": kept indices not strictly ascending"
     if np.array_equal(got_kept, want_kept):
         return 0
     diff = np.setxor1d(got_kept, want_kept)
-    thr = np.min(want_scores[want_kept])
+    ithr = want_kept[np.argmin(want_scores[want_kept])]
+    thr = want_scores[ithr]
     gap = np.abs(want_scores[diff] - thr)
-    allow = 2.0 * tol_scale * (RTOL * abs(thr) + ATOL)
+    if bound is None:
+        allow = 2.0 * tol_scale * (RTOL * abs(thr) + ATOL)
+    else:
+        allow = tol_scale * (bound[diff] + bound[ithr])
     assert np.all(gap <= allow), (
         "%s: %d kept tokens differ, largest oracle score gap to the threshold %.3g > %.3g" %
-        (what, len(diff), gap.max(), allow))
+        (what, len(diff), gap.max(), float(np.max(allow))))
     return len(diff)
 
 
@@ -110,9 +131,20 @@ def run_and_check(C, w: W.Workload, device, heads=None, group_bytes=0, kept_tol_
         s_gpu = scores[so[b] + g * n: so[b] + (g + 1) * n]
         i_gpu = kept[ko[b] + g * k: ko[b] + (g + 1) * k]
         s_ref, i_ref, kp_ref, vp_ref = oracle_head(w, b, l, h, phi_np)
-        if w.requests[b].attn is None:      # blended scores are z-scores: checked by their own test
+        bound = None
+        if w.requests[b].attn is None:
             stats["max_rel"] = max(stats["max_rel"], check_scores(s_gpu, s_ref, what))
-        stats["swaps"] += check_kept(i_gpu, i_ref, s_ref, what, kept_tol_scale)
+        else:      # blended scores are z-scores: the error of o, carried through the blend
+            K = O.bf16_bits_to_f64(W.bf16_bits(w.requests[b].k[l, h]))
+            o = (O.approx_leverage_ridge(K, phi_np, w.ridge_rel) if w.sketch_dim > 0
+                 else O.leverage_ridge_exact(K, w.ridge_rel))
+            bound = blend_bound(o, W.LAMBDA_BLEND)
+            err = np.abs(s_gpu.astype(np.float64) - s_ref)
+            assert np.all(err <= bound), "%s: blended score off by %.3g (bound %.3g)" % (
+                what, float(err.max()), float(bound[np.argmax(err - bound)]))
+            stats["max_blend_err_over_bound"] = max(stats.get("max_blend_err_over_bound", 0.0),
+                                                    float(np.max(err / bound)))
+        stats["swaps"] += check_kept(i_gpu, i_ref, s_ref, what, kept_tol_scale, bound)
         check_selection_valid(s_gpu, i_gpu, k, what)
         rows = slice(ko[b] + g * k, ko[b] + (g + 1) * k)
         kp = out["k_packed"][rows].view(torch.int16).cpu().numpy().view(np.uint16)

@@ -280,12 +280,49 @@ def test_blend_with_attention_scores(C):
         a = w.requests[0].attn[0, h].double().cpu().numpy()
         o = O.approx_leverage_ridge(K, phi)
         want = O.blend_scores(a, o, W.LAMBDA_BLEND)
-        mu, sd = o.mean(), o.std()
-        zo = (o - mu) / sd
-        bound = 1e-3 * W.LAMBDA_BLEND * ((o + mu) / sd + np.abs(zo) * (1 + (mu / sd) ** 2)) + 1e-5
-        assert np.all(np.abs(s[h * 4100:(h + 1) * 4100] - want) <= bound)
-    # and the fused path selects on the blended score
-    st, _ = U.run_and_check(C, w, DEV, kept_tol_scale=50.0)
+        assert np.all(np.abs(s[h * 4100:(h + 1) * 4100] - want) <= U.blend_bound(o, W.LAMBDA_BLEND))
+    # and the fused path selects on the blended score: kept sets may differ from the oracle's only
+    # between tokens whose blended scores are within the propagated score tolerance of the threshold
+    st, _ = U.run_and_check(C, w, DEV)
+    _say("  fused: blended score error at most %.3g of its bound, swaps %d" % (st["max_blend_err_over_bound"], st["swaps"]))
+
+
+def test_blend_with_selection_by_several_workgroups(C):
+    """Eq. "scoring" followed by the pooled selection paths: the blend rewrites the scores, so the
+    score kernel's first histogram cannot be used and the selection tallies its own."""
+    _say("blend + heads longer than one selection workgroup (n = 40000, 65537)")
+    for n in (40000, 65537):
+        w = W.config2(device=DEV, L=1, H=2, n=n)
+        w.requests[0].attn = W.synthetic_attention_scores(1, 2, n, device=DEV, seed=n)
+        st, out = U.run_and_check(C, w, DEV)
+        _say("  n=%d: blended score error at most %.3g of its bound, swaps %d" % (n, st["max_blend_err_over_bound"], st["swaps"]))
+        # exact on the library's own scores, ties included
+        s = out["scores"].cpu().numpy()
+        k = C.compactor_keep_count(n, w.requests[0].ratio)
+        kept = out["kept_idx"].cpu().numpy()
+        for h in range(2):
+            assert np.array_equal(kept[h * k:(h + 1) * k], O.select_topk(s[h * n:(h + 1) * n], k))
+    _say("blend + head-adaptive selection across the heads of a layer, ragged batch")
+    w = W.config4(DEV, L=2, H=3, n_req=3, n_lo=500, n_hi=40000)
+    for b, r in enumerate(w.requests):
+        r.attn = W.synthetic_attention_scores(2, 3, r.n, device=DEV, seed=50 + b)
+    params, reqs = U.make_call(C, w, DEV)
+    params.select_scope = C.SCOPE_LAYER
+    out = C.compactor_compress(params, reqs, want_scores=True)
+    torch.cuda.synchronize()
+    assert int(out["status"].max()) == 0
+    so, ko, kk = C.compactor_layout(params, reqs)
+    scores, kept, cnt = out["scores"].cpu().numpy(), out["kept_idx"].cpu().numpy(), out["kept_cnt"].cpu().numpy()
+    phi_np = params.phi.double().cpu().numpy()
+    for b, r in enumerate(w.requests):
+        sb = scores[so[b]:so[b + 1]]
+        _check_layer_selection(C, sb, kept, cnt, ko[b], kk[b], b, 2, 3, r.n, "blend, layer scope, req %d" % b)
+        for g in range(6):          # the blended scores themselves, against the oracle
+            l, h = divmod(g, 3)
+            K = O.bf16_bits_to_f64(W.bf16_bits(r.k[l, h]))
+            o = O.approx_leverage_ridge(K, phi_np)
+            want = O.blend_scores(r.attn[l, h].double().cpu().numpy(), o, W.LAMBDA_BLEND)
+            assert np.all(np.abs(sb[g * r.n:(g + 1) * r.n] - want) <= U.blend_bound(o, W.LAMBDA_BLEND))
 
 
 def _same_up_to_rounding(C, w, params, reqs, ref, other, what):
@@ -393,12 +430,24 @@ def test_a_pending_hip_error_of_the_caller_is_not_reported(C):
 
 # ------------------------------------------------------------------ full sizes (sampled heads)
 def _sample_heads(w, per_request=4, seed=11):
+    """Random heads of every request, plus the first head of the first request and the last head
+    of the last one (lowest and highest addresses of the batch)."""
     rng = np.random.default_rng(seed)
+    LH = w.layers * w.kv_heads
     heads = []
     for b in range(len(w.requests)):
-        picks = rng.choice(w.layers * w.kv_heads, size=min(per_request, w.layers * w.kv_heads), replace=False)
+        picks = rng.choice(LH, size=min(per_request, LH), replace=False)
         heads += [(b, int(g) // w.kv_heads, int(g) % w.kv_heads) for g in picks]
+    for extra in ((0, 0, 0), (len(w.requests) - 1, w.layers - 1, w.kv_heads - 1)):
+        if extra not in heads:
+            heads.append(extra)
     return heads
+
+
+def _release(*objs):
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
 
 
 def _structure_checks(C, w, out):
@@ -432,8 +481,10 @@ def test_config2_full_size_as_benchmarked(C):
     _say("config 2 at full size (32 x 8 heads, n = 32768), the launch configuration bench.py times")
     w = W.config2(device=DEV)
     st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 6))
-    _say("  %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
+    _say("  FULL-SIZE config2 sketched: %d sampled heads, max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
     _structure_checks(C, w, out)
+    del w, out
+    _release()
 
 
 def test_config2_full_size_layer_scope(C):
@@ -477,32 +528,42 @@ def test_config2_full_size_layer_scope(C):
     _say("  per-head counts of layer 3: %s (uniform would be %d)" % (kc[3 * H:4 * H].tolist(), k))
 
 
-def test_config3_full_length(C):
-    _say("config 3 at full length (n = 131072), 4 of 28 layers")
-    w = W.config3(device=DEV, L=4)
+def test_config3_full_size(C):
+    _say("config 3 at full size (28 x 4 heads, n = 131072): 7.5 GB of keys and values")
+    w = W.config3(device=DEV)
     st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 3))
-    _say("  %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
+    _say("  FULL-SIZE config3 sketched: %d sampled heads, max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
     _structure_checks(C, w, out)
+    del w, out
+    _release()
 
 
-def test_config5_full_length_sketched_and_exact(C):
-    _say("config 5 at full length (n = 100000), 2 of 64 layers")
-    w = W.config5(device=DEV, L=2)
+def test_config5_full_size_sketched_and_exact(C):
+    _say("config 5 at full size (64 x 8 heads, n = 100000): 26 GB of keys and values, row offsets past 2^31 elements")
+    w = W.config5(device=DEV)
+    assert w.requests[0].k.numel() > 2 ** 32
     st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 3))
-    _say("  sketched, %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
+    _say("  FULL-SIZE config5 sketched: %d sampled heads, max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
     _structure_checks(C, w, out)
+    del out
+    _release()
     w.sketch_dim, w.ridge_rel = 0, 1e-4
     st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 2))
-    _say("  exact ridge 1e-4, %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
+    _say("  FULL-SIZE config5 exact ridge 1e-4: %d sampled heads, max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
     _structure_checks(C, w, out)
+    del w, out
+    _release()
 
 
-def test_config4_ragged_batch_full_lengths(C):
-    _say("config 4: 16 requests with n in [8192, 65536], 2 of 32 layers")
-    w = W.config4(device=DEV, L=2)
+def test_config4_full_size_ragged_batch(C):
+    _say("config 4 at full size: 16 requests, n in [8192, 65536], 32 x 8 heads each, one fused call")
+    w = W.config4(device=DEV)
+    _say("  tokens %d, head-rows %d (%.1f GB of keys and values)" % (w.tokens, w.head_rows, w.head_rows * 512 / 1e9))
     st, out = U.run_and_check(C, w, DEV, heads=_sample_heads(w, 1))
-    _say("  %d sampled heads: max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
+    _say("  FULL-SIZE config4 sketched: %d sampled heads, max rel err %.3g, swaps %d" % (st["heads"], st["max_rel"], st["swaps"]))
     _structure_checks(C, w, out)
+    del w, out
+    _release()
 
 
 # ------------------------------------------------------------------ attention scores (Sec. 3.2)
@@ -544,7 +605,7 @@ def test_attention_scores_low_rank_keys_and_blend_end_to_end(C):
     worst, w, q, a = _attention_case(C, L, H, G, n, W.config2)
     _say("  attention max rel err %.3g" % worst)
     w.requests[0].attn = torch.from_numpy(a).to(DEV).contiguous()
-    st, _ = U.run_and_check(C, w, DEV, kept_tol_scale=50.0)
+    st, _ = U.run_and_check(C, w, DEV)
     _say("  fused compress with blended scores: swaps %d" % st["swaps"])
 
 

@@ -224,18 +224,45 @@ def test_duplicates_and_row_permutation():
 
 # ---------------------------------------------------------------- P9 select / compact
 def _brute_topk(s, k):
-    """Repeatedly take the largest remaining score, lowest index among equals."""
-    s = [(-math.inf if (x != x) else float(np.float32(x))) for x in s]
+    """Repeatedly take the best remaining score: a number beats a NaN, a larger number beats a
+    smaller one (float32 comparison, -0.0 = +0.0), the lowest index wins among equals."""
+    s = [float(np.float32(x)) for x in s]
+
+    def better(i, j):                     # is token i strictly better than token j?
+        if s[i] != s[i] or s[j] != s[j]:
+            return s[i] == s[i] and s[j] != s[j]
+        return s[i] > s[j]
     left = list(range(len(s)))
     out = []
     for _ in range(k):
         best = left[0]
         for i in left[1:]:
-            if s[i] > s[best]:
+            if better(i, best):
                 best = i
         out.append(best)
         left.remove(best)
     return sorted(out)
+
+
+def test_select_ranks_nan_below_minus_infinity():
+    """Sec. 3.3 says nothing about scores that are not numbers (they arise only from non-finite
+    keys).  Reading: every number, -inf included, outranks a NaN; NaNs among themselves go by
+    lower index.  Hand-written expectations for one head holding both."""
+    inf, nan = math.inf, math.nan
+    s = np.array([nan, -inf, 0.5, nan, -inf, inf, -1.0])
+    assert O.select_topk(s, 1).tolist() == [5]
+    assert O.select_topk(s, 3).tolist() == [2, 5, 6]
+    assert O.select_topk(s, 4).tolist() == [1, 2, 5, 6]          # first -inf before any NaN
+    assert O.select_topk(s, 5).tolist() == [1, 2, 4, 5, 6]       # second -inf, still no NaN
+    assert O.select_topk(s, 6).tolist() == [0, 1, 2, 4, 5, 6]    # NaNs last, lower index first
+    for k in range(1, 8):
+        assert O.select_topk(s, k).tolist() == _brute_topk(s, k)
+    # the same rule across the heads of a layer
+    S = np.array([[nan, -inf, 1.0], [-inf, nan, 2.0]])
+    got = O.select_topk_layer(S, 4)
+    assert [g.tolist() for g in got] == [[1, 2], [0, 2]]
+    got = O.select_topk_layer(S, 5)
+    assert [g.tolist() for g in got] == [[0, 1, 2], [0, 2]]
 
 
 @pytest.mark.parametrize("seed", range(6))
@@ -245,6 +272,9 @@ def test_select_matches_brute_force(seed):
     s = r.integers(-3, 4, n).astype(np.float64) / 4.0       # many exact ties, both signs, zeros
     if seed == 3:
         s[r.integers(0, n)] = np.nan
+    if seed == 5:                                           # NaN and -inf in one head
+        s[r.integers(0, n, 3)] = np.nan
+        s[r.integers(0, n, 3)] = -np.inf
     if seed == 4:
         s = np.where(s == 0, -0.0, s)                       # -0.0 ties with +0.0
     for k in {1, max(1, n // 3), n}:
