@@ -20,12 +20,15 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 # HBM bytes per launch measured with rocprofv3 (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
-# scale factors read off a 1 GiB copy kernel): profiles/compress_config2_hbm_traffic.txt.
-# Only the default workload has been profiled; other workloads report null.
+# scale factors read off a 1 GiB copy kernel), by (workload, mode, kernel):
+# profiles/compress_config*_hbm_traffic.txt.  Workloads that have not been profiled report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("config2_llama31_8b_n32768", "gather"): 2.607e9,
-    ("config2_llama31_8b_n32768", "gram"): 2.169e9,
-    ("config2_llama31_8b_n32768", "score"): 2.232e9,
+    ("config2_llama31_8b_n32768", "sketched", "gather"): 2.607e9,
+    ("config2_llama31_8b_n32768", "sketched", "gram"): 2.169e9,
+    ("config2_llama31_8b_n32768", "sketched", "score"): 2.232e9,
+    ("config4_ragged_batch", "sketched", "gather"): 6.558e10,
+    ("config4_ragged_batch", "sketched", "gram"): 4.335e10,
+    ("config4_ragged_batch", "sketched", "score"): 4.456e10,
 }
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
@@ -36,7 +39,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=int(os.environ.get("WORLD_SIZE", "1")))
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 5],
+                    help="headline workload (default: config 4, the largest that runs on one GPU)")
+    ap.add_argument("--exact", action="store_true",
+                    help="exact leverage scores (no sketch) with ridge_rel 1e-4: config 5's second mode")
+    ap.add_argument("--only", action="store_true",
+                    help="time the headline workload only (no `configs` array of the other workloads)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = config's own)")
     ap.add_argument("--group-mb", type=float, default=0.0, help="head-group size in MiB (0 = library default)")
     ap.add_argument("--gram-wgs", type=int, default=0, help="tuning override (0 = library's choice)")
@@ -56,7 +64,7 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="also capture one step in a HIP graph and time its replays (graph_ms_per_step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="time budget of each oracle leg")
     ap.add_argument("--cpu-threads", type=int, default=0,
                     help="cap the oracle leg's BLAS threads (0 = the host's default, all cores)")
     ap.add_argument("--flush-cache", action="store_true",
@@ -65,11 +73,14 @@ def parse():
     return ap.parse_args()
 
 
-def build_workload(W, cfg, dev, layers):
+def build_workload(W, cfg, dev, layers, exact=False):
     kw = {"device": dev}
     if layers:
         kw["L"] = layers
-    return {1: W.config1, 2: W.config2, 3: W.config3, 4: W.config4, 5: W.config5}[cfg](**kw)
+    w = {1: W.config1, 2: W.config2, 3: W.config3, 4: W.config4, 5: W.config5}[cfg](**kw)
+    if exact:
+        w.sketch_dim, w.ridge_rel = 0, 1e-4
+    return w
 
 
 # algorithmic HBM bytes per head-row of each stage (d = 128, bf16 K/V, fp32 scores, int32 idx)
@@ -80,8 +91,9 @@ def stage_bytes(w, kk):
     return {
         "gram": 256.0 * rows,                 # K read once
         "score": 260.0 * rows,                # K read again + fp32 score written
-        "select": 8.0 * rows + 4.0 * kept,    # scores read (histogram + emit), indices written
-        "gather": 1028.0 * kept,              # idx read, K and V rows read and written
+        "select": 8.0 * rows,                 # scores read (histogram + emit)
+        "gather": 1028.0 * kept,              # 4-byte index, K and V rows read and written
+        # (the index is counted once, with the stage that consumes it: 524 + 1028 r in all)
     }, rows, kept
 
 
@@ -234,21 +246,10 @@ def paged_mode(a, torch, C, W, w, reqs, params, bufs, dev):
         "n_gpus": 1, "dtype": "bf16", "data": "synthetic"}))
 
 
-def main():
-    a = parse()
-    if a.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (heads are independent, "
-              "so more GPUs would each take a share of the heads with no communication). "
-              "Run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    from paper_2507_08143_amd import compactor as C
-    from paper_2507_08143_amd import workloads as W
-
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    w = build_workload(W, a.config, dev, a.layers)
+def measure(a, torch, C, W, w, dev, full=True):
+    """Times the fused call on one workload.  -> dict with tokens/s, ms per step, per-stage event
+    times, the dominant kernel's rate and the whole path's rate; with `full` also the unfused
+    calls and the optional cold-cache and graph timings."""
     phi = W.make_phi(ks=w.sketch_dim, device=dev) if w.sketch_dim > 0 else None
     ev = C.StageEvents()
     group_bytes = int(a.group_mb * 1024 * 1024)
@@ -262,8 +263,7 @@ def main():
     nh = len(reqs) * w.layers * w.kv_heads
 
     # every output and the workspace are allocated once, outside the timed region
-    ws_bytes = max(256, C.compactor_workspace_size(params, reqs), C.compactor_workspace_size(params_ev, reqs))
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(256, C.compactor_workspace_size(params, reqs)), dtype=torch.uint8, device=dev)
     bufs = dict(kept_idx=torch.empty(ko[-1], dtype=torch.int32, device=dev),
                 kept_cnt=torch.empty(nh, dtype=torch.int32, device=dev),
                 k_packed=torch.empty(ko[-1], 128, dtype=torch.bfloat16, device=dev),
@@ -273,11 +273,139 @@ def main():
     def step(p):
         C.compactor_compress(p, reqs, want_scores=False, **bufs)
 
-    if a.attention:
-        attention_mode(a, torch, C, W, w, reqs, params, bufs, dev)
-        return
-    if a.paged:
-        paged_mode(a, torch, C, W, w, reqs, params, bufs, dev)
+    steps, warmup = (a.steps, a.warmup) if full else (max(3, a.steps // 2), max(1, a.warmup // 2))
+    for _ in range(warmup):
+        step(params)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(params)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / steps * 1e3
+    assert int(bufs["status"].max()) == 0, "a head was flagged during the benchmark"
+
+    # the same steps again with per-stage HIP events on the launch stream
+    stage_ms, step_ms = {}, []
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        step(params_ev)
+        torch.cuda.synchronize()
+        per = ev.elapsed_ms()
+        step_ms.append(sum(per.values()))
+        for k_, v_ in per.items():
+            stage_ms[k_] = stage_ms.get(k_, 0.0) + v_ / steps
+    ms_per_step_ev = (time.perf_counter() - t1) / steps * 1e3
+    ms_median_ev = sorted(step_ms)[len(step_ms) // 2]   # first to last stage event, per step
+
+    sbytes, rows, kept = stage_bytes(w, kk)
+    sflops = stage_flops(w, w.sketch_dim)
+    dominant = max(sbytes, key=lambda s: stage_ms.get(s, 0.0))
+    achieved = sbytes[dominant] / (stage_ms[dominant] * 1e-3) / 1e9
+    stages = {}
+    for s_, ms in stage_ms.items():
+        ent = {"ms": round(ms, 4)}
+        if s_ in sbytes and ms > 0:
+            ent["GB/s"] = round(sbytes[s_] / (ms * 1e-3) / 1e9, 1)
+        if s_ in sflops and ms > 0:
+            ent["TFLOP/s"] = round(sflops[s_] / (ms * 1e-3) / 1e12, 1)
+        stages[s_] = ent
+    total_bytes = sum(sbytes.values())
+    mode = "sketched k_s=%d" % w.sketch_dim if w.sketch_dim > 0 else "exact, ridge_rel=%g" % w.ridge_rel
+    res = {
+        "workload": w.name, "mode": mode, "tokens": w.tokens, "head_rows": rows, "kept_head_rows": kept,
+        "layers": w.layers, "kv_heads": w.kv_heads, "requests": len(reqs), "steps": steps,
+        "value": w.tokens / (dt / steps), "ms_per_step": ms_per_step,
+        "algorithmic_bytes": total_bytes,
+        "path_frac_of_8TB/s": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "dominant_kernel": dominant, "dominant_GB/s": achieved, "dominant_frac": achieved / HBM_PEAK_GBS,
+        "dominant_algorithmic_bytes": sbytes[dominant],
+        "stages": stages, "ms_per_step_with_events": ms_per_step_ev,
+        "ms_per_step_median_of_event_spans": ms_median_ev,
+        "mfma_path_TFLOP/s": sum(sflops.values()) / (ms_per_step * 1e-3) / 1e12,
+        "one_pass_K_bytes": total_bytes - sbytes["gram"],
+        "workspace_MB": round(ws.numel() / 1e6, 1),
+    }
+    if not full:
+        return res, (params, reqs, bufs, phi)
+
+    # cold steps: the last-level cache (256 MB) is overwritten before each one
+    if a.flush_cache:
+        junk = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        acc = []
+        for _ in range(steps):
+            junk.fill_(1)
+            e0.record()
+            step(params)
+            e1.record()
+            torch.cuda.synchronize()
+            acc.append(e0.elapsed_time(e1))
+        res["cold_ms_per_step"] = sorted(acc)[len(acc) // 2]
+        del junk
+
+    # one step captured in a HIP graph and replayed (the call only launches kernels, so it can be)
+    if a.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(params)
+        for _ in range(warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        res["graph_ms_per_step"] = (time.perf_counter() - t2) / steps * 1e3
+
+    # the three unfused calls on the same buffers (scores then travel through HBM once more)
+    scores = torch.empty(so[-1], dtype=torch.float32, device=dev)
+    ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    acc = [0.0, 0.0, 0.0]
+    for i in range(warmup + steps):
+        ev0[0].record()
+        C.compactor_score(params, reqs, scores=scores, status=bufs["status"], workspace=ws)
+        ev0[1].record()
+        C.compactor_select(params, reqs, scores, kept_idx=bufs["kept_idx"], kept_cnt=bufs["kept_cnt"],
+                           workspace=ws)
+        ev0[2].record()
+        C.compactor_compact(params, reqs, bufs["kept_idx"], bufs["kept_cnt"], bufs["k_packed"],
+                            bufs["v_packed"])
+        ev0[3].record()
+        torch.cuda.synchronize()
+        if i >= warmup:
+            for j in range(3):
+                acc[j] += ev0[j].elapsed_time(ev0[j + 1]) / steps
+    res["unfused_calls"] = {"score_ms": round(acc[0], 4), "select_ms": round(acc[1], 4),
+                            "compact_ms": round(acc[2], 4), "total_ms": round(sum(acc), 4)}
+    del scores
+    return res, (params, reqs, bufs, phi)
+
+
+# the other workloads of the benchmark set, reported beside the headline in "configs"
+OTHER_CONFIGS = [(1, False), (2, False), (3, False), (5, False), (5, True)]
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (heads are independent, "
+              "so more GPUs would each take a share of the heads with no communication). "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import gc
+    import torch
+    from paper_2507_08143_amd import compactor as C
+    from paper_2507_08143_amd import workloads as W
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = build_workload(W, a.config, dev, a.layers, a.exact)
+
+    if a.attention or a.paged:
+        res, (params, reqs, bufs, phi) = measure(a, torch, C, W, w, dev, full=False)
+        (attention_mode if a.attention else paged_mode)(a, torch, C, W, w, reqs, params, bufs, dev)
         return
 
     copy_rates = None
@@ -301,135 +429,70 @@ def main():
             copy_rates[name] = round(10 * 2.0 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
         del src, dst
 
-    for _ in range(a.warmup):
-        step(params)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        step(params)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / a.steps * 1e3
-    tokens = w.tokens
-    value = tokens / (dt / a.steps)
-    assert int(bufs["status"].max()) == 0, "a head was flagged during the benchmark"
-
-    # the same steps again with per-stage HIP events on the launch stream
-    stage_ms, step_ms = {}, []
-    t1 = time.perf_counter()
-    for _ in range(a.steps):
-        step(params_ev)
-        torch.cuda.synchronize()
-        per = ev.elapsed_ms()
-        step_ms.append(sum(per.values()))
-        for k_, v_ in per.items():
-            stage_ms[k_] = stage_ms.get(k_, 0.0) + v_ / a.steps
-    ms_per_step_ev = (time.perf_counter() - t1) / a.steps * 1e3
-    ms_median_ev = sorted(step_ms)[len(step_ms) // 2]   # first to last stage event, per step
-
-    # cold steps: the last-level cache (256 MB) is overwritten before each one
-    cold_ms = None
-    if a.flush_cache:
-        junk = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        acc = []
-        for _ in range(a.steps):
-            junk.fill_(1)
-            e0.record()
-            step(params)
-            e1.record()
-            torch.cuda.synchronize()
-            acc.append(e0.elapsed_time(e1))
-        cold_ms = sorted(acc)[len(acc) // 2]
-        del junk
-
-    # one step captured in a HIP graph and replayed (the call only launches kernels, so it can be)
-    graph_ms = None
-    if a.graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step(params)
-        for _ in range(a.warmup):
-            graph.replay()
-        torch.cuda.synchronize()
-        t2 = time.perf_counter()
-        for _ in range(a.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t2) / a.steps * 1e3
-
-    # the three unfused calls on the same buffers (scores then travel through HBM once more)
-    unfused = None
-    if True:
-        scores = torch.empty(so[-1], dtype=torch.float32, device=dev)
-        ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-        acc = [0.0, 0.0, 0.0]
-        for i in range(a.warmup + a.steps):
-            ev0[0].record()
-            C.compactor_score(params, reqs, scores=scores, status=bufs["status"], workspace=ws)
-            ev0[1].record()
-            C.compactor_select(params, reqs, scores, kept_idx=bufs["kept_idx"], kept_cnt=bufs["kept_cnt"],
-                               workspace=ws)
-            ev0[2].record()
-            C.compactor_compact(params, reqs, bufs["kept_idx"], bufs["kept_cnt"], bufs["k_packed"],
-                                bufs["v_packed"])
-            ev0[3].record()
-            torch.cuda.synchronize()
-            if i >= a.warmup:
-                for j in range(3):
-                    acc[j] += ev0[j].elapsed_time(ev0[j + 1]) / a.steps
-        unfused = {"score_ms": round(acc[0], 4), "select_ms": round(acc[1], 4),
-                   "compact_ms": round(acc[2], 4), "total_ms": round(sum(acc), 4)}
-        del scores
-
-    sbytes, rows, kept = stage_bytes(w, kk)
-    sflops = stage_flops(w, w.sketch_dim)
-    dominant = max(sbytes, key=lambda s: stage_ms.get(s, 0.0))
-    dom_ms = stage_ms[dominant]
-    achieved = sbytes[dominant] / (dom_ms * 1e-3) / 1e9
-    stages = {}
-    for s_, ms in stage_ms.items():
-        ent = {"ms": round(ms, 4)}
-        if s_ in sbytes and ms > 0:
-            ent["GB/s"] = round(sbytes[s_] / (ms * 1e-3) / 1e9, 1)
-        if s_ in sflops and ms > 0:
-            ent["TFLOP/s"] = round(sflops[s_] / (ms * 1e-3) / 1e12, 1)
-        stages[s_] = ent
-    total_bytes = sum(sbytes.values())
+    res, (params, reqs, bufs, phi) = measure(a, torch, C, W, w, dev, full=True)
+    dominant = res["dominant_kernel"]
+    traffic = None
+    if not a.layers and a.scope == "head" and not a.group_mb:
+        traffic = MEASURED_TRAFFIC_BYTES.get((w.name, res["mode"].split()[0], dominant))
 
     out = {
         "metric": "tokens compressed/sec (score+select+compact) at 1 GPU",
-        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "value": res["value"], "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "layers": w.layers, "kv_heads": w.kv_heads, "head_dim": 128,
-                   "requests": len(reqs), "tokens": tokens, "head_rows": rows,
-                   "kept_head_rows": kept, "sketch_dim": w.sketch_dim,
-                   "group_mb": a.group_mb, "select_scope": a.scope},
-        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "algorithmic_bytes": sbytes[dominant],
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dominant)) if not a.layers else None},
-        "path_hbm": {"algorithmic_bytes": total_bytes,
-                     "achieved_GB/s": total_bytes / (ms_per_step * 1e-3) / 1e9,
-                     "frac_of_8TB/s": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "config": {"workload": w.name, "mode": res["mode"], "layers": w.layers, "kv_heads": w.kv_heads,
+                   "head_dim": 128, "requests": res["requests"], "tokens": res["tokens"],
+                   "head_rows": res["head_rows"], "kept_head_rows": res["kept_head_rows"],
+                   "sketch_dim": w.sketch_dim, "group_mb": a.group_mb, "select_scope": a.scope,
+                   "why": "largest single-GPU workload of the benchmark set" if a.config == 4 else "chosen with --config"},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": res["dominant_GB/s"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["dominant_frac"],
+                     "algorithmic_bytes": res["dominant_algorithmic_bytes"], "traffic": traffic},
+        "path_hbm": {"algorithmic_bytes": res["algorithmic_bytes"],
+                     "achieved_GB/s": res["algorithmic_bytes"] / (res["ms_per_step"] * 1e-3) / 1e9,
+                     "frac_of_8TB/s": res["path_frac_of_8TB/s"],
                      # what a path whose second pass over K hit a cache would have to move
-                     "one_pass_K_bytes": total_bytes - sbytes["gram"]},
-        "mfma": {"path_TFLOP/s": sum(sflops.values()) / (ms_per_step * 1e-3) / 1e12,
-                 "frac_of_bf16_peak": sum(sflops.values()) / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
-        "stages": stages, "ms_per_step_with_events": ms_per_step_ev,
-        "ms_per_step_median_of_event_spans": ms_median_ev,
-        "unfused_calls": unfused,
+                     "one_pass_K_bytes": res["one_pass_K_bytes"]},
+        "mfma": {"path_TFLOP/s": res["mfma_path_TFLOP/s"],
+                 "frac_of_bf16_peak": res["mfma_path_TFLOP/s"] / MFMA_BF16_PEAK_TFLOPS},
+        "stages": res["stages"], "ms_per_step_with_events": res["ms_per_step_with_events"],
+        "ms_per_step_median_of_event_spans": res["ms_per_step_median_of_event_spans"],
+        "unfused_calls": res["unfused_calls"],
     }
-    if cold_ms is not None:
-        out["cold_ms_per_step"] = cold_ms
-    if graph_ms is not None:
-        out["graph_ms_per_step"] = graph_ms
+    for key in ("cold_ms_per_step", "graph_ms_per_step"):
+        if key in res:
+            out[key] = res[key]
     if copy_rates is not None:
         out["plain_copy_1GiB"] = copy_rates
+
     if not a.no_cpu_baseline:
+        # the oracle on a bounded sample of the headline workload: all host cores, then one thread
         from oracle import compactor_oracle as O
         out["cpu_baseline"] = cpu_baseline(W, O, w, phi, a.cpu_seconds, a.cpu_threads)
+        if a.cpu_threads == 0:
+            out["cpu_baseline_1thread"] = cpu_baseline(W, O, w, phi, a.cpu_seconds, 1)
+
+    # the other workloads of the set, each built, timed the same way and freed again
+    if not a.only and not a.layers:
+        del params, reqs, bufs, w
+        gc.collect()
+        torch.cuda.empty_cache()
+        out["configs"] = []
+        for cfg, exact in OTHER_CONFIGS:
+            if cfg == a.config and exact == a.exact:
+                continue
+            wo = build_workload(W, cfg, dev, 0, exact)
+            r, keep = measure(a, torch, C, W, wo, dev, full=False)
+            out["configs"].append({
+                "workload": r["workload"], "mode": r["mode"], "tokens": r["tokens"],
+                "tokens_per_s": r["value"], "ms_per_step": round(r["ms_per_step"], 4),
+                "path_frac_of_8TB/s": round(r["path_frac_of_8TB/s"], 4),
+                "dominant_kernel": r["dominant_kernel"], "dominant_frac": round(r["dominant_frac"], 4),
+                "stages_ms": {k_: v_["ms"] for k_, v_ in r["stages"].items()},
+                "steps": r["steps"]})
+            del wo, keep, r
+            gc.collect()
+            torch.cuda.empty_cache()
     print(json.dumps(out))
 
 
