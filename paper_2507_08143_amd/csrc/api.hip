@@ -111,8 +111,13 @@ int score_tokens_for(const compactor_params_t *p, const SegTable &T, int cus) {
 }
 
 struct GroupBytes {
-  size_t partials, g64, wt, hist1, sel, scores;   // in this order in the workspace
-  size_t total() const { return partials + g64 + wt + hist1 + sel + scores; }
+  size_t partials, g64, wt, hist1, sel, bstat, scores;   // in this order in the workspace
+  size_t total() const { return partials + g64 + wt + hist1 + sel + bstat + scores; }
+  size_t off_wt() const { return partials + g64; }
+  size_t off_hist1() const { return off_wt() + wt; }
+  size_t off_sel() const { return off_hist1() + hist1; }
+  size_t off_bstat() const { return off_sel() + sel; }
+  size_t off_scores() const { return off_bstat() + bstat; }
 };
 
 GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bool need_scores) {
@@ -126,7 +131,14 @@ GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bo
   g.g64 = ks > 0 ? 0 : align_up((size_t)T.nheads * D * D * sizeof(double));   // exact mode only
   g.wt = align_up((size_t)T.nheads * W_TERMS * m * D * sizeof(uint16_t));
   g.hist1 = align_up((size_t)T.nheads * HIST1_BINS * sizeof(int));
-  g.sel = align_up((size_t)select_scratch(T).ints() * sizeof(int));
+  g.sel = select_needs_pools(T) ? align_up((size_t)select_scratch(T).ints() * sizeof(int)) : 0;
+  // the blend's sums: two doubles per score workgroup and per selection chunk
+  g.bstat = 0;
+  if (blend_wanted(T)) {
+    const long long pairs = total_blocks(T, score_tokens_for(p, T, compute_units()), SCORE_STEP, false) +
+                            select_chunks(T);
+    g.bstat = align_up((size_t)pairs * 2 * sizeof(double));
+  }
   g.scores = need_scores ? align_up((size_t)rows * sizeof(float)) : 0;
   return g;
 }
@@ -176,6 +188,7 @@ int for_each_group(const compactor_params_t *p, const compactor_request_t *reqs,
         ++b;
       }
     }
+    index_chunks(T);
     const int rc = fn(T, rows);
     if (rc != COMPACTOR_OK) return rc;
   }
@@ -232,29 +245,19 @@ struct Marks {
     if (rc_ != COMPACTOR_OK) return rc_; \
   } while (0)
 
-// score (+ blend) of one group.  *hist1_out receives the per-head histogram of the top 12 key
-// bits of the final scores (for the selection), or null when a blend rewrote the scores.
+// score (+ blend) of one group.  With want_hist1 the per-pool histogram of the top 12 key bits
+// of the final scores is left at gb.off_hist1() of the workspace (for the selection).
 int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows, float *scores,
-                  int32_t *status, unsigned char *ws, hipStream_t st, const int **hist1_out) {
+                  int32_t *status, unsigned char *ws, hipStream_t st, bool want_hist1) {
   const GroupBytes gb = group_bytes_needed(p, T, false);
   float *partials = reinterpret_cast<float *>(ws);
   double *g64 = reinterpret_cast<double *>(ws + gb.partials);
-  uint16_t *wt = reinterpret_cast<uint16_t *>(ws + gb.partials + gb.g64);
-  int *hist_base = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt);
-  int *hist1 = hist_base;
-  bool blended = false;
-  for (int i = 0; i < T.nseg; ++i) blended |= T.s[i].attn != nullptr;
-  if (blended || hist1_out == nullptr) hist1 = nullptr;
-  if (hist1_out) *hist1_out = hist1;
-  // histograms cleared on the way: the score kernel's, and those of a pooled selection that
-  // follows (they sit right behind it)
-  int *zero = nullptr;
-  long long zero_ints = 0;
-  if (hist1_out != nullptr) {
-    zero = hist_base;
-    zero_ints = (long long)T.nheads * HIST1_BINS;
-    if (select_needs_pools(T)) zero_ints += select_scratch(T).zero_ints();
-  }
+  uint16_t *wt = reinterpret_cast<uint16_t *>(ws + gb.off_wt());
+  int *hist1 = want_hist1 ? reinterpret_cast<int *>(ws + gb.off_hist1()) : nullptr;
+  double *ostat = gb.bstat ? reinterpret_cast<double *>(ws + gb.off_bstat()) : nullptr;
+  // the histogram is cleared on the way, by the factorisation kernel
+  int *zero = hist1;
+  const long long zero_ints = hist1 ? (long long)T.nheads * HIST1_BINS : 0;
   const int cus = compute_units();
   const GramPlan gp = gram_plan(p, T, cus);
   const int rpw = gp.tiles_per_wg;
@@ -272,9 +275,13 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
     HIP_TRY(launch_solve(T, p->ridge_rel, g64, wt, status, st));
   }
   MARK(m, COMPACTOR_STAGE_SOLVE + 1);
-  HIP_TRY(launch_score(T, p->sketch_dim, score_tokens_for(p, T, cus), wt, scores, status, hist1, st));
+  const int score_tokens = score_tokens_for(p, T, cus);
+  HIP_TRY(launch_score(T, p->sketch_dim, score_tokens, wt, scores, status, hist1, ostat, st));
   MARK(m, COMPACTOR_STAGE_SCORE + 1);
-  HIP_TRY(launch_blend(T, p->lambda_blend, scores, st));
+  if (ostat != nullptr) {
+    double *astat = ostat + 2 * total_blocks(T, score_tokens, SCORE_STEP, false);
+    HIP_TRY(launch_blend(T, p->lambda_blend, score_tokens, scores, ostat, astat, hist1, st));
+  }
   MARK(m, COMPACTOR_STAGE_BLEND + 1);
   return COMPACTOR_OK;
 }
@@ -336,17 +343,14 @@ int enqueue_compress(const compactor_params_t *p, const compactor_request_t *req
                         [&](const SegTable &T, long long rows) {
     float *sc = scores;
     const GroupBytes gb = group_bytes_needed(p, T, true);
-    if (local_scores)
-      sc = reinterpret_cast<float *>(ws + gb.partials + gb.g64 + gb.wt + gb.hist1 + gb.sel);
-    const int *hist1 = nullptr;
-    const int rc2 = enqueue_score(p, T, rows, sc, status, ws, st, &hist1);
+    if (local_scores) sc = reinterpret_cast<float *>(ws + gb.off_scores());
+    const int rc2 = enqueue_score(p, T, rows, sc, status, ws, st, true);
     if (rc2) return rc2;
     const Marks m{p->stage_events, st};
+    int *hist1 = reinterpret_cast<int *>(ws + gb.off_hist1());
     if (select_needs_pools(T)) {
-      int *hist_base = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt);
-      int *sel = reinterpret_cast<int *>(ws + gb.partials + gb.g64 + gb.wt + gb.hist1);
-      HIP_TRY(launch_select_pools(T, sc, hist_base, hist1 != nullptr, sel, true, kept_idx, kept_cnt,
-                                  st));
+      int *sel = reinterpret_cast<int *>(ws + gb.off_sel());
+      HIP_TRY(launch_select_pools(T, sc, hist1, true, sel, kept_idx, kept_cnt, st));
     } else {
       HIP_TRY(launch_select(T, sc, hist1, kept_idx, kept_cnt, st));
     }
@@ -455,7 +459,7 @@ int compactor_score(const compactor_params_t *p, const compactor_request_t *reqs
   hipStream_t st = static_cast<hipStream_t>(stream);
   return for_each_group(p, reqs, nreq, group_rows_of(p), false,
                         [&](const SegTable &T, long long rows) {
-                          return enqueue_score(p, T, rows, scores, status, ws, st, nullptr);
+                          return enqueue_score(p, T, rows, scores, status, ws, st, false);
                         });
 }
 
@@ -491,7 +495,7 @@ int compactor_select(const compactor_params_t *p, const compactor_request_t *req
       const GroupBytes gb = group_bytes_needed(p, T, false);
       int *hist1 = static_cast<int *>(workspace);
       int *sel = reinterpret_cast<int *>(static_cast<unsigned char *>(workspace) + gb.hist1);
-      HIP_TRY(launch_select_pools(T, scores, hist1, false, sel, false, kept_idx, kept_cnt, st));
+      HIP_TRY(launch_select_pools(T, scores, hist1, false, sel, kept_idx, kept_cnt, st));
     } else {
       HIP_TRY(launch_select(T, scores, nullptr, kept_idx, kept_cnt, st));
     }

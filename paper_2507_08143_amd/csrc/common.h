@@ -22,6 +22,8 @@ constexpr int GRAM_TILE = 64;         // rows staged in LDS per step of the Gram
 constexpr int SCORE_STEP = 128;       // tokens a score workgroup multiplies per step
 constexpr int SCORE_MAX_TOKENS = 4096;   // most tokens a score workgroup takes (their scores wait in LDS)
 constexpr int SELECT_THREADS = 1024;
+constexpr int SEL_CHUNK = 8192;       // tokens per workgroup of the chunked selection and blend
+                                      // kernels (chunks never cross heads)
 constexpr int GATHER_THREADS = 128;   // a gather workgroup: 8 groups of 16 lanes, one row each
 constexpr int GATHER_ROWS = 16;       // kept rows per gather workgroup (2 per 16-lane group)
 
@@ -42,6 +44,13 @@ struct Seg {
   int lhead0;            // launch-local index of this segment's first head (workspace arrays)
   int H;                 // kv heads per layer
   int req;               // index of the request in the call
+  // Chunk enumeration of the selection and blend kernels, filled by index_chunks(): a workgroup
+  // finds its place from these instead of redoing the divisions for every segment before it.
+  int sel_blk0;          // number of the segment's first chunk in the launch
+  int sel_bph;           // chunks per head
+  int sel_chunk;         // tokens per chunk (the last chunk of a head may be shorter)
+  int pool0;             // launch-local index of the segment's first selection pool
+  long long tok0;        // position of the segment's first token in the launch's token sequence
 };
 
 struct SegTable {
@@ -282,33 +291,40 @@ hipError_t launch_srht_phi(int ks, const uint8_t *signs, const int32_t *cols, fl
                            hipStream_t st);
 
 // scores[i] = || W^T k_i ||^2
-// Also tallies the scores into hist1[selection pool][HIST1_BINS] (top 12 key bits; the pool is
-// the head, or the layer when T.layer_scope), which must be zero on entry; hist1 may be null.
+// Also tallies the scores of heads that will not be blended into hist1[selection pool][HIST1_BINS]
+// (top 12 key bits; the pool is the head, or the layer when T.layer_scope), which must be zero on
+// entry; hist1 may be null.  ostat, if not null, receives (sum, sum of squares) of every
+// workgroup's scores in fp64, two doubles per workgroup of the launch (for the blend).
 hipError_t launch_score(const SegTable &T, int ks, int tokens_per_wg, const uint16_t *wt,
-                        float *scores, int32_t *status, int *hist1, hipStream_t st);
+                        float *scores, int32_t *status, int *hist1, double *ostat, hipStream_t st);
 
-// s = z(a) + lambda z(o) in place over the scores of heads whose request has attn
-hipError_t launch_blend(const SegTable &T, float lambda, float *scores, hipStream_t st);
+// s = z(a) + lambda z(o) in place over the scores of heads whose request has attn; their first
+// selection histogram goes to hist1 (may be null).  score_tokens: the tokens_per_wg the score
+// launch ran with (it decides which entries of ostat belong to a head); astat: scratch, two
+// doubles per selection chunk (select_chunks).
+bool blend_wanted(const SegTable &T);
+long long select_chunks(const SegTable &T);
+hipError_t launch_blend(const SegTable &T, float lambda, int score_tokens, float *scores,
+                        const double *ostat, double *astat, int *hist1, hipStream_t st);
 
 // hist1: per-head histogram of the top 12 key bits made by the score kernel, or null.
 hipError_t launch_select(const SegTable &T, const float *scores, const int *hist1,
                          int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st);
 
-// Selection by several workgroups per pool (long heads, or layer scope).  hist1 (pools x 4096
-// ints) and the scratch `sel` must be adjacent in memory, hist1 first: hist1 | hist2 | hist3 are
-// cleared together.  hist1_ready: the score kernel has tallied it; zeroed: somebody has cleared
-// hist1 .. hist3 already.
+// Selection by several workgroups per pool (long heads, or layer scope).  hist1: pools x 4096
+// ints; hist1_ready: it holds the histogram of the scores' top 12 key bits already (otherwise it
+// is cleared and tallied here).  sel: scratch of select_scratch(T).ints() ints (candidate lists,
+// one slot per token of the launch; per-chunk records and offsets; per-pool state), none of which
+// needs clearing.
 struct SelectScratch {
   int pools;
-  long long chunks, hist2_ints, hist3_ints, rec_ints, coff_ints, thr_ints;
-  long long ints() const { return hist2_ints + hist3_ints + rec_ints + coff_ints + thr_ints; }
-  long long zero_ints() const { return hist2_ints + hist3_ints; }
+  long long chunks, cand_ints, rec_ints, coff_ints, state_ints;
+  long long ints() const { return cand_ints + rec_ints + coff_ints + state_ints; }
 };
 SelectScratch select_scratch(const SegTable &T);
 bool select_needs_pools(const SegTable &T);
 hipError_t launch_select_pools(const SegTable &T, const float *scores, int *hist1, bool hist1_ready,
-                               int *sel, bool zeroed, int32_t *kept_idx, int32_t *kept_cnt,
-                               hipStream_t st);
+                               int *sel, int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st);
 
 // kept_cnt is read in layer scope only (ragged heads inside a layer's region).
 hipError_t launch_gather(const SegTable &T, const int32_t *kept_idx, const int32_t *kept_cnt,
@@ -329,6 +345,24 @@ struct PagePool {
 // in_place: the rows are read from the pages themselves (token t at logical slot t).
 hipError_t launch_gather_paged(const SegTable &T, const PagePool &P, const int32_t *kept_idx,
                                const int32_t *kept_cnt, bool in_place, hipStream_t st);
+
+// Fills the chunk enumeration fields of every segment (host, after the table is otherwise
+// complete).
+inline void index_chunks(SegTable &T) {
+  int blk = 0, pool = 0;
+  long long tok = 0;
+  for (int i = 0; i < T.nseg; ++i) {
+    Seg &s = T.s[i];
+    s.sel_blk0 = blk;
+    s.sel_bph = blocks_per_head(s.n, SEL_CHUNK, 4);
+    s.sel_chunk = chunk_of(s.n, SEL_CHUNK, 4);
+    s.pool0 = pool;
+    s.tok0 = tok;
+    blk += s.sel_bph * s.head_count;
+    pool += s.head_count / pool_heads(T, s);
+    tok += (long long)s.n * s.head_count;
+  }
+}
 
 // Total workgroups of a launch whose blocks-per-head rule is (per_block, by_keep).
 inline long long total_blocks(const SegTable &T, int per_block, int step, bool by_keep) {

@@ -33,7 +33,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 template <int M>
 __global__ __launch_bounds__(256, M > 64 ? 1 : 2) void score_kernel(
     const SegTable T, int tokens_per_wg, const uint16_t *__restrict__ wt, float *__restrict__ scores,
-    int32_t *__restrict__ status, int *__restrict__ hist1) {
+    int32_t *__restrict__ status, int *__restrict__ hist1, double *__restrict__ ostat) {
   constexpr int NSUB = 2, WTOK = 16 * NSUB, STEP = 4 * WTOK;     // tokens per wave / per WG step
   constexpr int NLD = WTOK * 16 / 64;                            // 16-B loads per lane per step
   __shared__ __attribute__((aligned(16))) uint16_t wl[W_TERMS * M * WPITCH];
@@ -187,7 +187,31 @@ __global__ __launch_bounds__(256, M > 64 ? 1 : 2) void score_kernel(
     }
     for (int i = lead + ((cnt - lead) & ~3) + tid; i < cnt; i += 256) dst[i] = sc_l[i];
   }
-  if (hist1 != nullptr) {        // integer adds: the per-head histogram is order independent
+  if (ostat != nullptr && s.attn != nullptr) {
+    // (sum, sum of squares) of this workgroup's scores for the blend's standardisation, in fp64
+    // and in a fixed order: lanes stride the run, then a butterfly per wave, then the 4 waves
+    __shared__ double red[4][2];
+    const int cnt = tok_end - tok_begin;
+    double s1 = 0.0, s2 = 0.0;
+    for (int i = tid; i < cnt; i += 256) {
+      const double x = (double)sc_l[i];
+      s1 += x;
+      s2 += x * x;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+      s1 += __shfl_xor(s1, d);
+      s2 += __shfl_xor(s2, d);
+    }
+    if (lane == 0) { red[wave][0] = s1; red[wave][1] = s2; }
+    __syncthreads();
+    if (tid == 0) {
+      ostat[2 * (size_t)blockIdx.x] = (red[0][0] + red[1][0]) + (red[2][0] + red[3][0]);
+      ostat[2 * (size_t)blockIdx.x + 1] = (red[0][1] + red[1][1]) + (red[2][1] + red[3][1]);
+    }
+  }
+  // a head that will be blended gets its histogram from the blend, over the final scores
+  if (hist1 != nullptr && s.attn == nullptr) {   // integer adds: order independent
     int *h1 = hist1 + (size_t)(w.lhead / pool_heads(T, s)) * HIST1_BINS;
     for (int i = tid; i < HIST1_BINS; i += 256) {
       const int c = (int)((hl[i >> 1] >> (16 * (i & 1))) & 0xffffu);
@@ -198,23 +222,24 @@ __global__ __launch_bounds__(256, M > 64 ? 1 : 2) void score_kernel(
 
 template <int M>
 static hipError_t launch_m(const SegTable &T, int tokens_per_wg, const uint16_t *wt,
-                           float *scores, int32_t *status, int *hist1, hipStream_t st) {
+                           float *scores, int32_t *status, int *hist1, double *ostat,
+                           hipStream_t st) {
   const long long nb = total_blocks(T, tokens_per_wg, SCORE_STEP, false);
   if (nb <= 0) return hipSuccess;
   if (nb > 0x7fffffffll) return hipErrorInvalidValue;
   hipLaunchKernelGGL((score_kernel<M>), dim3((unsigned)nb), dim3(256), 0, st, T, tokens_per_wg, wt,
-                     scores, status, hist1);
+                     scores, status, hist1, ostat);
   return hipGetLastError();
 }
 
 hipError_t launch_score(const SegTable &T, int ks, int tokens_per_wg, const uint16_t *wt,
-                        float *scores, int32_t *status, int *hist1, hipStream_t st) {
+                        float *scores, int32_t *status, int *hist1, double *ostat, hipStream_t st) {
   switch (ks) {
-    case 16: return launch_m<16>(T, tokens_per_wg, wt, scores, status, hist1, st);
-    case 32: return launch_m<32>(T, tokens_per_wg, wt, scores, status, hist1, st);
-    case 48: return launch_m<48>(T, tokens_per_wg, wt, scores, status, hist1, st);
-    case 64: return launch_m<64>(T, tokens_per_wg, wt, scores, status, hist1, st);
-    case 0:  return launch_m<128>(T, tokens_per_wg, wt, scores, status, hist1, st);
+    case 16: return launch_m<16>(T, tokens_per_wg, wt, scores, status, hist1, ostat, st);
+    case 32: return launch_m<32>(T, tokens_per_wg, wt, scores, status, hist1, ostat, st);
+    case 48: return launch_m<48>(T, tokens_per_wg, wt, scores, status, hist1, ostat, st);
+    case 64: return launch_m<64>(T, tokens_per_wg, wt, scores, status, hist1, ostat, st);
+    case 0:  return launch_m<128>(T, tokens_per_wg, wt, scores, status, hist1, ostat, st);
     default: return hipErrorInvalidValue;
   }
 }

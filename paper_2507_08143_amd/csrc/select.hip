@@ -12,8 +12,9 @@
 
 namespace cmp {
 
-// Exclusive prefix sum of one int per thread over the 1024-thread workgroup; *total gets the
-// workgroup sum.  wsum is 16 ints of LDS.
+// Exclusive prefix sum of one int per thread over a workgroup of NT threads; *total gets the
+// workgroup sum.  wsum is NT / 64 ints of LDS.
+template <int NT = SELECT_THREADS>
 __device__ __forceinline__ int block_exclusive_scan(int v, int *wsum, int *total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int inc = v;
@@ -27,7 +28,7 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *wsum, int *total
   __syncthreads();
   int base = 0, tot = 0;
 #pragma unroll
-  for (int i = 0; i < SELECT_THREADS / 64; ++i) {
+  for (int i = 0; i < NT / 64; ++i) {
     const int x = wsum[i];
     if (i < wave) base += x;
     tot += x;
@@ -40,24 +41,26 @@ constexpr int LDS_KEYS = 32768;    // heads up to this many tokens keep their ke
 
 // Finds, in a histogram of `nb` digits, the digit where the descending cumulative count reaches
 // `need`; returns the digit and leaves in *need the count still wanted inside that digit.
+template <int NT = SELECT_THREADS>
 __device__ __forceinline__ int find_digit(const int *hist, int nb, int *need, int *wsum, int *found) {
+  constexpr int PER = 4096 / NT;     // digits per thread (nb <= 4096)
   const int tid = threadIdx.x;
-  // thread t owns the 4 digits nb-1-4t .. nb-4-4t (descending), so that an ascending scan over
+  // thread t owns the PER digits nb-1-PER*t .. (descending), so that an ascending scan over
   // threads is a descending scan over digits
-  int c[4], sum = 0;
+  int c[PER], sum = 0;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int dgt = nb - 1 - (4 * tid + q);
+  for (int q = 0; q < PER; ++q) {
+    const int dgt = nb - 1 - (PER * tid + q);
     c[q] = dgt >= 0 ? hist[dgt] : 0;
     sum += c[q];
   }
   int total;
-  int before = block_exclusive_scan(sum, wsum, &total);   // keys in higher digits
+  int before = block_exclusive_scan<NT>(sum, wsum, &total);   // keys in higher digits
   const int want = *need;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < PER; ++q) {
     if (before < want && want <= before + c[q]) {          // exactly one (thread, q) matches
-      found[0] = nb - 1 - (4 * tid + q);
+      found[0] = nb - 1 - (PER * tid + q);
       found[1] = want - before;
     }
     before += c[q];
@@ -248,53 +251,76 @@ __global__ __launch_bounds__(SELECT_THREADS) void select_kernel(const SegTable T
 // Used when a head is too long for one workgroup's LDS, and for head-adaptive selection, where
 // the pool is the H kv heads of a layer that share one budget of H * k_keep tokens (paper Sec. 3.3:
 // the top scores "across all heads"; scoring stays per head).  The same radix select and ordered
-// emit as above, cut into chunks of a head (one workgroup each) that meet in per-pool
-// histograms in global memory:
-//   hist1  top 12 key bits (made by the score kernel, or by msel_hist1_kernel)
-//   hist2  next 12 bits among the keys in the threshold's first digit
-//   hist3  last 8 bits among the keys that share the threshold's top 24 bits; every chunk also
-//          records its own share (and its count of keys above those 24 bits), from which one
-//          workgroup per pool derives every chunk's output position and its allowance of
-//          threshold ties, in (head, token) order
-// The chunk kernels are held to 64 registers so that two 1024-thread workgroups share a CU.
-// Four launches: hist2, hist3, scan, emit.  Each finds one digit of the threshold (every
-// workgroup of a pool for itself, from a few KB in L2) and passes it on in the pool's state.
-constexpr int SEL_CHUNK = 32768;         // tokens per workgroup (chunks never cross heads)
-constexpr int SEL_ROUNDS = SEL_CHUNK / (4 * SELECT_THREADS);   // 4-token groups per thread
-constexpr int SEL_REC = 260;             // ints per chunk record: [0] keys above the 24-bit
-                                         // prefix, [4 + b] keys equal to it with low byte b
+// emit as above, with the scores read twice in all.  A pool (head or layer) is cut into chunks of
+// up to 8192 tokens of one head, one workgroup each; three launches:
+//   cand   the first digit d1 of the threshold key comes from the pool's histogram of the top 12
+//          key bits (made by the score kernel, the blend, or msel_hist1_kernel).  Keys above d1
+//          are retained for sure and only counted; the keys inside d1 (the candidates: a few
+//          percent of the pool unless the scores are heavily tied) leave their low 20 bits in a
+//          per-chunk list
+//   thr    one workgroup per pool finds the remaining 12 + 8 bits of the threshold among the
+//          candidates and derives, chunk by chunk in (head, token) order, every chunk's output
+//          position and its allowance of threshold ties
+//   emit   ordered emit of every chunk
+// Everything is integer work on exact counts, so the result does not depend on the order in which
+// candidates are listed.  A chunk workgroup's chain (locate, load, classify, write) is latency
+// bound, so the chunk kernels are small workgroups of 256 threads held to 64 registers: eight of
+// them share a CU and overlap each other's waits (1024-thread workgroups on 32768-token chunks
+// moved 2.4 TB/s).
+constexpr int CHUNK_THREADS = 256;
+constexpr int SEL_ROUNDS = SEL_CHUNK / (4 * CHUNK_THREADS);    // 4-token groups per thread
 constexpr int SEL_STATE = 8;             // ints of state per pool:
-enum { ST_D1 = 0, ST_NEED1, ST_D2, ST_NEED2, ST_THR, ST_TIES };
+enum { ST_D1 = 0, ST_NEED1, ST_THR, ST_TIES };
 static_assert(SEL_ROUNDS >= 1 && SEL_ROUNDS <= 8, "one validity bit per token in 32 bits");
 
 struct SelWhere {
-  Where w;
+  int seg;
+  int head;        // l*H + h inside the request
+  int lhead;       // launch-local head index
+  int tile;        // chunk inside the head
   int pool;        // launch-local pool index
   int tok_begin, tok_end;
 };
+// Every wave of every chunk workgroup runs this, and it is scalar work that the waves of a CU
+// queue up for: the per-segment numbers come precomputed in the table (index_chunks), so that
+// one division remains.
 __device__ __forceinline__ SelWhere sel_locate(const SegTable &T, int blk) {
   SelWhere q;
-  q.w = locate_block(T, blk, SEL_CHUNK, 4, false);
-  const Seg &s = T.s[q.w.seg];
-  q.pool = q.w.lhead / pool_heads(T, s);
-  q.tok_begin = q.w.tile * q.w.chunk;
-  q.tok_end = min(s.n, q.tok_begin + q.w.chunk);
+  int seg = 0;
+  for (int i = 1; i < T.nseg; ++i) seg += blk >= T.s[i].sel_blk0;
+  const Seg &s = T.s[seg];
+  const int local = blk - s.sel_blk0;
+  const int hh = (int)((unsigned)local / (unsigned)s.sel_bph);
+  q.seg = seg;
+  q.head = s.head_begin + hh;
+  q.lhead = s.lhead0 + hh;
+  q.tile = local - hh * s.sel_bph;
+  q.pool = T.layer_scope ? s.pool0 + hh / s.H : s.pool0 + hh;
+  q.tok_begin = q.tile * s.sel_chunk;
+  q.tok_end = min(s.n, q.tok_begin + s.sel_chunk);
   return q;
 }
 
-// The keys of a chunk, 4 consecutive tokens per thread and round (token of key[r][e]:
-// tok_begin + 4 * (r * SELECT_THREADS + tid) + e); bit 4r+e of the result says that the token
-// exists.  Every load is issued before any key is used.
-__device__ __forceinline__ unsigned load_chunk_keys(const float *__restrict__ sp, const SelWhere &q,
-                                                    uint32_t (&key)[SEL_ROUNDS][4]) {
+// Position of a chunk's first token in the launch's token sequence (segments, heads and tokens in
+// order): where its candidate list starts.
+__device__ __forceinline__ long long chunk_token_base(const SegTable &T, const SelWhere &q) {
+  const Seg &s = T.s[q.seg];
+  return s.tok0 + (long long)(q.head - s.head_begin) * s.n + q.tok_begin;
+}
+
+// The scores of a chunk, 4 consecutive tokens per thread and round (token of f[r][e]:
+// tok_begin + 4 * (r * CHUNK_THREADS + tid) + e); bit 4r+e of the result says that the token
+// exists.  The loads are only issued here: whoever calls this first and converts to keys later
+// has the latency of everything in between for free.
+__device__ __forceinline__ unsigned load_chunk_scores(const float *__restrict__ sp, const SelWhere &q,
+                                                      float (&f)[SEL_ROUNDS][4]) {
   // one 16-byte load per 4 tokens also where a head's scores start off a 16-byte boundary (odd
   // n): global memory takes vector loads at any 4-byte address
   typedef float f32x4_any __attribute__((ext_vector_type(4), aligned(4)));
-  float f[SEL_ROUNDS][4];
   unsigned valid = 0;
 #pragma unroll
   for (int r = 0; r < SEL_ROUNDS; ++r) {
-    const int i0 = q.tok_begin + 4 * (r * SELECT_THREADS + (int)threadIdx.x);
+    const int i0 = q.tok_begin + 4 * (r * CHUNK_THREADS + (int)threadIdx.x);
     if (i0 + 3 < q.tok_end) {
       const f32x4_any v = *reinterpret_cast<const f32x4_any *>(sp + i0);
       f[r][0] = v.x; f[r][1] = v.y; f[r][2] = v.z; f[r][3] = v.w;
@@ -310,30 +336,36 @@ __device__ __forceinline__ unsigned load_chunk_keys(const float *__restrict__ sp
       }
     }
   }
+  return valid;
+}
+__device__ __forceinline__ void scores_to_keys(const float (&f)[SEL_ROUNDS][4],
+                                               uint32_t (&key)[SEL_ROUNDS][4]) {
 #pragma unroll
   for (int r = 0; r < SEL_ROUNDS; ++r)
 #pragma unroll
     for (int e = 0; e < 4; ++e) key[r][e] = score_key(f[r][e]);
-  return valid;
 }
 
-// find_digit on a histogram in global memory (16-byte aligned, nb a multiple of 4).
-__device__ __forceinline__ int find_digit_global(const int *__restrict__ g, int nb, int *need,
-                                                 int *wsum, int *found) {
-  const int t4 = 4 * threadIdx.x;
-  int c[4] = {0, 0, 0, 0}, sum = 0;
-  if (t4 < nb) {       // digits nb-1-t4 .. nb-4-t4, descending
-    const int4 v = *reinterpret_cast<const int4 *>(g + nb - 4 - t4);
-    c[0] = v.w; c[1] = v.z; c[2] = v.y; c[3] = v.x;
-    sum = c[0] + c[1] + c[2] + c[3];
+// find_digit on the 4096-digit histogram of a pool in global memory (16-byte aligned), by a
+// workgroup of CHUNK_THREADS.
+__device__ __forceinline__ int find_digit_global(const int *__restrict__ g, int *need, int *wsum,
+                                                 int *found) {
+  constexpr int NB = 4096, PER = NB / CHUNK_THREADS;
+  const int t0 = PER * threadIdx.x;      // digits NB-1-t0 .. NB-PER-t0, descending
+  int c[PER], sum = 0;
+#pragma unroll
+  for (int u = 0; u < PER / 4; ++u) {
+    const int4 v = *reinterpret_cast<const int4 *>(g + NB - 4 - t0 - 4 * u);
+    c[4 * u] = v.w; c[4 * u + 1] = v.z; c[4 * u + 2] = v.y; c[4 * u + 3] = v.x;
+    sum += v.x + v.y + v.z + v.w;
   }
   int total;
-  int before = block_exclusive_scan(sum, wsum, &total);
+  int before = block_exclusive_scan<CHUNK_THREADS>(sum, wsum, &total);
   const int want = *need;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < PER; ++q) {
     if (before < want && want <= before + c[q]) {
-      found[0] = nb - 1 - (t4 + q);
+      found[0] = NB - 1 - (t0 + q);
       found[1] = want - before;
     }
     before += c[q];
@@ -343,194 +375,270 @@ __device__ __forceinline__ int find_digit_global(const int *__restrict__ g, int 
   return found[0];
 }
 
+template <int NT>
 __device__ __forceinline__ void flush_hist(const int *hist, int nb, int *__restrict__ g) {
-  for (int i = threadIdx.x; i < nb; i += SELECT_THREADS) {
+  for (int i = threadIdx.x; i < nb; i += NT) {
     const int c = hist[i];
     if (c) atomicAdd(&g[i], c);
   }
 }
 
 // First digit, for scores that did not come with a histogram (hist1 zero on entry).
-__global__ __launch_bounds__(SELECT_THREADS, 8) void msel_hist1_kernel(const SegTable T,
+__global__ __launch_bounds__(CHUNK_THREADS, 8) void msel_hist1_kernel(const SegTable T,
                                                                     const float *__restrict__ scores,
                                                                     int *__restrict__ hist1) {
   __shared__ int hist[4096];
   const SelWhere q = sel_locate(T, blockIdx.x);
-  const Seg &s = T.s[q.w.seg];
-  const float *sp = scores + s.score_off + (long long)q.w.head * s.n;
-  uint32_t key[SEL_ROUNDS][4];
-  const unsigned valid = load_chunk_keys(sp, q, key);
-  for (int i = threadIdx.x; i < 4096; i += SELECT_THREADS) hist[i] = 0;
+  const Seg &s = T.s[q.seg];
+  const float *sp = scores + s.score_off + (long long)q.head * s.n;
+  float f[SEL_ROUNDS][4];
+  const unsigned valid = load_chunk_scores(sp, q, f);
+  for (int i = threadIdx.x; i < 4096; i += CHUNK_THREADS) hist[i] = 0;
   __syncthreads();
+  uint32_t key[SEL_ROUNDS][4];
+  scores_to_keys(f, key);
 #pragma unroll
   for (int r = 0; r < SEL_ROUNDS; ++r)
 #pragma unroll
     for (int e = 0; e < 4; ++e)
       if (valid >> (4 * r + e) & 1) atomicAdd(&hist[key[r][e] >> 20], 1);
   __syncthreads();
-  flush_hist(hist, 4096, hist1 + (size_t)q.pool * 4096);
+  flush_hist<CHUNK_THREADS>(hist, 4096, hist1 + (size_t)q.pool * 4096);
 }
 
-// Second digit (hist2 zero on entry).  The first chunk of a head also presets the head's count.
-__global__ __launch_bounds__(SELECT_THREADS, 8) void msel_hist2_kernel(const SegTable T,
-                                                                    const float *__restrict__ scores,
-                                                                    const int *__restrict__ hist1,
-                                                                    int *__restrict__ hist2,
-                                                                    int *__restrict__ state,
-                                                                    int32_t *__restrict__ kept_cnt) {
-  __shared__ int hist[4096];
-  __shared__ int wsum[SELECT_THREADS / 64];
+// Candidates of a chunk: counts the keys above the threshold's first digit and lists the low 20
+// bits of the keys inside it (cand, at the chunk's position in the launch's token sequence, so a
+// list can never outgrow its room).  rec[chunk] = (keys above, candidates listed).
+__global__ __launch_bounds__(CHUNK_THREADS, 6) void msel_cand_kernel(const SegTable T,
+                                                                  const float *__restrict__ scores,
+                                                                  const int *__restrict__ hist1,
+                                                                  uint32_t *__restrict__ cand,
+                                                                  int *__restrict__ rec,
+                                                                  int *__restrict__ state) {
+  __shared__ int wsum[CHUNK_THREADS / 64];
   __shared__ int found[2];
+  __shared__ int above_s, ncand_s;
   const SelWhere q = sel_locate(T, blockIdx.x);
-  const Seg &s = T.s[q.w.seg];
-  const float *sp = scores + s.score_off + (long long)q.w.head * s.n;
-  uint32_t key[SEL_ROUNDS][4];
-  const unsigned valid = load_chunk_keys(sp, q, key);
-  for (int i = threadIdx.x; i < 4096; i += SELECT_THREADS) hist[i] = 0;
+  const Seg &s = T.s[q.seg];
+  const float *sp = scores + s.score_off + (long long)q.head * s.n;
+  float f[SEL_ROUNDS][4];
+  const unsigned valid = load_chunk_scores(sp, q, f);    // in flight while the digit is found
+  if (threadIdx.x == 0) { above_s = 0; ncand_s = 0; }
   const int ph = pool_heads(T, s);
-  if (q.w.tile == 0 && threadIdx.x == 0)
-    kept_cnt[s.ghead0 + q.w.head] = T.layer_scope ? 0 : s.k_keep;   // layer scope: summed later
   int need = ph * s.k_keep;
-  const uint32_t d1 = find_digit_global(hist1 + (size_t)q.pool * 4096, 4096, &need, wsum, found);
-  if (q.w.tile == 0 && q.w.lhead % ph == 0 && threadIdx.x == 0) {   // the pool's first chunk
+  const uint32_t d1 = find_digit_global(hist1 + (size_t)q.pool * 4096, &need, wsum, found);
+  if (q.tile == 0 && q.lhead % ph == 0 && threadIdx.x == 0) {   // the pool's first chunk
     state[q.pool * SEL_STATE + ST_D1] = (int)d1;
     state[q.pool * SEL_STATE + ST_NEED1] = need;
   }
-#pragma unroll
-  for (int r = 0; r < SEL_ROUNDS; ++r)
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if ((valid >> (4 * r + e) & 1) && (key[r][e] >> 20) == d1)
-        atomicAdd(&hist[(key[r][e] >> 8) & 0xfff], 1);
-  __syncthreads();
-  flush_hist(hist, 4096, hist2 + (size_t)q.pool * 4096);
-}
-
-// Third digit (hist3 zero on entry) and the chunk records.
-__global__ __launch_bounds__(SELECT_THREADS, 8) void msel_hist3_kernel(const SegTable T,
-                                                                    const float *__restrict__ scores,
-                                                                    const int *__restrict__ hist2,
-                                                                    int *__restrict__ hist3,
-                                                                    int *__restrict__ state,
-                                                                    int *__restrict__ rec) {
-  __shared__ int hist[256];
-  __shared__ int wsum[SELECT_THREADS / 64];
-  __shared__ int found[2];
-  __shared__ int above_s;
-  const SelWhere q = sel_locate(T, blockIdx.x);
-  const Seg &s = T.s[q.w.seg];
-  const float *sp = scores + s.score_off + (long long)q.w.head * s.n;
+  uint32_t *list = cand + chunk_token_base(T, q);
   uint32_t key[SEL_ROUNDS][4];
-  const unsigned valid = load_chunk_keys(sp, q, key);
-  for (int i = threadIdx.x; i < 256; i += SELECT_THREADS) hist[i] = 0;
-  if (threadIdx.x == 0) above_s = 0;
-  const uint32_t d1 = (uint32_t)state[q.pool * SEL_STATE + ST_D1];
-  int need = state[q.pool * SEL_STATE + ST_NEED1];
-  const uint32_t d2 = find_digit_global(hist2 + (size_t)q.pool * 4096, 4096, &need, wsum, found);
-  if (q.w.tile == 0 && q.w.lhead % pool_heads(T, s) == 0 && threadIdx.x == 0) {
-    state[q.pool * SEL_STATE + ST_D2] = (int)d2;
-    state[q.pool * SEL_STATE + ST_NEED2] = need;
-  }
-  const uint32_t prefix = (d1 << 12) | d2;
-  int above = 0;
+  scores_to_keys(f, key);
+  const int lane = threadIdx.x & 63;
+  // A thread's candidates go to consecutive slots: count, scan inside the wave, one LDS add per
+  // wave for the wave's share of the list (the order in which waves claim theirs does not matter).
+  int above = 0, mine = 0;
 #pragma unroll
   for (int r = 0; r < SEL_ROUNDS; ++r)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      if (!(valid >> (4 * r + e) & 1)) continue;
-      const uint32_t top = key[r][e] >> 8;
-      above += top > prefix;
-      if (top == prefix) atomicAdd(&hist[key[r][e] & 0xff], 1);
+      const bool v = valid >> (4 * r + e) & 1;
+      const uint32_t top = key[r][e] >> 20;
+      above += (v && top > d1) ? 1 : 0;
+      mine += (v && top == d1) ? 1 : 0;
     }
+  int inc = mine;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  int base = 0;
+  if (lane == 63 && inc) base = atomicAdd(&ncand_s, inc);
+  int off = __shfl(base, 63) + inc - mine;
+#pragma unroll
+  for (int r = 0; r < SEL_ROUNDS; ++r)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if ((valid >> (4 * r + e) & 1) && (key[r][e] >> 20) == d1) list[off++] = key[r][e] & 0xfffffu;
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) above += __shfl_xor(above, d);
-  if ((threadIdx.x & 63) == 0 && above) atomicAdd(&above_s, above);
+  if (lane == 0 && above) atomicAdd(&above_s, above);
   __syncthreads();
-  int *r = rec + (size_t)blockIdx.x * SEL_REC;
-  if (threadIdx.x == 0) r[0] = above_s;
-  for (int i = threadIdx.x; i < 256; i += SELECT_THREADS) r[4 + i] = hist[i];
-  flush_hist(hist, 256, hist3 + (size_t)q.pool * 256);
+  if (threadIdx.x == 0) {
+    rec[2 * blockIdx.x] = above_s;
+    rec[2 * blockIdx.x + 1] = ncand_s;
+  }
 }
 
-// One workgroup per pool: the threshold key, and for every chunk of the pool (in head, token
-// order) the position of its first retained token in the pool's output and how many
-// threshold ties it may keep.
-__global__ __launch_bounds__(SELECT_THREADS) void msel_scan_kernel(const SegTable T,
-                                                                   const int *__restrict__ hist3,
-                                                                   const int *__restrict__ rec,
-                                                                   int *__restrict__ coff,
-                                                                   int *__restrict__ state,
-                                                                   int32_t *__restrict__ kept_cnt) {
-  __shared__ int wsum[SELECT_THREADS / 64];
-  __shared__ int found[2];
-  __shared__ int gt_s[SELECT_THREADS], eq_s[SELECT_THREADS];
-  // locate the pool: segment, first head, first chunk
-  const int pool = blockIdx.x;
-  int seg = 0, chunk0 = 0, head0 = 0;
-  {
-    int pbase = 0, cbase = 0;
-    for (int i = 0; i < T.nseg; ++i) {
-      const int ph = pool_heads(T, T.s[i]);
-      const int np = T.s[i].head_count / ph;
-      const int bph = blocks_per_head(T.s[i].n, SEL_CHUNK, 4);
-      if (pool < pbase + np || i == T.nseg - 1) {
-        seg = i;
-        head0 = T.s[i].head_begin + (pool - pbase) * ph;
-        chunk0 = cbase + (pool - pbase) * ph * bph;
-        break;
+// Visits the `cnt` values of a candidate list, f(value) for each: a wave's lanes take 4
+// consecutive values each with one 16-byte load (at any 4-byte address), two loads in flight.
+template <class F>
+__device__ __forceinline__ void for_each_cand(const uint32_t *__restrict__ l, int cnt, int lane, F &&f) {
+  typedef uint32_t u32x4_any __attribute__((ext_vector_type(4), aligned(4)));
+  for (int i = 4 * lane; i < cnt; i += 512) {
+    uint32_t v[2][4];
+    int have[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int j = i + 256 * h;
+      have[h] = min(4, cnt - j);
+      if (have[h] == 4) {
+        const u32x4_any t = *reinterpret_cast<const u32x4_any *>(l + j);
+        v[h][0] = t.x; v[h][1] = t.y; v[h][2] = t.z; v[h][3] = t.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[h][e] = e < have[h] ? l[j + e] : 0u;
       }
-      pbase += np;
-      cbase += bph * T.s[i].head_count;
     }
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (e < have[h]) f(v[h][e]);
   }
+}
+
+// One workgroup per pool: the threshold key from the pool's candidates, then for every chunk of
+// the pool (in head, token order) the position of its first retained token in the pool's
+// output and how many threshold ties it may keep; the per-head counts.
+// Two passes over the candidates: (1) histogram of their bits 19..8 -> second digit d2;
+// (2) per chunk the count above d2, a histogram of the low 8 bits of those inside d2, and those
+// few themselves as (chunk, low byte) in a short LDS list, from which, once the last digit is
+// known, every chunk's counts above and at the threshold follow.  If the list overflows (heavily
+// tied scores) or the pool has more than THR_BLOCK chunks, a third pass counts instead.
+// The chunks' records are fetched into LDS in blocks of THR_BLOCK (a load per chunk in turn
+// would string their latencies together); inside a block a wave takes every fourth chunk.
+constexpr int THR_THREADS = 256, THR_BLOCK = 512, THR_SHORT = 2048;
+__global__ __launch_bounds__(THR_THREADS) void msel_thr_kernel(const SegTable T,
+                                                               const uint32_t *__restrict__ cand,
+                                                               const int *__restrict__ rec,
+                                                               int *__restrict__ coff,
+                                                               int *__restrict__ state,
+                                                               int32_t *__restrict__ kept_cnt) {
+  constexpr int NW = THR_THREADS / 64;
+  __shared__ int hist[4096];
+  __shared__ int wsum[NW];
+  __shared__ int found[2];
+  __shared__ int above_c[THR_BLOCK], cnt_c[THR_BLOCK], gt_c[THR_BLOCK], eq_c[THR_BLOCK];
+  __shared__ uint32_t short_l[THR_SHORT];
+  __shared__ int nshort;
+  // locate the pool: segment, first head, first chunk, first token
+  const int pool = blockIdx.x;
+  int seg = 0;
+  for (int i = 1; i < T.nseg; ++i) seg += pool >= T.s[i].pool0;
   const Seg &s = T.s[seg];
   const int ph = pool_heads(T, s);
-  const int bph = blocks_per_head(s.n, SEL_CHUNK, 4);
+  const int bph = s.sel_bph, csize = s.sel_chunk;
+  const int head0 = s.head_begin + (pool - s.pool0) * ph;
+  const int chunk0 = s.sel_blk0 + (pool - s.pool0) * ph * bph;
+  const long long tok0 = s.tok0 + (long long)(pool - s.pool0) * ph * s.n;
   const int nchunks = ph * bph;
+  const bool single = nchunks <= THR_BLOCK;      // all records fit LDS at once
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // candidate list of chunk c of the pool
+  auto list_of = [&](int c) { return cand + tok0 + (long long)(c / bph) * s.n + (long long)(c % bph) * csize; };
+  // records of the chunks [cb, cb + THR_BLOCK) into LDS
+  auto fetch = [&](int cb) {
+    __syncthreads();
+    for (int u = tid; u < THR_BLOCK && cb + u < nchunks; u += THR_THREADS) {
+      const int2 r = *reinterpret_cast<const int2 *>(rec + 2 * (chunk0 + cb + u));
+      above_c[u] = r.x;
+      cnt_c[u] = r.y;
+    }
+    __syncthreads();
+  };
 
   const uint32_t d1 = (uint32_t)state[pool * SEL_STATE + ST_D1];
-  const uint32_t d2 = (uint32_t)state[pool * SEL_STATE + ST_D2];
-  int need = state[pool * SEL_STATE + ST_NEED2];
-  const int d3 = find_digit_global(hist3 + (size_t)pool * 256, 256, &need, wsum, found);
+  int need = state[pool * SEL_STATE + ST_NEED1];
+
+  // pass 1: bits 19..8 of every candidate
+  for (int i = tid; i < 4096; i += THR_THREADS) hist[i] = 0;
+  if (tid == 0) nshort = 0;
+  for (int cb = 0; cb < nchunks; cb += THR_BLOCK) {
+    fetch(cb);
+    for (int u = wave; u < THR_BLOCK && cb + u < nchunks; u += NW)
+      for_each_cand(list_of(cb + u), cnt_c[u], lane,
+                    [&](uint32_t v) { atomicAdd(&hist[(v >> 8) & 0xfffu], 1); });
+  }
+  __syncthreads();
+  const uint32_t d2 = (uint32_t)find_digit<THR_THREADS>(hist, 4096, &need, wsum, found);
+  // pass 2: bits 7..0 of the candidates that share the second digit; per chunk those above it
+  for (int i = tid; i < 256; i += THR_THREADS) hist[i] = 0;
+  for (int cb = 0; cb < nchunks; cb += THR_BLOCK) {
+    if (!single) fetch(cb); else __syncthreads();
+    for (int u = wave; u < THR_BLOCK && cb + u < nchunks; u += NW) {
+      int gt = 0;
+      for_each_cand(list_of(cb + u), cnt_c[u], lane, [&](uint32_t v) {
+        const uint32_t top = v >> 8;
+        gt += top > d2;
+        if (top == d2) {
+          atomicAdd(&hist[v & 0xffu], 1);
+          if (single) {
+            const int at = atomicAdd(&nshort, 1);
+            if (at < THR_SHORT) short_l[at] = ((uint32_t)u << 8) | (v & 0xffu);
+          }
+        }
+      });
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) gt += __shfl_xor(gt, d);
+      if (lane == 0) { gt_c[u] = gt; eq_c[u] = 0; }
+    }
+  }
+  __syncthreads();
+  const uint32_t d3 = (uint32_t)find_digit<THR_THREADS>(hist, 256, &need, wsum, found);
   const int tie_keep = need;             // keys equal to the threshold that are retained
-  if (threadIdx.x == 0) {
-    state[pool * SEL_STATE + ST_THR] = (int)((d1 << 20) | (d2 << 8) | (uint32_t)d3);
+  const uint32_t thr20 = (d2 << 8) | d3;
+  if (tid == 0) {
+    state[pool * SEL_STATE + ST_THR] = (int)((d1 << 20) | thr20);
     state[pool * SEL_STATE + ST_TIES] = tie_keep;
   }
+  const bool from_short = single && nshort <= THR_SHORT;
+  if (from_short) {                      // the chunks' counts at the last digit, from the short list
+    for (int i = tid; i < nshort; i += THR_THREADS) {
+      const uint32_t e = short_l[i];
+      const uint32_t low = e & 0xffu;
+      if (low > d3) atomicAdd(&gt_c[e >> 8], 1);
+      else if (low == d3) atomicAdd(&eq_c[e >> 8], 1);
+    }
+  }
 
-  int carry_kept = 0, carry_eq = 0;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int base = 0; base < nchunks; base += SELECT_THREADS) {
-    // a wave per chunk record: keys above the threshold and equal to it
-    __syncthreads();
-    for (int c = base + wave; c < min(nchunks, base + SELECT_THREADS); c += SELECT_THREADS / 64) {
-      const int *r = rec + (size_t)(chunk0 + c) * SEL_REC;
-      const int4 v = *reinterpret_cast<const int4 *>(r + 4 + 4 * lane);
-      const int b0 = 4 * lane;
-      int g = (b0 > d3 ? v.x : 0) + (b0 + 1 > d3 ? v.y : 0) + (b0 + 2 > d3 ? v.z : 0) +
-              (b0 + 3 > d3 ? v.w : 0);
+  // every chunk's output position and tie allowance: thread 0 runs the prefix over the chunks in
+  // order, a block at a time
+  int pos = 0, eq_before = 0, head_kept = 0;
+  for (int cb = 0; cb < nchunks; cb += THR_BLOCK) {
+    if (!from_short) {                   // pass 3: count against the full threshold
+      if (!single) fetch(cb); else __syncthreads();
+      for (int u = wave; u < THR_BLOCK && cb + u < nchunks; u += NW) {
+        int gt = 0, eq = 0;
+        for_each_cand(list_of(cb + u), cnt_c[u], lane, [&](uint32_t v) {
+          gt += v > thr20;
+          eq += v == thr20;
+        });
 #pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) g += __shfl_xor(g, d);
-      if (lane == 0) {
-        gt_s[c - base] = g + r[0];
-        eq_s[c - base] = r[4 + d3];
+        for (int d = 32; d >= 1; d >>= 1) {
+          gt += __shfl_xor(gt, d);
+          eq += __shfl_xor(eq, d);
+        }
+        if (lane == 0) { gt_c[u] = gt; eq_c[u] = eq; }
       }
     }
     __syncthreads();
-    const int c = base + threadIdx.x;
-    const int gt = c < nchunks ? gt_s[threadIdx.x] : 0, eq = c < nchunks ? eq_s[threadIdx.x] : 0;
-    int tot_eq, tot_kept;
-    const int eq_before = carry_eq + block_exclusive_scan(eq, wsum, &tot_eq);
-    const int allow = max(0, min(eq, tie_keep - eq_before));
-    const int kept = gt + allow;
-    const int pos = carry_kept + block_exclusive_scan(kept, wsum, &tot_kept);
-    if (c < nchunks) {
-      coff[2 * (chunk0 + c)] = pos;
-      coff[2 * (chunk0 + c) + 1] = allow;
-      if (T.layer_scope && kept) atomicAdd(&kept_cnt[s.ghead0 + head0 + c / bph], kept);
+    if (tid == 0) {
+      for (int u = 0; u < THR_BLOCK && cb + u < nchunks; ++u) {
+        const int cc = cb + u;
+        const int allow = max(0, min(eq_c[u], tie_keep - eq_before));
+        const int kept = above_c[u] + gt_c[u] + allow;
+        *reinterpret_cast<int2 *>(coff + 2 * (chunk0 + cc)) = make_int2(pos, allow);
+        pos += kept;
+        eq_before += eq_c[u];
+        head_kept += kept;
+        if ((cc + 1) % bph == 0) {       // last chunk of a head
+          kept_cnt[s.ghead0 + head0 + cc / bph] = T.layer_scope ? head_kept : s.k_keep;
+          head_kept = 0;
+        }
+      }
     }
-    carry_eq += tot_eq;
-    carry_kept += tot_kept;
   }
 }
 
@@ -538,28 +646,31 @@ __global__ __launch_bounds__(SELECT_THREADS) void msel_scan_kernel(const SegTabl
 // token's output position is the sum of four prefixes: rounds before it, waves before it in its
 // round, lanes before it in its wave, elements before it in its lane.  The lane prefix is a
 // wave scan, the other two come from one table of (round, wave) counts scanned once: two
-// workgroup barriers in all.  Counts are packed as (above | equal << 16), at most 32768 each.
-__global__ __launch_bounds__(SELECT_THREADS, 8) void msel_emit_kernel(const SegTable T,
+// workgroup barriers in all.  Counts are packed as (above | equal << 16), at most 8192 each.
+__global__ __launch_bounds__(CHUNK_THREADS, 6) void msel_emit_kernel(const SegTable T,
                                                                    const float *__restrict__ scores,
                                                                    const int *__restrict__ coff,
                                                                    const int *__restrict__ state,
                                                                    int32_t *__restrict__ kept_idx) {
-  constexpr int NW = SELECT_THREADS / 64;
-  constexpr int EMIT_STAGE = 16384;
+  constexpr int NW = CHUNK_THREADS / 64;
+  constexpr int EMIT_STAGE = 4096;
   __shared__ unsigned table[SEL_ROUNDS * NW];
   __shared__ unsigned total_s;
   __shared__ int stage[EMIT_STAGE];
   const SelWhere q = sel_locate(T, blockIdx.x);
-  const Seg &s = T.s[q.w.seg];
-  const float *sp = scores + s.score_off + (long long)q.w.head * s.n;
-  uint32_t key[SEL_ROUNDS][4];
-  const unsigned valid = load_chunk_keys(sp, q, key);
+  const Seg &s = T.s[q.seg];
+  const float *sp = scores + s.score_off + (long long)q.head * s.n;
+  float f[SEL_ROUNDS][4];
+  const unsigned valid = load_chunk_scores(sp, q, f);    // in flight with the three loads below
   const int ph = pool_heads(T, s);
   const int limit = ph * s.k_keep;                       // rows of the pool's output
-  int32_t *out = kept_idx + (s.kept_off + (long long)(q.w.head / ph) * limit);
+  int32_t *out = kept_idx + (s.kept_off + (long long)(q.head / ph) * limit);
   const uint32_t thr = (uint32_t)state[q.pool * SEL_STATE + ST_THR];
-  const int pos0 = coff[2 * blockIdx.x], allow = coff[2 * blockIdx.x + 1];
+  const int2 pa = *reinterpret_cast<const int2 *>(coff + 2 * blockIdx.x);
+  const int pos0 = pa.x, allow = pa.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t key[SEL_ROUNDS][4];
+  scores_to_keys(f, key);
 
   unsigned before[SEL_ROUNDS];      // packed counts of the lanes before this one, per round
 #pragma unroll
@@ -610,10 +721,10 @@ __global__ __launch_bounds__(SELECT_THREADS, 8) void msel_emit_kernel(const SegT
   // written out as one run (what does not fit the stage goes straight to memory)
 #pragma unroll
   for (int r = 0; r < SEL_ROUNDS; ++r) {
-    if (q.tok_begin + 4 * r * SELECT_THREADS >= q.tok_end) break;      // uniform
+    if (q.tok_begin + 4 * r * CHUNK_THREADS >= q.tok_end) break;       // uniform
     const unsigned p = table[r * NW + wave] + before[r];
     int pg = (int)(p & 0xffffu), pe = (int)(p >> 16);
-    const int i0 = q.tok_begin + 4 * (r * SELECT_THREADS + (int)threadIdx.x);
+    const int i0 = q.tok_begin + 4 * (r * CHUNK_THREADS + (int)threadIdx.x);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       if (valid >> (4 * r + e) & 1) {
@@ -631,48 +742,107 @@ __global__ __launch_bounds__(SELECT_THREADS, 8) void msel_emit_kernel(const SegT
   __syncthreads();
   const int total = (int)(total_s & 0xffffu) + min((int)(total_s >> 16), allow);
   const int staged = min(min(total, EMIT_STAGE), limit - pos0);
-  for (int j = threadIdx.x; j < staged; j += SELECT_THREADS) out[pos0 + j] = stage[j];
+  for (int j = threadIdx.x; j < staged; j += CHUNK_THREADS) out[pos0 + j] = stage[j];
 }
 
-// ---- blend: s = z(a) + lambda z(o), population standard deviation, fp64 statistics --------
-__device__ __forceinline__ double block_sum(double v, double *wd) {
+// ---- blend: s = z(a) + lambda z(o) (paper Eq. "scoring"), population standard deviation ------
+// The sums that the two standardisations need are gathered on the way: those of o per score
+// workgroup in the score kernel's epilogue (ostat), those of a by blend_stats_kernel, one pair
+// per chunk of 8192 tokens (astat); both as fp64 (sum, sum of squares), a shifted by the head's
+// first element so that a nearly constant vector does not cancel.  blend_apply_kernel then adds
+// a head's pairs up in index order (every chunk of the head gets the same mean and deviation,
+// bit for bit), rewrites the scores in place and tallies the first selection histogram.
+__device__ __forceinline__ void block_sum2(double &x, double &y, double (*wd)[2]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+  for (int d = 32; d >= 1; d >>= 1) {
+    x += __shfl_xor(x, d);
+    y += __shfl_xor(y, d);
+  }
   __syncthreads();
-  if (lane == 0) wd[wave] = v;
+  if (lane == 0) { wd[wave][0] = x; wd[wave][1] = y; }
   __syncthreads();
-  double t = 0.0;
+  double tx = 0.0, ty = 0.0;
 #pragma unroll
-  for (int i = 0; i < SELECT_THREADS / 64; ++i) t += wd[i];
-  return t;
+  for (int i = 0; i < CHUNK_THREADS / 64; ++i) { tx += wd[i][0]; ty += wd[i][1]; }
+  x = tx;
+  y = ty;
 }
 
-__global__ __launch_bounds__(SELECT_THREADS) void blend_kernel(const SegTable T, float lambda,
-                                                               float *__restrict__ scores) {
-  __shared__ double wd[SELECT_THREADS / 64];
-  const Where w = locate_block(T, blockIdx.x, 0, 1, false);
-  const Seg &s = T.s[w.seg];
+__global__ __launch_bounds__(CHUNK_THREADS) void blend_stats_kernel(const SegTable T,
+                                                                    double *__restrict__ astat) {
+  __shared__ double wd[CHUNK_THREADS / 64][2];
+  const SelWhere q = sel_locate(T, blockIdx.x);
+  const Seg &s = T.s[q.seg];
+  if (s.attn == nullptr) return;
+  const float *a = s.attn + (long long)q.head * s.n;
+  const double shift = (double)a[0];
+  double s1 = 0.0, s2 = 0.0;
+  for (int i = q.tok_begin + (int)threadIdx.x; i < q.tok_end; i += CHUNK_THREADS) {
+    const double x = (double)a[i] - shift;
+    s1 += x;
+    s2 += x * x;
+  }
+  block_sum2(s1, s2, wd);
+  if (threadIdx.x == 0) {
+    astat[2 * (size_t)blockIdx.x] = s1;
+    astat[2 * (size_t)blockIdx.x + 1] = s2;
+  }
+}
+
+// Mean and reciprocal deviation from `count` (sum, sum of squares) pairs, added in index order.
+__device__ __forceinline__ void moments(const double *__restrict__ pairs, int count, int n,
+                                        double shift, double (*wd)[2], double &mean, double &inv_sd) {
+  double s1 = 0.0, s2 = 0.0;
+  for (int i = threadIdx.x; i < count; i += CHUNK_THREADS) {
+    s1 += pairs[2 * i];
+    s2 += pairs[2 * i + 1];
+  }
+  block_sum2(s1, s2, wd);
+  const double m = s1 / n;
+  double var = s2 / n - m * m;
+  if (!(var > 0.0)) var = 0.0;
+  mean = shift + m;
+  // a constant vector (deviation 0) contributes nothing
+  inv_sd = var > 0.0 ? 1.0 / sqrt(var) : 0.0;
+}
+
+// Where a segment's pairs start in ostat (its first score workgroup) and how many a head has.
+struct OstatIndex {
+  long long first[MAX_SEG];
+  int per_head[MAX_SEG];
+};
+__global__ __launch_bounds__(CHUNK_THREADS) void blend_apply_kernel(
+    const SegTable T, const OstatIndex X, float lambda, float *__restrict__ scores,
+    const double *__restrict__ ostat, const double *__restrict__ astat, int *__restrict__ hist1) {
+  __shared__ double wd[CHUNK_THREADS / 64][2];
+  __shared__ int hist[HIST1_BINS];
+  const SelWhere q = sel_locate(T, blockIdx.x);
+  const Seg &s = T.s[q.seg];
   if (s.attn == nullptr) return;
   const int n = s.n, tid = threadIdx.x;
-  float *o = scores + s.score_off + (long long)w.head * n;
-  const float *a = s.attn + (long long)w.head * n;
-
-  double so = 0.0, sa = 0.0;
-  for (int i = tid; i < n; i += SELECT_THREADS) { so += o[i]; sa += a[i]; }
-  const double mo = block_sum(so, wd) / n, ma = block_sum(sa, wd) / n;
-  double vo = 0.0, va = 0.0;
-  for (int i = tid; i < n; i += SELECT_THREADS) {
-    const double x = o[i] - mo, y = a[i] - ma;
-    vo += x * x;
-    va += y * y;
+  float *o = scores + s.score_off + (long long)q.head * n;
+  const float *a = s.attn + (long long)q.head * n;
+  // where the head's pairs start: its first score workgroup, its first chunk
+  const int obph = X.per_head[q.seg], abph = s.sel_bph;
+  const long long ob = X.first[q.seg] + (long long)(q.head - s.head_begin) * obph;
+  const long long ab = (long long)blockIdx.x - q.tile;
+  double mo, io, ma, ia;
+  moments(ostat + 2 * ob, obph, n, 0.0, wd, mo, io);
+  moments(astat + 2 * ab, abph, n, (double)a[0], wd, ma, ia);
+  io *= (double)lambda;
+  if (hist1 != nullptr)
+    for (int i = tid; i < HIST1_BINS; i += CHUNK_THREADS) hist[i] = 0;
+  __syncthreads();
+  for (int i = q.tok_begin + tid; i < q.tok_end; i += CHUNK_THREADS) {
+    const float v = (float)(((double)a[i] - ma) * ia + ((double)o[i] - mo) * io);
+    o[i] = v;
+    if (hist1 != nullptr) atomicAdd(&hist[score_key(v) >> 20], 1);
   }
-  const double sdo = sqrt(block_sum(vo, wd) / n), sda = sqrt(block_sum(va, wd) / n);
-  // a constant vector (std 0) contributes nothing
-  const double io = sdo > 0.0 ? (double)lambda / sdo : 0.0;
-  const double ia = sda > 0.0 ? 1.0 / sda : 0.0;
-  for (int i = tid; i < n; i += SELECT_THREADS)
-    o[i] = (float)((a[i] - ma) * ia + (o[i] - mo) * io);
+  if (hist1 != nullptr) {
+    __syncthreads();
+    flush_hist<CHUNK_THREADS>(hist, HIST1_BINS, hist1 + (size_t)q.pool * HIST1_BINS);
+  }
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(int *__restrict__ z, long long count) {
@@ -688,47 +858,44 @@ bool select_needs_pools(const SegTable &T) {
 
 SelectScratch select_scratch(const SegTable &T) {
   SelectScratch z;
-  long long pools = 0;
-  for (int i = 0; i < T.nseg; ++i) pools += T.s[i].head_count / pool_heads(T, T.s[i]);
+  long long pools = 0, rows = 0;
+  for (int i = 0; i < T.nseg; ++i) {
+    pools += T.s[i].head_count / pool_heads(T, T.s[i]);
+    rows += (long long)T.s[i].n * T.s[i].head_count;
+  }
   z.pools = (int)pools;
   z.chunks = total_blocks(T, SEL_CHUNK, 4, false);
-  z.hist2_ints = pools * 4096;
-  z.hist3_ints = pools * 256;
-  z.rec_ints = z.chunks * SEL_REC;
+  z.cand_ints = rows;
+  z.rec_ints = z.chunks * 2;
   z.coff_ints = z.chunks * 2;
-  z.thr_ints = pools * SEL_STATE;
+  z.state_ints = pools * SEL_STATE;
   return z;
 }
 
+long long select_chunks(const SegTable &T) { return total_blocks(T, SEL_CHUNK, 4, false); }
+
 hipError_t launch_select_pools(const SegTable &T, const float *scores, int *hist1, bool hist1_ready,
-                               int *sel, bool zeroed, int32_t *kept_idx, int32_t *kept_cnt,
-                               hipStream_t st) {
+                               int *sel, int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st) {
   if (T.nheads <= 0) return hipSuccess;
   const SelectScratch z = select_scratch(T);
   if (z.chunks > 0x7fffffffll) return hipErrorInvalidValue;
-  int *hist2 = sel, *hist3 = hist2 + z.hist2_ints, *rec = hist3 + z.hist3_ints;
-  int *coff = rec + z.rec_ints;
-  int *state = coff + z.coff_ints;
+  uint32_t *cand = reinterpret_cast<uint32_t *>(sel);
+  int *rec = sel + z.cand_ints, *coff = rec + z.rec_ints, *state = coff + z.coff_ints;
   const unsigned nb = (unsigned)z.chunks;
-  if (!zeroed) {       // hist1 .. hist3 are contiguous
-    const long long cnt = (hist3 + z.hist3_ints) - hist1;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, st, hist1, cnt);
-    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-  }
   if (!hist1_ready) {
-    hipLaunchKernelGGL(msel_hist1_kernel, dim3(nb), dim3(SELECT_THREADS), 0, st, T, scores, hist1);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, st, hist1,
+                       (long long)z.pools * HIST1_BINS);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    hipLaunchKernelGGL(msel_hist1_kernel, dim3(nb), dim3(CHUNK_THREADS), 0, st, T, scores, hist1);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   }
-  hipLaunchKernelGGL(msel_hist2_kernel, dim3(nb), dim3(SELECT_THREADS), 0, st, T, scores, hist1,
-                     hist2, state, kept_cnt);
+  hipLaunchKernelGGL(msel_cand_kernel, dim3(nb), dim3(CHUNK_THREADS), 0, st, T, scores, hist1, cand,
+                     rec, state);
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-  hipLaunchKernelGGL(msel_hist3_kernel, dim3(nb), dim3(SELECT_THREADS), 0, st, T, scores, hist2,
-                     hist3, state, rec);
+  hipLaunchKernelGGL(msel_thr_kernel, dim3((unsigned)z.pools), dim3(THR_THREADS), 0, st, T, cand,
+                     rec, coff, state, kept_cnt);
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-  hipLaunchKernelGGL(msel_scan_kernel, dim3((unsigned)z.pools), dim3(SELECT_THREADS), 0, st, T,
-                     hist3, rec, coff, state, kept_cnt);
-  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-  hipLaunchKernelGGL(msel_emit_kernel, dim3(nb), dim3(SELECT_THREADS), 0, st, T, scores, coff,
+  hipLaunchKernelGGL(msel_emit_kernel, dim3(nb), dim3(CHUNK_THREADS), 0, st, T, scores, coff,
                      state, kept_idx);
   return hipGetLastError();
 }
@@ -742,12 +909,28 @@ hipError_t launch_select(const SegTable &T, const float *scores, const int *hist
   return hipGetLastError();
 }
 
-hipError_t launch_blend(const SegTable &T, float lambda, float *scores, hipStream_t st) {
-  bool any = false;
-  for (int i = 0; i < T.nseg; ++i) any |= T.s[i].attn != nullptr;
-  if (!any || T.nheads <= 0) return hipSuccess;
-  hipLaunchKernelGGL(blend_kernel, dim3((unsigned)T.nheads), dim3(SELECT_THREADS), 0, st, T,
-                     lambda, scores);
+bool blend_wanted(const SegTable &T) {
+  for (int i = 0; i < T.nseg; ++i)
+    if (T.s[i].attn != nullptr) return true;
+  return false;
+}
+
+hipError_t launch_blend(const SegTable &T, float lambda, int score_tokens, float *scores,
+                        const double *ostat, double *astat, int *hist1, hipStream_t st) {
+  if (!blend_wanted(T) || T.nheads <= 0) return hipSuccess;
+  const long long nb = select_chunks(T);
+  if (nb > 0x7fffffffll) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(blend_stats_kernel, dim3((unsigned)nb), dim3(CHUNK_THREADS), 0, st, T, astat);
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  OstatIndex X;
+  long long ob = 0;
+  for (int i = 0; i < MAX_SEG; ++i) {
+    X.first[i] = ob;
+    X.per_head[i] = i < T.nseg ? blocks_per_head(T.s[i].n, score_tokens, SCORE_STEP) : 0;
+    if (i < T.nseg) ob += (long long)X.per_head[i] * T.s[i].head_count;
+  }
+  hipLaunchKernelGGL(blend_apply_kernel, dim3((unsigned)nb), dim3(CHUNK_THREADS), 0, st, T, X, lambda,
+                     scores, ostat, astat, hist1);
   return hipGetLastError();
 }
 
