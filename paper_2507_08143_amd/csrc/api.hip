@@ -94,14 +94,15 @@ GramPlan gram_plan(const compactor_params_t *p, const SegTable &T, int cus) {
 // of W workgroups takes ceil(W / slots) rounds; the run length is chosen to keep the last
 // round full and the per-workgroup fixed cost (staging W^T, about 32 KB) small.
 int score_tokens_for(const compactor_params_t *p, const SegTable &T, int cus) {
-  if (p->score_tokens > 0) {           // at most SCORE_MAX_TOKENS: a workgroup's scores wait in LDS
+  const int cap = p->sketch_dim == 0 ? SCORE_EXACT_MAX_TOKENS : SCORE_MAX_TOKENS;
+  if (p->score_tokens > 0) {           // at most `cap`: a workgroup's scores wait in LDS
     const int t = (p->score_tokens + SCORE_STEP - 1) / SCORE_STEP * SCORE_STEP;
-    return t > SCORE_MAX_TOKENS ? SCORE_MAX_TOKENS : t;
+    return t > cap ? cap : t;
   }
   const int slots = 2 * cus;
-  int best = SCORE_MAX_TOKENS;
+  int best = cap;
   double best_score = -1.0;
-  for (int c = SCORE_MAX_TOKENS; c >= 1024; c -= SCORE_STEP) {
+  for (int c = cap; c >= 1024; c -= SCORE_STEP) {
     const double w = (double)total_blocks(T, c, SCORE_STEP, false);
     const double rounds = ceil(w / slots);
     const double score = w / (rounds * slots) * (c * 256.0) / (c * 256.0 + 32768.0);
@@ -111,9 +112,9 @@ int score_tokens_for(const compactor_params_t *p, const SegTable &T, int cus) {
 }
 
 struct GroupBytes {
-  size_t partials, g64, wt, hist1, sel, bstat, scores;   // in this order in the workspace
-  size_t total() const { return partials + g64 + wt + hist1 + sel + bstat + scores; }
-  size_t off_wt() const { return partials + g64; }
+  size_t partials, wt, hist1, sel, bstat, scores;   // in this order in the workspace
+  size_t total() const { return partials + wt + hist1 + sel + bstat + scores; }
+  size_t off_wt() const { return partials; }
   size_t off_hist1() const { return off_wt() + wt; }
   size_t off_sel() const { return off_hist1() + hist1; }
   size_t off_bstat() const { return off_sel() + sel; }
@@ -128,7 +129,6 @@ GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bo
   GroupBytes g;
   g.partials = align_up(((size_t)gram_plan(p, T, compute_units()).nwg + T.nheads) *
                         GRAM_PARTIAL_FLOATS * sizeof(float));
-  g.g64 = ks > 0 ? 0 : align_up((size_t)T.nheads * D * D * sizeof(double));   // exact mode only
   g.wt = align_up((size_t)T.nheads * W_TERMS * m * D * sizeof(uint16_t));
   g.hist1 = align_up((size_t)T.nheads * HIST1_BINS * sizeof(int));
   g.sel = select_needs_pools(T) ? align_up((size_t)select_scratch(T).ints() * sizeof(int)) : 0;
@@ -251,7 +251,6 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
                   int32_t *status, unsigned char *ws, hipStream_t st, bool want_hist1) {
   const GroupBytes gb = group_bytes_needed(p, T, false);
   float *partials = reinterpret_cast<float *>(ws);
-  double *g64 = reinterpret_cast<double *>(ws + gb.partials);
   uint16_t *wt = reinterpret_cast<uint16_t *>(ws + gb.off_wt());
   int *hist1 = want_hist1 ? reinterpret_cast<int *>(ws + gb.off_hist1()) : nullptr;
   double *ostat = gb.bstat ? reinterpret_cast<double *>(ws + gb.off_bstat()) : nullptr;
@@ -265,14 +264,12 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   MARK(m, 0);
   HIP_TRY(launch_gram(T, gp.nwg, gp.tiles_per_wg, partials, st));
   MARK(m, COMPACTOR_STAGE_GRAM + 1);
+  MARK(m, COMPACTOR_STAGE_REDUCE + 1);       // the fp64 sum of the partials is part of the next kernel
   if (p->sketch_dim > 0) {
-    hipEvent_t mid = m.ev ? static_cast<hipEvent_t>(m.ev[COMPACTOR_STAGE_REDUCE + 1]) : nullptr;
     HIP_TRY(launch_sketch_solve(T, p->sketch_dim, rpw, partials, p->phi, p->ridge_rel, wt, status,
-                                zero, zero_ints, st, mid));
+                                zero, zero_ints, st));
   } else {
-    HIP_TRY(launch_gram_reduce(T, rpw, partials, g64, zero, zero_ints, st));
-    MARK(m, COMPACTOR_STAGE_REDUCE + 1);
-    HIP_TRY(launch_solve(T, p->ridge_rel, g64, wt, status, st));
+    HIP_TRY(launch_exact_solve(T, rpw, partials, p->ridge_rel, wt, status, zero, zero_ints, st));
   }
   MARK(m, COMPACTOR_STAGE_SOLVE + 1);
   const int score_tokens = score_tokens_for(p, T, cus);

@@ -21,6 +21,7 @@ constexpr int GRAM_PARTIAL_FLOATS = 10 * 32 * 32;   // upper blocks of one parti
 constexpr int GRAM_TILE = 64;         // rows staged in LDS per step of the Gram kernel
 constexpr int SCORE_STEP = 128;       // tokens a score workgroup multiplies per step
 constexpr int SCORE_MAX_TOKENS = 4096;   // most tokens a score workgroup takes (their scores wait in LDS)
+constexpr int SCORE_EXACT_MAX_TOKENS = 2048;   // the same in exact mode, where W^T takes more of the LDS
 constexpr int SELECT_THREADS = 1024;
 constexpr int SEL_CHUNK = 8192;       // tokens per workgroup of the chunked selection and blend
                                       // kernels (chunks never cross heads)
@@ -269,22 +270,18 @@ __device__ __forceinline__ long long partial_base(const SegTable &T, int lhead, 
 hipError_t launch_gram(const SegTable &T, int nwg, int tiles_per_wg, float *partials,
                        hipStream_t st);
 
-// G64[lhead] = sum over splits of the head's partials, in fp64.
+// Exact mode: partial Gram blocks -> G + rho I -> Cholesky -> W^T = L^{-1} (as W_TERMS bf16
+// planes, [term][128][128] per head) and the status word, in one kernel.
 // zero[0, zero_ints) is cleared on the way (selection histograms), if not null.
-hipError_t launch_gram_reduce(const SegTable &T, int tiles_per_wg, const float *partials,
-                              double *g64, int *zero, long long zero_ints, hipStream_t st);
-
-// Exact mode: factor G + rho I and emit W^T (as W_TERMS bf16 planes, [term][128][128] per head)
-// and the status word.
-hipError_t launch_solve(const SegTable &T, float ridge_rel, const double *g64, uint16_t *wt,
-                        int32_t *status, hipStream_t st);
+hipError_t launch_exact_solve(const SegTable &T, int tiles_per_wg, const float *partials,
+                              float ridge_rel, uint16_t *wt, int32_t *status, int *zero,
+                              long long zero_ints, hipStream_t st);
 
 // Sketched mode: partial Gram blocks -> S = Phi^T G Phi + rho I -> W^T ([term][k_s][128] per
-// head) and status, in one kernel.  `mid`, if not null, is recorded before it.
+// head) and status, in one kernel.
 hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, const float *partials,
                                const float *phi, float ridge_rel, uint16_t *wt,
-                               int32_t *status, int *zero, long long zero_ints, hipStream_t st,
-                               hipEvent_t mid);
+                               int32_t *status, int *zero, long long zero_ints, hipStream_t st);
 
 // phi[128][ks] = sqrt(128/ks) * D H[cols]^T (signs, cols: host arrays, copied into the launch)
 hipError_t launch_srht_phi(int ks, const uint8_t *signs, const int32_t *cols, float *phi,

@@ -209,60 +209,12 @@ __global__ __launch_bounds__(256, GRAM_OCC) void gram_kernel(const SegTable T, i
   }
 }
 
-// Order in which the waves own the upper blocks, as (I, J) per stored block number.
-__device__ __constant__ int kBlockI[10] = {0, 0, 0, 0, 1, 1, 1, 2, 2, 3};
-__device__ __constant__ int kBlockJ[10] = {0, 1, 2, 3, 1, 2, 3, 2, 3, 3};
-
-// G64 = sum of a head's partials in fp64, in split order (deterministic), written as the full
-// symmetric 128 x 128 matrix: one workgroup per (head, upper block), the mirror image goes
-// through an LDS transpose so that both stores are coalesced.
-__global__ __launch_bounds__(256) void gram_reduce_kernel(const SegTable T, int tiles_per_wg,
-                                                          const float *__restrict__ partials,
-                                                          double *__restrict__ g64,
-                                                          int *__restrict__ zero,
-                                                          long long zero_ints) {
-  __shared__ double tile[32][33];
-  const int lhead = blockIdx.x / 10;
-  const int blk = blockIdx.x - lhead * 10;
-  zero_slice(zero, zero_ints);   // histograms that the score and selection kernels add into
-  int nsplit;
-  const long long pb = partial_base(T, lhead, tiles_per_wg, nsplit);
-  const int e = threadIdx.x * 4;                 // this thread's float4 of the block
-  int row0, col;
-  partial_quad(threadIdx.x, row0, col);          // it holds rows row0 .. row0+3 of column col
-  double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
-  for (int sidx = 0; sidx < nsplit; ++sidx) {
-    const float4 p = *reinterpret_cast<const float4 *>(partials + (pb + sidx) * (10 * GBLK) +
-                                                       blk * GBLK + e);
-    a0 += p.x; a1 += p.y; a2 += p.z; a3 += p.w;
-  }
-  const int I = kBlockI[blk], J = kBlockJ[blk];
-  double *G = g64 + (size_t)lhead * (D * D);
-  double *o = G + (32 * I + row0) * D + 32 * J + col;
-  o[0] = a0; o[D] = a1; o[2 * D] = a2; o[3 * D] = a3;
-  if (I != J) {
-    tile[row0][col] = a0; tile[row0 + 1][col] = a1; tile[row0 + 2][col] = a2; tile[row0 + 3][col] = a3;
-    __syncthreads();
-    double *m = G + (32 * J + row0) * D + 32 * I + col;   // G[32J + r][32I + c] = block[c][r]
-    m[0] = tile[col][row0]; m[D] = tile[col][row0 + 1]; m[2 * D] = tile[col][row0 + 2];
-    m[3 * D] = tile[col][row0 + 3];
-  }
-}
-
 hipError_t launch_gram(const SegTable &T, int nwg, int tiles_per_wg, float *partials,
                        hipStream_t st) {
   const long long total = total_tiles(T);
   if (total <= 0 || nwg <= 0) return hipSuccess;
   hipLaunchKernelGGL(gram_kernel, dim3((unsigned)nwg), dim3(256), 0, st, T, tiles_per_wg, total,
                      partials);
-  return hipGetLastError();
-}
-
-hipError_t launch_gram_reduce(const SegTable &T, int tiles_per_wg, const float *partials,
-                              double *g64, int *zero, long long zero_ints, hipStream_t st) {
-  if (T.nheads <= 0) return hipSuccess;
-  hipLaunchKernelGGL(gram_reduce_kernel, dim3((unsigned)T.nheads * 10), dim3(256), 0, st, T,
-                     tiles_per_wg, partials, g64, zero, zero_ints);
   return hipGetLastError();
 }
 

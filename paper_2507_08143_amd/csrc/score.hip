@@ -19,6 +19,39 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int WPITCH = 136;   // bf16 per LDS row of W^T and of staged key rows (272 B)
 
+// LDS layout of the W^T planes.  Sketched mode: k_s full rows of 128 channels.  Exact mode
+// (M = 128): W^T = L^{-1} is lower triangular, row j is zero beyond channel j, so rows are kept in
+// four groups of 32 with 32, 64, 96 and 128 channels (a third less LDS, which is what lets two
+// workgroups share a CU, and 20 of 32 channel blocks to multiply).  Each row carries 16 bytes of
+// padding: consecutive rows are then 20, 36, 52 or 68 banks apart and the 16 rows an MFMA
+// operand read touches fall on distinct banks.
+template <int M>
+struct WLayout {
+  static constexpr int PLANE = M * WPITCH;                       // bf16 per plane
+  static constexpr int MAX_TOKENS = SCORE_MAX_TOKENS;            // scores of a workgroup wait in LDS
+  __device__ static __forceinline__ int row(int r) { return r * WPITCH; }
+  __device__ static __forceinline__ int blocks(int /*jb*/) { return 4; }   // 32-channel blocks of a row
+  static constexpr int CHUNKS = M * 16;                          // 16-byte pieces per plane
+  __device__ static __forceinline__ void piece(int c, int &r, int &ch) { r = c >> 4; ch = c & 15; }
+};
+template <>
+struct WLayout<128> {
+  static constexpr int PLANE = 32 * (40 + 72 + 104 + 136);      // 11264 bf16
+  static constexpr int MAX_TOKENS = SCORE_EXACT_MAX_TOKENS;
+  __device__ static __forceinline__ int row(int r) {
+    const int g = r >> 5;
+    return 1280 * g + 512 * g * (g - 1) + (r & 31) * (40 + 32 * g);
+  }
+  __device__ static __forceinline__ int blocks(int jb) { return (jb >> 1) + 1; }
+  static constexpr int CHUNKS = 32 * (4 + 8 + 12 + 16);          // 1280
+  __device__ static __forceinline__ void piece(int c, int &r, int &ch) {
+    if (c < 128)      { r = c >> 2;               ch = c & 3; }
+    else if (c < 384) { r = 32 + ((c - 128) >> 3); ch = (c - 128) & 7; }
+    else if (c < 768) { r = 64 + (c - 384) / 12;   ch = (c - 384) % 12; }
+    else              { r = 96 + ((c - 768) >> 4); ch = (c - 768) & 15; }
+  }
+};
+
 __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -31,12 +64,13 @@ __device__ __forceinline__ void wave_lds_fence() {
 // MFMA B-operand arrangement; two steps of loads are in flight while a third is multiplied.
 // Nothing in the loop needs a workgroup barrier: a wave only reads what it wrote itself.
 template <int M>
-__global__ __launch_bounds__(256, M > 64 ? 1 : 2) void score_kernel(
+__global__ __launch_bounds__(256, 2) void score_kernel(
     const SegTable T, int tokens_per_wg, const uint16_t *__restrict__ wt, float *__restrict__ scores,
     int32_t *__restrict__ status, int *__restrict__ hist1, double *__restrict__ ostat) {
   constexpr int NSUB = 2, WTOK = 16 * NSUB, STEP = 4 * WTOK;     // tokens per wave / per WG step
   constexpr int NLD = WTOK * 16 / 64;                            // 16-B loads per lane per step
-  __shared__ __attribute__((aligned(16))) uint16_t wl[W_TERMS * M * WPITCH];
+  typedef WLayout<M> WL;
+  __shared__ __attribute__((aligned(16))) uint16_t wl[W_TERMS * WL::PLANE];
   // a wave stages 16 tokens at a time (its 32 tokens of a step in two halves); measured, a third
   // workgroup per CU does not pay, the smaller staging buffer does on the long-context shapes
   __shared__ __attribute__((aligned(16))) uint16_t kl[4][16 * WPITCH];
@@ -44,7 +78,7 @@ __global__ __launch_bounds__(256, M > 64 ? 1 : 2) void score_kernel(
                                             // way out: two 16-bit counters per word
   // The scores of the workgroup's tokens collect here and leave in one burst at the end: 4-byte
   // stores trickling out between the streaming reads cost 12 % of the kernel's time.
-  __shared__ __attribute__((aligned(16))) float sc_l[SCORE_MAX_TOKENS];
+  __shared__ __attribute__((aligned(16))) float sc_l[WL::MAX_TOKENS];
 
   const Where w = locate_block(T, blockIdx.x, tokens_per_wg, SCORE_STEP, false);
   const Seg &s = T.s[w.seg];
@@ -86,10 +120,12 @@ __global__ __launch_bounds__(256, M > 64 ? 1 : 2) void score_kernel(
 
   for (int i = tid; i < HIST1_BINS / 2; i += 256) hl[i] = 0;
   const uint16_t *wh = wt + (size_t)w.lhead * (W_TERMS * M * D);
-  for (int cidx = tid; cidx < W_TERMS * M * 16; cidx += 256) {
-    const int row = cidx >> 4, ch = cidx & 15;
-    *reinterpret_cast<uint4 *>(&wl[row * WPITCH + ch * 8]) =
-        *reinterpret_cast<const uint4 *>(wh + row * D + ch * 8);
+  for (int cidx = tid; cidx < W_TERMS * WL::CHUNKS; cidx += 256) {
+    const int t = cidx / WL::CHUNKS;
+    int row, ch;
+    WL::piece(cidx - t * WL::CHUNKS, row, ch);
+    *reinterpret_cast<uint4 *>(&wl[t * WL::PLANE + WL::row(row) + ch * 8]) =
+        *reinterpret_cast<const uint4 *>(wh + (t * M + row) * D + ch * 8);
   }
   __syncthreads();
 
@@ -123,15 +159,17 @@ __global__ __launch_bounds__(256, M > 64 ? 1 : 2) void score_kernel(
       f32x4 acc[NSUB];
 #pragma unroll
       for (int st = 0; st < NSUB; ++st) acc[st] = f32x4{0.f, 0.f, 0.f, 0.f};
+      const int wrow = WL::row(jb * 16 + t16), nblk = WL::blocks(jb);    // nblk is wave-uniform
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
+        if (kk < nblk) {
 #pragma unroll
-        for (int t = 0; t < W_TERMS; ++t) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
-              &wl[(t * M + jb * 16 + t16) * WPITCH + 32 * kk + 8 * g]);
+          for (int t = 0; t < W_TERMS; ++t) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&wl[t * WL::PLANE + wrow + 32 * kk + 8 * g]);
 #pragma unroll
-          for (int st = 0; st < NSUB; ++st)
-            acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, kb[st][kk], acc[st], 0, 0, 0);
+            for (int st = 0; st < NSUB; ++st)
+              acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, kb[st][kk], acc[st], 0, 0, 0);
+          }
         }
       }
 #pragma unroll

@@ -38,90 +38,6 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_floa
 // accumulated Gram matrix resolves: the direction is dropped and the head flagged.
 constexpr double PIVOT_REL = 1.4901161193847656e-08;   // 2^-26
 
-// ---- exact mode: S = G + rho I (128 x 128), one workgroup per head, everything in LDS -------
-__global__ __launch_bounds__(256) void solve_exact_kernel(const SegTable T, float ridge_rel,
-                                                          const double *__restrict__ g64,
-                                                          uint16_t *__restrict__ wt,
-                                                          int32_t *__restrict__ status) {
-  constexpr int m = D, SP = D + 1;
-  __shared__ double S[m * SP];
-  __shared__ double dinv[m];
-  __shared__ double d0[m];
-  __shared__ int flag;
-
-  const int lhead = blockIdx.x;
-  const Where w = locate_head(T, lhead);
-  const Seg &sg = T.s[w.seg];
-  const double *G = g64 + (size_t)lhead * (D * D);
-  const int tid = threadIdx.x;
-  if (tid == 0) flag = 0;
-  for (int idx = tid; idx < m * m; idx += 256) {
-    const int a = idx / m, b = idx - a * m;
-    if (b <= a) S[a * SP + b] = G[a * D + b];
-  }
-  __syncthreads();
-
-  // ridge: rho = ridge_rel * trace(S) / m (every thread sums in the same order)
-  double tr = 0.0;
-  for (int a = 0; a < m; ++a) tr += S[a * SP + a];
-  const double rho = (double)ridge_rel * tr / (double)m;
-  __syncthreads();
-  if (tid < m) {
-    const double v = S[tid * SP + tid] + rho;
-    S[tid * SP + tid] = v;
-    d0[tid] = v;
-  }
-
-  // right-looking Cholesky; L overwrites the strict lower triangle, 1/L_kk goes to dinv
-  const int tx = tid & 15, ty = tid >> 4;
-  for (int k = 0; k < m; ++k) {
-    __syncthreads();
-    const double piv = S[k * SP + k];
-    const bool ok = piv > PIVOT_REL * d0[k] && piv < 1.0e300;   // false for NaN too
-    const double dk = ok ? 1.0 / sqrt(piv) : 0.0;
-    if (tid == 0) {
-      dinv[k] = dk;
-      if (!ok) flag = COMPACTOR_STATUS_PIVOT;
-    }
-    for (int i = k + 1 + tid; i < m; i += 256) S[i * SP + k] = ok ? S[i * SP + k] * dk : 0.0;
-    __syncthreads();
-    if (ok) {
-      for (int i = k + 1 + ty; i < m; i += 16) {
-        const double lik = S[i * SP + k];
-        for (int j = k + 1 + tx; j <= i; j += 16) S[i * SP + j] -= lik * S[j * SP + k];
-      }
-    }
-  }
-  __syncthreads();
-
-  // X = L^{-1}, column c by thread c; X[j][c] (j > c) is kept in the free upper triangle S[c][j]
-  if (tid < m) {
-    const int c = tid;
-    const double xcc = dinv[c];
-    for (int j = c + 1; j < m; ++j) {
-      double sum = S[j * SP + c] * xcc;
-      for (int q = c + 1; q < j; ++q) sum += S[j * SP + q] * S[c * SP + q];
-      S[c * SP + j] = -sum * dinv[j];
-    }
-  }
-  __syncthreads();
-
-  // W^T = X (lower triangular), split into bf16 planes
-  uint16_t *wh = wt + (size_t)lhead * (W_TERMS * m * D);
-  const int ch = tid & 127;
-  for (int j = tid >> 7; j < m; j += 2) {
-    const double wv = ch < j ? S[ch * SP + j] : (ch == j ? dinv[j] : 0.0);
-    float x = (float)wv;
-#pragma unroll
-    for (int t = 0; t < W_TERMS; ++t) {
-      const uint16_t b = bf16_rne(x);
-      wh[(t * m + j) * D + ch] = b;
-      x -= bf16_to_f32(b);
-    }
-  }
-  if (tid == 0) status[sg.ghead0 + w.head] = flag;
-}
-
 // ---- sketched mode, one kernel: partial Gram blocks -> S -> L -> L^{-1} -> W^T ------------------
 // One workgroup (4 waves) per head; every O(n^3)-ish piece runs on the fp64 matrix cores
 // (16x16x4 MFMA: A[i][k] in lane (i = l & 15, k = l >> 4), B[k][j] in lane (j = l & 15,
@@ -464,29 +380,234 @@ __global__ __launch_bounds__(256, M > 48 ? 1 : 2) void sketch_solve_kernel(
   }
 }
 
+// ---- exact mode, one kernel: partial Gram blocks -> G + rho I -> L -> L^{-1} = W^T -------------
+// The same blocked factorisation as above on the full 128 x 128 Gram matrix (8 panels of 16).
+// One matrix of 128 x 129 doubles is all LDS has room for, so L lives in its lower block
+// triangle and the blocks of X = L^{-1} below the diagonal are written, transposed, into the
+// upper block triangle, which the factorisation never reads (element X[j][c], block of j below
+// block of c, is at S[c][j]); the eight diagonal blocks of X have an array of their own.
+__global__ __launch_bounds__(256) void exact_solve_kernel(
+    const SegTable T, int tiles_per_wg, const float *__restrict__ partials, float ridge_rel,
+    uint16_t *__restrict__ wt, int32_t *__restrict__ status, int *__restrict__ zero,
+    long long zero_ints) {
+  constexpr int M = D, P = M / 16, SP = M + 1;
+  __shared__ double Ss[M * SP];
+  __shared__ double Xd[P][16][17];
+  __shared__ double d0_s[M], rs_s[M], col_s[64];
+  __shared__ int flag_s;
+
+  const int lhead = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
+  if (tid == 0) flag_s = 0;
+  zero_slice(zero, zero_ints);   // histograms that the score and selection kernels add into
+
+  // ---- 1. G: the head's 10 upper blocks summed over the splits in fp64 (split order) ----
+  int nsplit;
+  const long long pb = partial_base(T, lhead, tiles_per_wg, nsplit);
+  int row0, col;
+  partial_quad(tid, row0, col);   // this thread's float4 of a block: rows row0..+3 of column col
+  double gsum[10][4];
+#pragma unroll
+  for (int b = 0; b < 10; ++b)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) gsum[b][c] = 0.0;
+  {
+    const float *src = partials + pb * GRAM_PARTIAL_FLOATS + tid * 4;
+    for (int s0 = 0; s0 < nsplit; s0 += 2) {
+      float4 v[2][10];
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int b = 0; b < 10; ++b) {
+          v[u][b] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (s0 + u < nsplit)
+            v[u][b] = *reinterpret_cast<const float4 *>(src + (long long)(s0 + u) * GRAM_PARTIAL_FLOATS + b * 1024);
+        }
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int b = 0; b < 10; ++b) {
+          gsum[b][0] += v[u][b].x; gsum[b][1] += v[u][b].y;
+          gsum[b][2] += v[u][b].z; gsum[b][3] += v[u][b].w;
+        }
+    }
+  }
+  // into the lower triangle: block (I, J), I < J, holds G[32I + r][32J + c] = G[32J + c][32I + r]
+#pragma unroll
+  for (int I = 0; I < 4; ++I)
+#pragma unroll
+    for (int J = I; J < 4; ++J) {
+      const int blk = upper_block(I, J);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if (I == J) Ss[(32 * I + row0 + c) * SP + 32 * J + col] = gsum[blk][c];
+        else        Ss[(32 * J + col) * SP + 32 * I + row0 + c] = gsum[blk][c];
+      }
+    }
+  __syncthreads();
+
+  // ridge: rho = ridge_rel * trace(G) / M (every thread sums in the same order)
+  double tr = 0.0;
+  for (int a = 0; a < M; ++a) tr += Ss[a * SP + a];
+  const double rho = (double)ridge_rel * tr / (double)M;
+  __syncthreads();
+  if (tid < M) {
+    const double v = Ss[tid * SP + tid] + rho;
+    Ss[tid * SP + tid] = v;
+    d0_s[tid] = v;
+  }
+  __syncthreads();
+
+  // ---- 2. blocked Cholesky ----
+#pragma unroll 1
+  for (int p = 0; p < P; ++p) {
+    if (wave == 0) {
+      const int base = 16 * p;
+      const bool rowlane = lane < 16;
+      double row[16], lrow[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) row[j] = rowlane ? Ss[(base + lane) * SP + base + j] : 0.0;
+      const double d0_mine = rowlane ? d0_s[base + lane] : 0.0;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        const double piv = readlane_f64(row[k], k);
+        const double d0k = readlane_f64(d0_mine, k);
+        const bool ok = piv > PIVOT_REL * d0k && piv < 1.0e300;      // false for NaN too
+        const double rs = ok ? rsqrt(piv) : 0.0;
+        if (lane == k) rs_s[base + k] = rs;
+        if (!ok && lane == 0) flag_s = COMPACTOR_STATUS_PIVOT;
+        const double lk = (rowlane && lane >= k) ? row[k] * rs : 0.0;   // L[lane][k]
+        lrow[k] = lk;
+        wave_fence();
+        col_s[lane] = lk;
+        wave_fence();
+#pragma unroll
+        for (int j = k + 1; j < 16; ++j) row[j] -= lk * col_s[j];       // col_s[j] = L[j][k]
+      }
+      if (rowlane) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) Ss[(base + lane) * SP + base + k] = lrow[k];
+      }
+      wave_fence();
+      // X_pp = L_pp^{-1}: lane j solves column j by forward substitution
+      double x[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        double sum = (i == lane) ? 1.0 : 0.0;
+#pragma unroll
+        for (int k = 0; k < i; ++k) sum -= Ss[(base + i) * SP + base + k] * x[k];
+        x[i] = sum * rs_s[base + i];
+      }
+      if (rowlane) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Xd[p][i][lane] = x[i];
+      }
+    }
+    __syncthreads();
+    // panel below the diagonal block: L_qp = A_qp X_pp^T
+    for (int q = p + 1 + wave; q < P; q += 4) {
+      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const double a = Ss[(16 * q + l16) * SP + 16 * p + 4 * ks + lq];
+        const double b = Xd[p][l16][4 * ks + lq];
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Ss[(16 * q + 4 * v + lq) * SP + 16 * p + l16] = acc[v];
+    }
+    __syncthreads();
+    // trailing blocks: A_qr -= L_qp L_rp^T for p < r <= q
+    int t = 0;
+    for (int q = p + 1; q < P; ++q)
+      for (int r = p + 1; r <= q; ++r, ++t) {
+        if ((t & 3) != wave) continue;
+        f64x4 acc;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[v] = Ss[(16 * q + 4 * v + lq) * SP + 16 * r + l16];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const double a = -Ss[(16 * q + l16) * SP + 16 * p + 4 * ks + lq];
+          const double b = Ss[(16 * r + l16) * SP + 16 * p + 4 * ks + lq];
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Ss[(16 * q + 4 * v + lq) * SP + 16 * r + l16] = acc[v];
+      }
+    __syncthreads();
+  }
+
+  // ---- 3. the blocks of X = L^{-1} below the diagonal: X_qp = -X_qq sum_r L_qr X_rp.  A wave
+  // takes the block columns p = wave and wave + 4; a column only reads what the same wave wrote.
+  for (int p = wave; p < P - 1; p += 4) {
+    for (int q = p + 1; q < P; ++q) {
+      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+      for (int r = p; r < q; ++r) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const double a = Ss[(16 * q + l16) * SP + 16 * r + 4 * ks + lq];        // L_qr[i][k]
+          const double b = r == p ? Xd[p][4 * ks + lq][l16]                        // X_pp[k][j]
+                                  : Ss[(16 * p + l16) * SP + 16 * r + 4 * ks + lq];  // X_rp[k][j], transposed
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+        }
+      }
+      // the result layout of acc is the B-operand layout of the next product
+      f64x4 out = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const double a = -Xd[q][l16][4 * ks + lq];
+        out = __builtin_amdgcn_mfma_f64_16x16x4f64(a, acc[ks], out, 0, 0, 0);
+      }
+      // X_qp[i = 4v + lq][j = l16], stored transposed in block (p, q) of the upper triangle
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Ss[(16 * p + l16) * SP + 16 * q + 4 * v + lq] = out[v];
+      wave_fence();            // the next block row of this column reads what was just written
+    }
+  }
+  __syncthreads();
+
+  // ---- 4. W^T = X (lower triangular), split into bf16 planes ----
+  uint16_t *wh = wt + (size_t)lhead * (W_TERMS * M * D);
+  const int ch = tid & 127;
+  for (int j = tid >> 7; j < M; j += 2) {
+    const int qb = j >> 4, pb2 = ch >> 4;
+    double wv = 0.0;
+    if (pb2 == qb) wv = Xd[qb][j & 15][ch & 15];
+    else if (pb2 < qb) wv = Ss[ch * SP + j];
+    float x = (float)wv;
+#pragma unroll
+    for (int t = 0; t < W_TERMS; ++t) {
+      const uint16_t b = bf16_rne(x);
+      wh[(t * M + j) * D + ch] = b;
+      x -= bf16_to_f32(b);
+    }
+  }
+  if (tid == 0) {
+    const Where w = locate_head(T, lhead);
+    status[T.s[w.seg].ghead0 + w.head] = flag_s;
+  }
+}
+
 template <int M>
 static hipError_t launch_sketched(const SegTable &T, int tiles_per_wg, const float *partials,
                                   const float *phi, float ridge_rel, uint16_t *wt,
                                   int32_t *status, int *zero, long long zero_ints,
-                                  hipStream_t st, hipEvent_t mid) {
-  if (mid && hipEventRecord(mid, st) != hipSuccess) return hipErrorLaunchFailure;
+                                  hipStream_t st) {
   hipLaunchKernelGGL((sketch_solve_kernel<M>), dim3((unsigned)T.nheads), dim3(256), 0, st, T,
                      tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints);
   return hipGetLastError();
 }
 
-// Sketched mode: partial Gram blocks -> W^T in one kernel (see above).  `mid`, if not null, is
-// recorded before it (profiling: the separate reduce stage is empty in this mode).
+// Sketched mode: partial Gram blocks -> W^T in one kernel (see above).
 hipError_t launch_sketch_solve(const SegTable &T, int ks, int tiles_per_wg, const float *partials,
                                const float *phi, float ridge_rel, uint16_t *wt,
-                               int32_t *status, int *zero, long long zero_ints, hipStream_t st,
-                               hipEvent_t mid) {
+                               int32_t *status, int *zero, long long zero_ints, hipStream_t st) {
   if (T.nheads <= 0) return hipSuccess;
   switch (ks) {
-    case 16: return launch_sketched<16>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st, mid);
-    case 32: return launch_sketched<32>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st, mid);
-    case 48: return launch_sketched<48>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st, mid);
-    case 64: return launch_sketched<64>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st, mid);
+    case 16: return launch_sketched<16>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st);
+    case 32: return launch_sketched<32>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st);
+    case 48: return launch_sketched<48>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st);
+    case 64: return launch_sketched<64>(T, tiles_per_wg, partials, phi, ridge_rel, wt, status, zero, zero_ints, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -519,12 +640,13 @@ hipError_t launch_srht_phi(int ks, const uint8_t *signs, const int32_t *cols, fl
   return hipGetLastError();
 }
 
-// Exact mode: full G (fp64, from gram_reduce) -> Cholesky of G + rho I -> W^T = L^{-1}.
-hipError_t launch_solve(const SegTable &T, float ridge_rel, const double *g64, uint16_t *wt,
-                        int32_t *status, hipStream_t st) {
+// Exact mode: partial Gram blocks -> Cholesky of G + rho I -> W^T = L^{-1}, in one kernel.
+hipError_t launch_exact_solve(const SegTable &T, int tiles_per_wg, const float *partials,
+                              float ridge_rel, uint16_t *wt, int32_t *status, int *zero,
+                              long long zero_ints, hipStream_t st) {
   if (T.nheads <= 0) return hipSuccess;
-  hipLaunchKernelGGL(solve_exact_kernel, dim3((unsigned)T.nheads), dim3(256), 0, st, T, ridge_rel,
-                     g64, wt, status);
+  hipLaunchKernelGGL(exact_solve_kernel, dim3((unsigned)T.nheads), dim3(256), 0, st, T, tiles_per_wg,
+                     partials, ridge_rel, wt, status, zero, zero_ints);
   return hipGetLastError();
 }
 
