@@ -165,8 +165,21 @@ def attention_mode(a, torch, C, W, w, reqs, params, bufs, dev):
         return (time.perf_counter() - t0) / a.steps * 1e3
 
     ms_attn = run(lambda: C.compactor_attention_scores(ap, areqs, attn=attn, workspace=aws))
+    # the blended compress needs a little more workspace than the plain one (the blend's sums)
+    bufs = dict(bufs)
+    bufs["workspace"] = torch.empty(max(256, C.compactor_workspace_size(params, breqs)), dtype=torch.uint8, device=dev)
     ms_full = run(lambda: (C.compactor_attention_scores(ap, areqs, attn=attn, workspace=aws),
                            C.compactor_compress(params, breqs, want_scores=False, **bufs)))
+    # stage times of the blended compress (HIP events on the launch stream)
+    ev = C.StageEvents()
+    params.stage_events = ev
+    stage_ms = {}
+    for _ in range(a.steps):
+        C.compactor_compress(params, breqs, want_scores=False, **bufs)
+        torch.cuda.synchronize()
+        for k_, v_ in ev.elapsed_ms().items():
+            stage_ms[k_] = stage_ms.get(k_, 0.0) + v_ / a.steps
+    params.stage_events = None
     rows_q = sum(r.n for r in w.requests) * w.layers * w.kv_heads * G
     rows_k = sum(r.n for r in w.requests) * w.layers * w.kv_heads
     flops = 2.0 * 256 * 128 * rows_q                   # Q K^T inside 256-token blocks
@@ -179,6 +192,8 @@ def attention_mode(a, torch, C, W, w, reqs, params, bufs, dev):
         "attention_frac_of_8TB/s": nbytes / (ms_attn * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "attention_frac_of_bf16_mfma_peak": flops / (ms_attn * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         "full_step_ms": ms_full, "full_step_tokens_per_s": w.tokens / (ms_full * 1e-3),
+        "blended_compress_stages_ms": {k_: round(v_, 4) for k_, v_ in stage_ms.items()},
+        "blend_GB/s": 16.0 * rows_k / (stage_ms.get("blend", float("nan")) * 1e-3) / 1e9,
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "dtype": "bf16", "data": "synthetic"}))
 
 

@@ -222,8 +222,14 @@ __global__ __launch_bounds__(GATHER_THREADS) void gather_paged_kernel(const SegT
 // retained rows move to the front.  One workgroup per head walks the retained list in ascending
 // runs of 256 rows: all rows of a run are read, the workgroup meets, the run is written.  A run's
 // sources lie at or behind its own destinations and strictly behind those of earlier runs
-// (kept[j] >= j, ascending), so nothing is overwritten before it has been read.
+// (kept[j] >= j, ascending), so nothing is overwritten before it has been read; for the same
+// reason the next run's rows can be fetched while this run is being written (its sources lie
+// behind every slot written so far), which keeps loads in flight across the barrier.
 constexpr int INPLACE_THREADS = 1024, INPLACE_RUN = 256;
+struct InplaceRun {
+  uint4 kv[INPLACE_RUN / 64], vv[INPLACE_RUN / 64];
+  long long dst[INPLACE_RUN / 64];
+};
 __global__ __launch_bounds__(INPLACE_THREADS) void compact_inplace_kernel(
     const SegTable T, const PagePool P, const int32_t *__restrict__ kept_idx,
     const int32_t *__restrict__ kept_cnt) {
@@ -240,33 +246,43 @@ __global__ __launch_bounds__(INPLACE_THREADS) void compact_inplace_kernel(
   }
   const int32_t *idx = kept_idx + first;
   const int chunk = threadIdx.x & 15, sub = threadIdx.x >> 4;    // 64 rows per pass
-  for (int base = 0; base < rows; base += INPLACE_RUN) {
-    uint4 kv[INPLACE_RUN / 64], vv[INPLACE_RUN / 64];
-    long long dst[INPLACE_RUN / 64];
+  auto fetch = [&](int base, InplaceRun &r) {
 #pragma unroll
     for (int p = 0; p < INPLACE_RUN / 64; ++p) {
       const int j = base + p * 64 + sub;
-      dst[p] = -1;
-      kv[p] = make_uint4(0, 0, 0, 0);
-      vv[p] = make_uint4(0, 0, 0, 0);
+      r.dst[p] = -1;
+      r.kv[p] = make_uint4(0, 0, 0, 0);
+      r.vv[p] = make_uint4(0, 0, 0, 0);
       if (j < rows) {
         const int tok = idx[j];
         const long long src = (tok >= j && tok < s.n) ? page_slot(P, w.seg, layer, h, tok) : -1;
         if (src >= 0) {
-          kv[p] = *reinterpret_cast<const uint4 *>(P.k + src + chunk * 8);
-          vv[p] = *reinterpret_cast<const uint4 *>(P.v + src + chunk * 8);
-          dst[p] = tok == j ? -1 : page_slot(P, w.seg, layer, h, j);   // already in place
+          r.kv[p] = load_stream16(P.k + src + chunk * 8);
+          r.vv[p] = load_stream16(P.v + src + chunk * 8);
+          r.dst[p] = tok == j ? -1 : page_slot(P, w.seg, layer, h, j);   // already in place
         }
       }
     }
-    __syncthreads();      // every row of the run has been read (the barrier waits for the loads)
+  };
+  auto write = [&](const InplaceRun &r) {
 #pragma unroll
     for (int p = 0; p < INPLACE_RUN / 64; ++p) {
-      if (dst[p] >= 0) {
-        *reinterpret_cast<uint4 *>(P.k + dst[p] + chunk * 8) = kv[p];
-        *reinterpret_cast<uint4 *>(P.v + dst[p] + chunk * 8) = vv[p];
+      if (r.dst[p] >= 0) {
+        store_stream16(P.k + r.dst[p] + chunk * 8, r.kv[p]);
+        store_stream16(P.v + r.dst[p] + chunk * 8, r.vv[p]);
       }
     }
+  };
+  InplaceRun a, b;
+  fetch(0, a);
+  for (int base = 0; base < rows; base += 2 * INPLACE_RUN) {
+    __syncthreads();      // every row of run `a` has been read (the barrier waits for the loads)
+    fetch(base + INPLACE_RUN, b);
+    write(a);
+    if (base + INPLACE_RUN >= rows) break;         // uniform
+    __syncthreads();
+    fetch(base + 2 * INPLACE_RUN, a);
+    write(b);
   }
 }
 

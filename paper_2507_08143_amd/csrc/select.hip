@@ -312,15 +312,16 @@ __device__ __forceinline__ long long chunk_token_base(const SegTable &T, const S
 // tok_begin + 4 * (r * CHUNK_THREADS + tid) + e); bit 4r+e of the result says that the token
 // exists.  The loads are only issued here: whoever calls this first and converts to keys later
 // has the latency of everything in between for free.
-__device__ __forceinline__ unsigned load_chunk_scores(const float *__restrict__ sp, const SelWhere &q,
-                                                      float (&f)[SEL_ROUNDS][4]) {
+template <int R>
+__device__ __forceinline__ unsigned load_scores_part(const float *__restrict__ sp, const SelWhere &q,
+                                                     int r0, float (&f)[R][4]) {
   // one 16-byte load per 4 tokens also where a head's scores start off a 16-byte boundary (odd
   // n): global memory takes vector loads at any 4-byte address
   typedef float f32x4_any __attribute__((ext_vector_type(4), aligned(4)));
   unsigned valid = 0;
 #pragma unroll
-  for (int r = 0; r < SEL_ROUNDS; ++r) {
-    const int i0 = q.tok_begin + 4 * (r * CHUNK_THREADS + (int)threadIdx.x);
+  for (int r = 0; r < R; ++r) {
+    const int i0 = q.tok_begin + 4 * ((r0 + r) * CHUNK_THREADS + (int)threadIdx.x);
     if (i0 + 3 < q.tok_end) {
       const f32x4_any v = *reinterpret_cast<const f32x4_any *>(sp + i0);
       f[r][0] = v.x; f[r][1] = v.y; f[r][2] = v.z; f[r][3] = v.w;
@@ -337,6 +338,10 @@ __device__ __forceinline__ unsigned load_chunk_scores(const float *__restrict__ 
     }
   }
   return valid;
+}
+__device__ __forceinline__ unsigned load_chunk_scores(const float *__restrict__ sp, const SelWhere &q,
+                                                      float (&f)[SEL_ROUNDS][4]) {
+  return load_scores_part<SEL_ROUNDS>(sp, q, 0, f);
 }
 __device__ __forceinline__ void scores_to_keys(const float (&f)[SEL_ROUNDS][4],
                                                uint32_t (&key)[SEL_ROUNDS][4]) {
@@ -776,13 +781,19 @@ __global__ __launch_bounds__(CHUNK_THREADS) void blend_stats_kernel(const SegTab
   const Seg &s = T.s[q.seg];
   if (s.attn == nullptr) return;
   const float *a = s.attn + (long long)q.head * s.n;
+  float f[SEL_ROUNDS][4];
+  const unsigned valid = load_chunk_scores(a, q, f);
   const double shift = (double)a[0];
   double s1 = 0.0, s2 = 0.0;
-  for (int i = q.tok_begin + (int)threadIdx.x; i < q.tok_end; i += CHUNK_THREADS) {
-    const double x = (double)a[i] - shift;
-    s1 += x;
-    s2 += x * x;
-  }
+#pragma unroll
+  for (int r = 0; r < SEL_ROUNDS; ++r)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (valid >> (4 * r + e) & 1) {
+        const double x = (double)f[r][e] - shift;
+        s1 += x;
+        s2 += x * x;
+      }
   block_sum2(s1, s2, wd);
   if (threadIdx.x == 0) {
     astat[2 * (size_t)blockIdx.x] = s1;
@@ -834,10 +845,37 @@ __global__ __launch_bounds__(CHUNK_THREADS) void blend_apply_kernel(
   if (hist1 != nullptr)
     for (int i = tid; i < HIST1_BINS; i += CHUNK_THREADS) hist[i] = 0;
   __syncthreads();
-  for (int i = q.tok_begin + tid; i < q.tok_end; i += CHUNK_THREADS) {
-    const float v = (float)(((double)a[i] - ma) * ia + ((double)o[i] - mo) * io);
-    o[i] = v;
-    if (hist1 != nullptr) atomicAdd(&hist[score_key(v) >> 20], 1);
+  typedef float f32x4_any __attribute__((ext_vector_type(4), aligned(4)));
+  // the chunk in parts of PART rounds: the fp64 arithmetic of a whole chunk at once would take
+  // so many registers that only three workgroups fit a CU
+  constexpr int PART = 2;
+#pragma unroll 1
+  for (int r0 = 0; r0 < SEL_ROUNDS; r0 += PART) {
+    if (q.tok_begin + 4 * r0 * CHUNK_THREADS >= q.tok_end) break;       // uniform
+    float fa[PART][4], fo[PART][4];
+    const unsigned valid = load_scores_part<PART>(a, q, r0, fa);
+    load_scores_part<PART>(o, q, r0, fo);
+#pragma unroll
+    for (int r = 0; r < PART; ++r) {
+      const unsigned m = (valid >> (4 * r)) & 0xfu;
+      if (m == 0) continue;
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[e] = (float)(((double)fa[r][e] - ma) * ia + ((double)fo[r][e] - mo) * io);
+        if (hist1 != nullptr && (m >> e & 1)) atomicAdd(&hist[score_key(v[e]) >> 20], 1);
+      }
+      const int i0 = q.tok_begin + 4 * ((r0 + r) * CHUNK_THREADS + tid);
+      if (m == 0xfu) {
+        f32x4_any t;
+        t.x = v[0]; t.y = v[1]; t.z = v[2]; t.w = v[3];
+        *reinterpret_cast<f32x4_any *>(o + i0) = t;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (m >> e & 1) o[i0 + e] = v[e];
+      }
+    }
   }
   if (hist1 != nullptr) {
     __syncthreads();
