@@ -99,7 +99,7 @@ typedef struct compactor_params {
                              pass that finds a group's keys in the last-level cache is no faster
                              than one that streams them from HBM. */
   int32_t gram_wgs;       /* tuning: workgroups of the persistent Gram kernel and target tokens */
-  int32_t score_tokens;   /* per workgroup of the score kernel (at most 4096; larger values are
+  int32_t score_tokens;   /* per workgroup of the score kernel (at most 32768; larger values are
                              clamped); 0 = chosen by the library */
   int32_t select_scope;   /* COMPACTOR_SCOPE_HEAD (default): every head keeps its own top k_keep.
                              COMPACTOR_SCOPE_LAYER: head-adaptive selection (Sec. 3.3, retain the

@@ -20,8 +20,10 @@ constexpr int W_TERMS = 2;        // W^T is carried as a sum of this many bf16 p
 constexpr int GRAM_PARTIAL_FLOATS = 10 * 32 * 32;   // upper blocks of one partial Gram matrix
 constexpr int GRAM_TILE = 64;         // rows staged in LDS per step of the Gram kernel
 constexpr int SCORE_STEP = 128;       // tokens a score workgroup multiplies per step
-constexpr int SCORE_MAX_TOKENS = 4096;   // most tokens a score workgroup takes (their scores wait in LDS)
-constexpr int SCORE_EXACT_MAX_TOKENS = 2048;   // the same in exact mode, where W^T takes more of the LDS
+constexpr int SCORE_BURST = 4096;     // scores a score workgroup collects in LDS before writing them
+constexpr int SCORE_EXACT_BURST = 2048;   // the same in exact mode, where W^T takes more of the LDS
+constexpr int SCORE_MAX_RUN = 32768;  // most tokens a score workgroup takes (its histogram counts in
+                                      // 16 bits)
 constexpr int SELECT_THREADS = 1024;
 constexpr int SEL_CHUNK = 8192;       // tokens per workgroup of the chunked selection and blend
                                       // kernels (chunks never cross heads)

@@ -28,7 +28,7 @@ constexpr int WPITCH = 136;   // bf16 per LDS row of W^T and of staged key rows 
 template <int M>
 struct WLayout {
   static constexpr int PLANE = M * WPITCH;                       // bf16 per plane
-  static constexpr int MAX_TOKENS = SCORE_MAX_TOKENS;            // scores of a workgroup wait in LDS
+  static constexpr int BURST = SCORE_BURST;                      // scores that wait in LDS
   __device__ static __forceinline__ int row(int r) { return r * WPITCH; }
   __device__ static __forceinline__ int blocks(int /*jb*/) { return 4; }   // 32-channel blocks of a row
   static constexpr int CHUNKS = M * 16;                          // 16-byte pieces per plane
@@ -37,7 +37,7 @@ struct WLayout {
 template <>
 struct WLayout<128> {
   static constexpr int PLANE = 32 * (40 + 72 + 104 + 136);      // 11264 bf16
-  static constexpr int MAX_TOKENS = SCORE_EXACT_MAX_TOKENS;
+  static constexpr int BURST = SCORE_EXACT_BURST;
   __device__ static __forceinline__ int row(int r) {
     const int g = r >> 5;
     return 1280 * g + 512 * g * (g - 1) + (r & 31) * (40 + 32 * g);
@@ -62,7 +62,11 @@ __device__ __forceinline__ void wave_lds_fence() {
 // sub-tiles).  Key rows arrive with fully coalesced streaming loads (a wave instruction covers
 // four whole 256-byte rows), pass through a wave-private LDS buffer, and are read back in the
 // MFMA B-operand arrangement; two steps of loads are in flight while a third is multiplied.
-// Nothing in the loop needs a workgroup barrier: a wave only reads what it wrote itself.
+// The multiply loop needs no workgroup barrier: a wave only reads what it wrote itself.  The
+// scores collect in LDS and leave in bursts of BURST tokens; a run may span several bursts (up to
+// SCORE_MAX_RUN tokens), so that what a workgroup pays once (staging W^T, the histogram, filling
+// and draining its load pipeline) is spread over more rows; the loads of the steps that follow a
+// burst are already in flight while it is written.
 template <int M>
 __global__ __launch_bounds__(256, 2) void score_kernel(
     const SegTable T, int tokens_per_wg, const uint16_t *__restrict__ wt, float *__restrict__ scores,
@@ -76,9 +80,12 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
   __shared__ __attribute__((aligned(16))) uint16_t kl[4][16 * WPITCH];
   __shared__ unsigned hl[HIST1_BINS / 2];   // first radix digit of the selection, tallied on the
                                             // way out: two 16-bit counters per word
-  // The scores of the workgroup's tokens collect here and leave in one burst at the end: 4-byte
-  // stores trickling out between the streaming reads cost 12 % of the kernel's time.
-  __shared__ __attribute__((aligned(16))) float sc_l[WL::MAX_TOKENS];
+  // The scores collect here and leave in bursts: 4-byte stores trickling out between the
+  // streaming reads cost 12 % of the kernel's time.
+  constexpr int BURST = WL::BURST, BSTEPS = BURST / STEP;
+  static_assert((BURST & (BURST - 1)) == 0 && BSTEPS % 2 == 0, "bursts end on even steps");
+  __shared__ __attribute__((aligned(16))) float sc_l[BURST];
+  __shared__ double red[4][2];
 
   const Where w = locate_block(T, blockIdx.x, tokens_per_wg, SCORE_STEP, false);
   const Seg &s = T.s[w.seg];
@@ -186,32 +193,20 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
     x += __shfl_xor(up ? x0 : x1, 16);
     const int tok = tok_begin + it * STEP + wave * WTOK + (lane & 31);   // 16*(g&1) + t16
     if (g < 2 && tok < tok_end) {
-      sc_l[tok - tok_begin] = x;
+      sc_l[(tok - tok_begin) & (BURST - 1)] = x;
       bad |= !(fabsf(x) <= 3.0e38f);
       const uint32_t bin = score_key(x) >> 20;
       atomicAdd(&hl[bin >> 1], 1u << (16 * (bin & 1)));
     }
   };
 
-  for (int it = 0; it < nsteps; it += 2) {
-    redistribute(stA);
-    load_step(it + 2, stA);
-    multiply(it);
-    if (it + 1 < nsteps) {
-      redistribute(stB);
-      load_step(it + 3, stB);
-      multiply(it + 1);
-    }
-  }
-  if (__any(bad)) {
-    if (lane == 0) atomicOr(&status[s.ghead0 + w.head], COMPACTOR_STATUS_NONFINITE);
-  }
-  __syncthreads();
-  {    // the scores leave as 16-byte streaming stores (they disturb the other workgroups' reads
-       // least: 1 to 4 % of the kernel's time against plain stores); a head whose scores do not
-       // start on a 16-byte boundary (odd n) gets up to 3 single stores in front
-    const int cnt = tok_end - tok_begin;
-    float *dst = sp + tok_begin;
+  const bool want_stat = ostat != nullptr && s.attn != nullptr;
+  double s1 = 0.0, s2 = 0.0;       // this thread's share of (sum, sum of squares) for the blend
+  // The scores of tokens [b0, b0 + cnt) of the run leave as 16-byte streaming stores (they disturb
+  // the other workgroups' reads least: 1 to 4 % of the kernel's time against plain stores); a
+  // burst that does not start on a 16-byte boundary (odd n) gets up to 3 single stores in front.
+  auto burst = [&](int b0, int cnt) {
+    float *dst = sp + tok_begin + b0;
     const int mis = (int)((reinterpret_cast<uintptr_t>(dst) >> 2) & 3u);
     const int lead = min(cnt, mis ? 4 - mis : 0);
     if (tid < lead) dst[tid] = sc_l[tid];
@@ -224,18 +219,37 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
                                            __float_as_uint(sc_l[i + 2]), __float_as_uint(sc_l[i + 3])));
     }
     for (int i = lead + ((cnt - lead) & ~3) + tid; i < cnt; i += 256) dst[i] = sc_l[i];
-  }
-  if (ostat != nullptr && s.attn != nullptr) {
-    // (sum, sum of squares) of this workgroup's scores for the blend's standardisation, in fp64
-    // and in a fixed order: lanes stride the run, then a butterfly per wave, then the 4 waves
-    __shared__ double red[4][2];
-    const int cnt = tok_end - tok_begin;
-    double s1 = 0.0, s2 = 0.0;
-    for (int i = tid; i < cnt; i += 256) {
-      const double x = (double)sc_l[i];
-      s1 += x;
-      s2 += x * x;
+    if (want_stat) {
+      for (int i = tid; i < cnt; i += 256) {
+        const double x = (double)sc_l[i];
+        s1 += x;
+        s2 += x * x;
+      }
     }
+  };
+
+  for (int it = 0; it < nsteps; it += 2) {
+    redistribute(stA);
+    load_step(it + 2, stA);
+    multiply(it);
+    if (it + 1 < nsteps) {
+      redistribute(stB);
+      load_step(it + 3, stB);
+      multiply(it + 1);
+    }
+    const bool last = it + 2 >= nsteps;
+    if (last || (it + 2) % BSTEPS == 0) {          // uniform: a burst is complete
+      const int b0 = (it / BSTEPS) * BURST;
+      __syncthreads();
+      burst(b0, min(BURST, tok_end - tok_begin - b0));
+      if (!last) __syncthreads();                   // before the next burst's scores overwrite these
+    }
+  }
+  if (__any(bad)) {
+    if (lane == 0) atomicOr(&status[s.ghead0 + w.head], COMPACTOR_STATUS_NONFINITE);
+  }
+  if (want_stat) {
+    // fixed order: lanes stride every burst, then a butterfly per wave, then the 4 waves
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
       s1 += __shfl_xor(s1, d);
