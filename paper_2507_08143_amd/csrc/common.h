@@ -54,6 +54,11 @@ struct Seg {
   int sel_chunk;         // tokens per chunk (the last chunk of a head may be shorter)
   int pool0;             // launch-local index of the segment's first selection pool
   long long tok0;        // position of the segment's first token in the launch's token sequence
+  // The same for the score kernel's workgroups, filled by index_score_blocks() for the run
+  // length of the launch.
+  int score_blk0;        // number of the segment's first score workgroup in the launch
+  int score_bph;         // score workgroups per head
+  int score_chunk;       // tokens per score workgroup
 };
 
 struct SegTable {
@@ -361,6 +366,20 @@ inline void index_chunks(SegTable &T) {
     pool += s.head_count / pool_heads(T, s);
     tok += (long long)s.n * s.head_count;
   }
+}
+
+// Fills the score kernel's enumeration fields for workgroups of about tokens_per_wg tokens;
+// returns the number of workgroups.
+inline long long index_score_blocks(SegTable &T, int tokens_per_wg) {
+  long long blk = 0;
+  for (int i = 0; i < T.nseg; ++i) {
+    Seg &s = T.s[i];
+    s.score_blk0 = (int)blk;
+    s.score_bph = blocks_per_head(s.n, tokens_per_wg, SCORE_STEP);
+    s.score_chunk = chunk_of(s.n, tokens_per_wg, SCORE_STEP);
+    blk += (long long)s.score_bph * s.head_count;
+  }
+  return blk;
 }
 
 // Total workgroups of a launch whose blocks-per-head rule is (per_block, by_keep).

@@ -69,7 +69,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 // burst are already in flight while it is written.
 template <int M>
 __global__ __launch_bounds__(256, 2) void score_kernel(
-    const SegTable T, int tokens_per_wg, const uint16_t *__restrict__ wt, float *__restrict__ scores,
+    const SegTable T, const uint16_t *__restrict__ wt, float *__restrict__ scores,
     int32_t *__restrict__ status, int *__restrict__ hist1, double *__restrict__ ostat) {
   constexpr int NSUB = 2, WTOK = 16 * NSUB, STEP = 4 * WTOK;     // tokens per wave / per WG step
   constexpr int NLD = WTOK * 16 / 64;                            // 16-B loads per lane per step
@@ -87,8 +87,20 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
   __shared__ __attribute__((aligned(16))) float sc_l[BURST];
   __shared__ double red[4][2];
 
-  const Where w = locate_block(T, blockIdx.x, tokens_per_wg, SCORE_STEP, false);
+  // Where this workgroup works.  Every wave does this scalar work before its first load can
+  // leave, so the per-segment numbers come precomputed in the table (index_score_blocks) and
+  // one division remains.
+  Where w{0, 0, 0, 0, 0};
+  for (int i = 1; i < T.nseg; ++i) w.seg += (int)blockIdx.x >= T.s[i].score_blk0;
   const Seg &s = T.s[w.seg];
+  {
+    const int local = (int)blockIdx.x - s.score_blk0;
+    const int hh = (int)((unsigned)local / (unsigned)s.score_bph);
+    w.head = s.head_begin + hh;
+    w.lhead = s.lhead0 + hh;
+    w.tile = local - hh * s.score_bph;
+    w.chunk = s.score_chunk;
+  }
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int t16 = lane & 15, g = lane >> 4;
@@ -276,11 +288,12 @@ template <int M>
 static hipError_t launch_m(const SegTable &T, int tokens_per_wg, const uint16_t *wt,
                            float *scores, int32_t *status, int *hist1, double *ostat,
                            hipStream_t st) {
-  const long long nb = total_blocks(T, tokens_per_wg, SCORE_STEP, false);
+  SegTable Ti = T;
+  const long long nb = index_score_blocks(Ti, tokens_per_wg);
   if (nb <= 0) return hipSuccess;
   if (nb > 0x7fffffffll) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((score_kernel<M>), dim3((unsigned)nb), dim3(256), 0, st, T, tokens_per_wg, wt,
-                     scores, status, hist1, ostat);
+  hipLaunchKernelGGL((score_kernel<M>), dim3((unsigned)nb), dim3(256), 0, st, Ti, wt, scores, status,
+                     hist1, ostat);
   return hipGetLastError();
 }
 
