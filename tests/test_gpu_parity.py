@@ -230,6 +230,24 @@ def test_gram_partitions_that_cross_heads(C, gram_wgs):
     _say("  max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
 
 
+@pytest.mark.parametrize("score_tokens", [128, 1024, 8192, 32768])
+def test_score_runs_of_several_bursts(C, score_tokens):
+    """A score workgroup takes `score_tokens` tokens and writes its scores in bursts of 4096 (2048
+    in exact mode): one partial burst, exactly one, two and a half, and a whole head of 11 bursts
+    must all match the oracle; with attention scores the workgroup sums of the blend follow the
+    same partition."""
+    _say("score workgroups of %d tokens on heads of 10300 tokens, sketched, exact and blended" % score_tokens)
+    w = W.config2(DEV, L=1, H=3, n=10300)
+    st, _ = U.run_and_check(C, w, DEV, tune={"score_tokens": score_tokens})
+    _say("  sketched: max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+    w.requests[0].attn = W.synthetic_attention_scores(1, 3, 10300, device=DEV, seed=score_tokens)
+    st, _ = U.run_and_check(C, w, DEV, tune={"score_tokens": score_tokens})
+    _say("  blended: score error at most %.3g of its bound, swaps %d" % (st["max_blend_err_over_bound"], st["swaps"]))
+    w = W.config5(DEV, L=1, H=2, n=10300, exact=True)
+    st, _ = U.run_and_check(C, w, DEV, tune={"score_tokens": score_tokens})
+    _say("  exact ridge 1e-4: max rel err %.3g, swaps %d" % (st["max_rel"], st["swaps"]))
+
+
 def test_config2_small(C):
     _say("config 2 shape, 2 layers x 8 heads, n=6000")
     st, _ = U.run_and_check(C, W.config2(device=DEV, L=2, H=8, n=6000), DEV)
@@ -794,6 +812,52 @@ def test_compress_replays_from_a_hip_graph(C):
             assert torch.equal(gb[name], eb[name]), "replay %d: %s differs from the eager call" % (rep, name)
         assert torch.equal(gb["k_packed"].view(torch.int16), eb["k_packed"].view(torch.int16))
         assert torch.equal(gb["v_packed"].view(torch.int16), eb["v_packed"].view(torch.int16))
+
+
+def test_pooled_and_blended_compress_replays_from_a_hip_graph_on_a_side_stream(C):
+    """The same for the kernels of the pooled selection and of the blend (heads longer than one
+    selection workgroup's reach, attention scores given), captured on a stream that is not the
+    current one: they clear their scratch themselves too."""
+    _say("pooled selection + blend captured in a HIP graph on a side stream")
+    w = W.config2(DEV, L=1, H=3, n=40000)
+    w.requests[0].attn = W.synthetic_attention_scores(1, 3, 40000, device=DEV, seed=9)
+    params, reqs = U.make_call(C, w, DEV)
+    so, ko, kk = C.compactor_layout(params, reqs)
+    ws = torch.empty(max(256, C.compactor_workspace_size(params, reqs)), dtype=torch.uint8, device=DEV)
+
+    def buffers():
+        return dict(kept_idx=torch.empty(ko[-1], dtype=torch.int32, device=DEV),
+                    kept_cnt=torch.empty(3, dtype=torch.int32, device=DEV),
+                    k_packed=torch.empty(ko[-1], 128, dtype=torch.bfloat16, device=DEV),
+                    v_packed=torch.empty(ko[-1], 128, dtype=torch.bfloat16, device=DEV),
+                    status=torch.empty(3, dtype=torch.int32, device=DEV),
+                    scores=torch.empty(so[-1], dtype=torch.float32, device=DEV))
+    gb, eb = buffers(), buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        C.compactor_compress(params, reqs, want_scores=True, workspace=ws, stream=side, **gb)   # warm-up, eager
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        C.compactor_compress(params, reqs, want_scores=True, workspace=ws, stream=side, **gb)
+    for rep in range(3):
+        fresh = W.config2(DEV, seed=200 + rep, L=1, H=3, n=40000).requests[0]
+        w.requests[0].k.copy_(fresh.k)
+        w.requests[0].v.copy_(fresh.v)
+        w.requests[0].attn.copy_(W.synthetic_attention_scores(1, 3, 40000, device=DEV, seed=300 + rep))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        C.compactor_compress(params, reqs, want_scores=True, workspace=ws, **eb)
+        torch.cuda.synchronize()
+        for name in ("scores", "kept_idx", "kept_cnt", "status"):
+            assert torch.equal(gb[name], eb[name]), "replay %d: %s differs from the eager call" % (rep, name)
+        assert torch.equal(gb["k_packed"].view(torch.int16), eb["k_packed"].view(torch.int16))
+        assert torch.equal(gb["v_packed"].view(torch.int16), eb["v_packed"].view(torch.int16))
+    # and the eager result is the oracle's
+    st, _ = U.run_and_check(C, w, DEV)
+    _say("  blended score error at most %.3g of its bound, swaps %d" % (st["max_blend_err_over_bound"], st["swaps"]))
 
 
 def test_pooled_select_edges_and_regrouping(C):
