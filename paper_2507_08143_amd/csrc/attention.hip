@@ -24,7 +24,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int ATT_C = 256;          // block (chunk) size C of the paper
 constexpr int ATT_QB = 64;          // queries per step
-constexpr int QPITCH = 136;         // bf16 per LDS row of staged queries (272 B)
+constexpr int ATT_QBUF = 4;         // staged query tiles in flight (three steps ahead)
 constexpr int ATT_MAX_SEG = 16;
 
 struct AttnSeg {
@@ -64,8 +64,11 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
   return r;
 }
 
+// A staged query tile is 64 rows of 256 B without padding; the 16-byte pieces of row r are
+// stored at position (piece ^ (r & 15)), so that the 16 lanes that read the same piece of 16
+// consecutive rows touch every bank once.
 struct AttnLds {
-  uint16_t ql[2][ATT_QB * QPITCH];   // staged query rows, double buffered
+  uint16_t ql[ATT_QBUF][ATT_QB * D];   // staged query rows, filled by loads that write LDS directly
   float st_m[2][4][ATT_QB];          // per wave: scaled maximum of every query of the step
   float st_l[2][4][ATT_QB];          //           and the sum of its exponentials
 };
@@ -108,25 +111,39 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
 #pragma unroll
     for (int v = 0; v < 16; ++v) pacc[kt][v] = 0.f;
 
+  // Query rows go from memory into LDS without passing through registers, so that the tiles of
+  // three later steps can be in flight at no cost in registers (one step of arithmetic is
+  // shorter than the latency of a load while the memory system is busy).  One such load of a
+  // wave moves four rows: lane l brings a 16-byte piece of row l >> 4 to LDS position
+  // base + 16 l, which is position l & 15 of that row; it fetches the piece that belongs there.
   const int nsteps = s.G * (ATT_C / ATT_QB);          // (query head of the group, 64-query block)
-  const int ld_row = tid >> 4, ld_chunk = tid & 15;   // loader: 16 lanes per 256-B query row
-  auto load_q = [&](int step, uint4 (&stg)[4]) {
-    const int qh = step / (ATT_C / ATT_QB);
-    const uint16_t *qp = s.q + (long long)layer * s.q_stride_l + (long long)(kvh * s.G + qh) * s.q_stride_h;
-    const int r0 = c0 + (step % (ATT_C / ATT_QB)) * ATT_QB;
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const int ld_row = 4 * wv + (lane >> 4);            // row within a group of 16
+  const int ld_piece = (lane & 15) ^ (ld_row & 15);
+  const uint16_t *q_head0 = s.q + (long long)layer * s.q_stride_l + (long long)(kvh * s.G) * s.q_stride_h;
+  // this lane's piece of row c0 + ld_row of the group's first query head; a step adds an offset
+  // that is the same for all lanes
+  const uint16_t *q_lane = q_head0 + (long long)(c0 + ld_row) * s.q_stride_t + ld_piece * 8;
+  auto issue_q = [&](int step) {
+    const int qh = step / (ATT_C / ATT_QB), r0 = (step % (ATT_C / ATT_QB)) * ATT_QB;
+    uint16_t *dst = &L.ql[step % ATT_QBUF][4 * wv * D];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row = r0 + ld_row + 16 * i;
-      stg[i] = make_uint4(0, 0, 0, 0);
-      if (step < nsteps && (!RAGGED || row < n))
-        stg[i] = load_stream16(qp + (long long)row * s.q_stride_t + ld_chunk * 8);
+      const uint16_t *src;
+      if (RAGGED) {      // past the end: any valid row, masked below
+        const int row = min(c0 + r0 + 16 * i + ld_row, n - 1);
+        src = q_head0 + (long long)qh * s.q_stride_h + (long long)row * s.q_stride_t + ld_piece * 8;
+      } else {
+        src = q_lane + ((long long)qh * s.q_stride_h + (long long)(r0 + 16 * i) * s.q_stride_t);
+      }
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                       (__attribute__((address_space(3))) void *)(dst + 16 * i * D),
+                                       16, 0, 0);
     }
   };
-  auto store_q = [&](int buf, const uint4 (&stg)[4]) {
+  int q_piece[8];    // where piece 2*kk + lh of this lane's query row (l32 of a tile) is stored
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<uint4 *>(&L.ql[buf][(ld_row + 16 * i) * QPITCH + ld_chunk * 8]) = stg[i];
-  };
+  for (int kk = 0; kk < 8; ++kk) q_piece[kk] = l32 * D + 8 * ((2 * kk + lh) ^ (l32 & 15));
 
   // S^T tiles of one 32-query tile: acc[qt][kt] = keys (tile kt) x queries, contraction over
   // channels; the two key tiles alternate so that consecutive MFMAs are independent
@@ -135,7 +152,7 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
     bf16x8 qb[8];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk)
-      qb[kk] = *reinterpret_cast<const bf16x8 *>(&L.ql[buf][(32 * qt + l32) * QPITCH + 16 * kk + 8 * lh]);
+      qb[kk] = *reinterpret_cast<const bf16x8 *>(&L.ql[buf][32 * qt * D + q_piece[kk]]);
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -147,16 +164,22 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
         acc[qt][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kt][kk], qb[kk], acc[qt][kt], 0, 0, 0);
   };
 
-  uint4 stg[4];
-  load_q(0, stg);
-  store_q(0, stg);
-  __syncthreads();
+  // The compiler does not count loads that write LDS when it places its waits, and a
+  // __syncthreads() would wait for all of them; the waits and barriers of the query pipeline
+  // are therefore written out.  Loads complete in order and every step issues four per wave, so
+  // "at most 8 outstanding" means: everything up to the next step's tile has arrived.
+  issue_q(0);
+  issue_q(1);
+  issue_q(2);
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
   product(0, 0);
 
   const float c2 = scale * 1.4426950408889634f;       // logits in units of log 2
   for (int step = 0; step < nsteps; ++step) {
-    const int buf = step & 1;
-    load_q(step + 1, stg);                              // in flight during this step
+    const int buf = step % ATT_QBUF, sb = step & 1;
+    // the tile of three steps ahead replaces the one of the previous step, which every wave
+    // has finished reading before the barrier that ended that step
+    if (step + 3 < nsteps) issue_q(step + 3);
 
     // Local softmax statistics of every query over this wave's 64 keys, in the base-2 domain:
     // e = 2^(c*s - m) with c = scale * log2(e), so an element costs half a max3, one fma, one
@@ -201,22 +224,25 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
         l_mine = l;
       }
     }
-    L.st_m[buf][wave][lane] = m_mine;
-    L.st_l[buf][wave][lane] = l_mine;
+    L.st_m[sb][wave][lane] = m_mine;
+    L.st_l[sb][wave][lane] = l_mine;
 
-    store_q(buf ^ 1, stg);
-    __syncthreads();        // statistics of this step and the next step's queries are in LDS
+    // statistics of this step and the next step's queries are in LDS after this barrier
+    if (step + 3 < nsteps)
+      asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     // merge the four waves' statistics, one query per lane, then hand both tiles their factor
-    float mw[4], m = L.st_m[buf][0][lane];
+    float mw[4], m = L.st_m[sb][0][lane];
 #pragma unroll
     for (int w2 = 0; w2 < 4; ++w2) {
-      mw[w2] = L.st_m[buf][w2][lane];
+      mw[w2] = L.st_m[sb][w2][lane];
       m = fmaxf(m, mw[w2]);
     }
     float l = 0.f;
 #pragma unroll
-    for (int w2 = 0; w2 < 4; ++w2) l = fmaf(L.st_l[buf][w2][lane], __builtin_amdgcn_exp2f(mw[w2] - m), l);
+    for (int w2 = 0; w2 < 4; ++w2) l = fmaf(L.st_l[sb][w2][lane], __builtin_amdgcn_exp2f(mw[w2] - m), l);
     float f = __builtin_amdgcn_exp2f(m_mine - m) * __builtin_amdgcn_rcpf(l);
     if (RAGGED) {
       const int q0 = c0 + (step % (ATT_C / ATT_QB)) * ATT_QB;
@@ -230,7 +256,9 @@ __device__ __forceinline__ void attn_block(const AttnSeg &s, float scale, int he
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) pacc[kt][v] = fmaf(acc[qt][kt][v], fq, pacc[kt][v]);
-      if (qt == 0 && step + 1 < nsteps) product(buf ^ 1, 0);   // first tile of the next step
+      // First tile of the next step, in the same basic block as the accumulation so that the two
+      // interleave; after the last step it multiplies an old tile and the result is dropped.
+      if (qt == 0) product((step + 1) % ATT_QBUF, 0);
     }
   }
 
