@@ -42,7 +42,8 @@ constexpr double PIVOT_REL = 1.4901161193847656e-08;   // 2^-26
 // One workgroup (4 waves) per head; every O(n^3)-ish piece runs on the fp64 matrix cores
 // (16x16x4 MFMA: A[i][k] in lane (i = l & 15, k = l >> 4), B[k][j] in lane (j = l & 15,
 // k = l >> 4), register v of lane l of the result is D[4v + (l >> 4)][l & 15]):
-//   1. S = Phi^T G Phi, G summed in fp64 from the head's partial blocks, 32 rows of G at a time
+//   1. S = Phi^T G Phi, G summed in fp64 from the head's partial blocks; a wave takes 32 rows of G
+//      through T = G Phi to its share of S in registers, then the four shares are added
 //   2. blocked right-looking Cholesky of S + rho I with 16-wide panels: wave 0 factors the
 //      diagonal block in registers (the only serial part, 16 pivots) and inverts it, the panel
 //      below is L_qp = A_qp X_pp^T and the trailing blocks get A_qr -= L_qp L_rp^T
@@ -62,21 +63,68 @@ __device__ __forceinline__ double readlane_f64(double x, int lane) {
   return __hiloint2double(hi, lo);
 }
 
+// Rows 32 WV + 16t .. + 15 of G = sum of a head's partial Gram matrices, in the arrangement of
+// an fp64 MFMA A operand: g[q] of lane (l16, lq) is G[32 WV + 16t + l16][4q + lq].  G is
+// symmetric and only its upper blocks are stored, so an element left of the diagonal block is
+// read as its mirror image; in the diagonal block and right of it the 16 lanes of a row tile
+// read consecutive 16-byte pieces.  Sums are fp64, in split order, two splits in flight.
+struct PartialRows {
+  const float *src;     // the head's first partial
+  int nsplit, l16, lq;
+  int wv;               // the wave (uniform): rows 32 wv .. 32 wv + 31
+};
+__device__ __forceinline__ void fetch_partial_rows(const PartialRows &P, int sp, int t, float (&v)[32]) {
+  // float offsets inside a partial: the lane's part (one address register per arrangement) and
+  // a part that is the same for all lanes
+  const unsigned lane_up = 4 * P.l16 + P.lq;   // stored block (kb, wv): row 4(q&7) + lq, column 16t + l16
+  const unsigned lane_lo = (64 * (P.l16 >> 3) + 32 * ((P.l16 >> 2) & 1)) * 4 + (P.l16 & 3) + 4 * P.lq;
+                                               // stored block (wv, kb): row 16t + l16, column 4(q&7) + lq
+  const float *ps = P.src + (long long)sp * GRAM_PARTIAL_FLOATS;
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    if (kb <= P.wv) {                          // uniform
+      const float *pb = ps + (upper_block(kb, P.wv) * 1024 + 64 * t);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[8 * kb + u] = (pb + (64 * (u >> 1) + 32 * (u & 1)) * 4)[lane_up];
+    } else {
+      const float *pb = ps + (upper_block(P.wv, kb) * 1024 + 512 * t);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[8 * kb + u] = (pb + 16 * u)[lane_lo];
+    }
+  }
+}
+// v0, v1 hold splits 0 and 1 on entry (fetched by the caller, so that they can be in flight behind
+// other work)
+__device__ __forceinline__ void sum_partial_rows(const PartialRows &P, int t, float (&v0)[32],
+                                                 float (&v1)[32], double (&g)[32]) {
+  for (int sp = 0; sp < P.nsplit; sp += 2) {
+#pragma unroll
+    for (int q = 0; q < 32; ++q) g[q] += (double)v0[q];
+    if (sp + 2 < P.nsplit) fetch_partial_rows(P, sp + 2, t, v0);
+    if (sp + 1 < P.nsplit) {
+#pragma unroll
+      for (int q = 0; q < 32; ++q) g[q] += (double)v1[q];
+      if (sp + 3 < P.nsplit) fetch_partial_rows(P, sp + 3, t, v1);
+    }
+  }
+}
+__device__ __forceinline__ void fetch_first_splits(const PartialRows &P, int t, float (&v0)[32],
+                                                   float (&v1)[32]) {
+  if (P.nsplit > 0) fetch_partial_rows(P, 0, t, v0);
+  if (P.nsplit > 1) fetch_partial_rows(P, 1, t, v1);
+}
+
 template <int M>
 __global__ __launch_bounds__(256, M > 48 ? 1 : 2) void sketch_solve_kernel(
     const SegTable T, int tiles_per_wg, const float *__restrict__ partials,
     const float *__restrict__ phi, float ridge_rel, uint16_t *__restrict__ wt,
     int32_t *__restrict__ status, int *__restrict__ zero, long long zero_ints) {
   constexpr int P = M / 16, CT = M / 16;
-  // LDS pitches in doubles.  GP = 132 spreads the A-operand reads of G (16 rows x 4 k per
-  // instruction) over all banks: row stride 8 dwords mod 64, k stride 2.
-  constexpr int GP = D + 4, TP = M + 1, SP = M + 1;
-  // the staging of G and T (step 1) and the matrices S, X (steps 2-4) share one region: two
-  // workgroups fit a CU, so that the serial parts of one overlap the matrix work of the other
-  constexpr int STAGE = 32 * GP + 32 * TP, FACT = 2 * M * SP;
-  __shared__ double region[STAGE > FACT ? STAGE : FACT];
+  // LDS pitch in doubles.  Two workgroups fit a CU, so that the serial parts of one overlap the
+  // matrix work of the other.
+  constexpr int SP = M + 1;
+  __shared__ double region[2 * M * SP];
   __shared__ __attribute__((aligned(16))) float PH[D * M];
-  double *Gs = region, *Ts = region + 32 * GP;
   double *Ss = region;                 // S, then L in its lower blocks
   double *Xs = region + M * SP;        // L^{-1} (lower blocks)
   __shared__ double d0_s[M], rs_s[M], col_s[64];
@@ -84,144 +132,113 @@ __global__ __launch_bounds__(256, M > 48 ? 1 : 2) void sketch_solve_kernel(
 
   const int lhead = blockIdx.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
-  for (int idx = tid; idx < D * M / 4; idx += 256)
-    reinterpret_cast<float4 *>(PH)[idx] = reinterpret_cast<const float4 *>(phi)[idx];
+  // Phi on its way to LDS: the loads leave first and are stored once the loads of the partial
+  // sums and the clearing stores have been issued behind them
+  constexpr int PHN = (D * M / 4 + 255) / 256;
+  float4 ph_reg[PHN];
+#pragma unroll
+  for (int i = 0; i < PHN; ++i) {
+    const int idx = tid + 256 * i;
+    ph_reg[i] = idx < D * M / 4 ? reinterpret_cast<const float4 *>(phi)[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
   if (tid == 0) flag_s = 0;
-  zero_slice(zero, zero_ints);   // histograms that the score and selection kernels add into
 
   // ---- 1. S = Phi^T G Phi ----
+  // Wave w owns rows 32w .. 32w+31 of G.  As the A operand of T = G Phi lane (l16, lq) holds
+  // G[32w + 16t + l16][4q + lq] for t < 2, q < 32; it fetches these 64 numbers of every partial
+  // straight from the stored blocks (G is symmetric, so whichever of (row, col) and (col, row)
+  // lies in an upper block is read) and sums them in fp64 in split order.  T's accumulators
+  // are in turn B operands of S_w = Phi_w^T T_w (the rows of this wave), so G and T never pass
+  // through LDS and nothing waits on a barrier until the four S_w are added.
   int nsplit;
   const long long pb = partial_base(T, lhead, tiles_per_wg, nsplit);
-  constexpr int ST = (CT * CT + 3) / 4;          // S tiles per wave: tile = wave + 4 i
-  f64x4 sacc[ST];
+  constexpr int CT2 = CT * CT;
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const PartialRows PR{partials + pb * GRAM_PARTIAL_FLOATS, nsplit, l16, lq, wv};
+  float v0[32], v1[32];
+  fetch_first_splits(PR, 0, v0, v1);
+  zero_slice(zero, zero_ints);   // histograms that the score and selection kernels add into
 #pragma unroll
-  for (int i = 0; i < ST; ++i) sacc[i] = f64x4{0.0, 0.0, 0.0, 0.0};
-  const int e = tid * 4;
-  int row0, col;
-  partial_quad(tid, row0, col);   // this thread's float4 of a block: rows row0..+3 of column col
-  // the head's 10 upper blocks of G, summed over the splits in fp64 (split order): every thread
-  // keeps its 4 elements of each block in registers, all loads of two splits in flight at a time
-  double gsum[10][4];
+  for (int i = 0; i < PHN; ++i) {
+    const int idx = tid + 256 * i;
+    if (idx < D * M / 4) reinterpret_cast<float4 *>(PH)[idx] = ph_reg[i];
+  }
+  __syncthreads();                                // Phi is in LDS
+  // T_w = G_w Phi, one 16-row tile of G at a time: CT tiles, 32 steps each, independent chains;
+  // the first splits of the second tile are in flight during the products of the first
+  f64x4 tacc[2][CT];
 #pragma unroll
-  for (int b = 0; b < 10; ++b)
+  for (int t = 0; t < 2; ++t) {
+    double ga[32];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) gsum[b][c] = 0.0;
-  {
-    const float *src = partials + pb * GRAM_PARTIAL_FLOATS + e;
-    for (int s0 = 0; s0 < nsplit; s0 += 2) {
-      float4 v[2][10];
+    for (int q = 0; q < 32; ++q) ga[q] = 0.0;
+    sum_partial_rows(PR, t, v0, v1, ga);
+    if (t == 0) fetch_first_splits(PR, 1, v0, v1);
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+    for (int ct = 0; ct < CT; ++ct) tacc[t][ct] = f64x4{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int b = 0; b < 10; ++b) {
-          v[u][b] = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (s0 + u < nsplit)
-            v[u][b] = *reinterpret_cast<const float4 *>(src + (long long)(s0 + u) * GRAM_PARTIAL_FLOATS + b * 1024);
-        }
+    for (int q0 = 0; q0 < 32; q0 += 8) {
+      float pbv[8][CT];
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+      for (int u = 0; u < 8; ++u)
 #pragma unroll
-        for (int b = 0; b < 10; ++b) {
-          gsum[b][0] += v[u][b].x; gsum[b][1] += v[u][b].y;
-          gsum[b][2] += v[u][b].z; gsum[b][3] += v[u][b].w;
-        }
+        for (int ct = 0; ct < CT; ++ct) pbv[u][ct] = PH[(4 * (q0 + u) + lq) * M + 16 * ct + l16];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+          tacc[t][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(ga[q0 + u], (double)pbv[u][ct], tacc[t][ct], 0, 0, 0);
     }
   }
+  // S_w = Phi_w^T T_w: register v of T's accumulators is row 4v + lq of the tile, which is the
+  // B operand of step v
+  f64x4 sacc[CT2];
 #pragma unroll
-  for (int I = 0; I < 4; ++I) {
-    __syncthreads();                              // Gs and Ts of the previous block are done with
-    // rows 32I .. 32I+31 of G (mirror blocks written transposed)
+  for (int i = 0; i < CT2; ++i) sacc[i] = f64x4{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-    for (int J = 0; J < 4; ++J) {
-      const int blk = J >= I ? upper_block(I, J) : upper_block(J, I);
-      if (J >= I) {          // stored as (I,J): element (r, c) is G[32I + r][32J + c]
+  for (int t = 0; t < 2; ++t) {
+    float pav[4][CT];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) Gs[(row0 + c) * GP + 32 * J + col] = gsum[blk][c];
-      } else {               // stored as (J,I): element (r, c) is G[32I + c][32J + r]
-        double *d = &Gs[col * GP + 32 * J + row0];
-        d[0] = gsum[blk][0]; d[1] = gsum[blk][1]; d[2] = gsum[blk][2]; d[3] = gsum[blk][3];
-      }
-    }
-    __syncthreads();
-    // T_I = G_I Phi (32 x M).  A wave runs two independent accumulation chains so that the
-    // matrix core always has a second MFMA to start: two tiles side by side, or the even and
-    // odd k-steps of a single tile.
-    {
-      const int t0 = wave, t1 = wave + 4;
-      const bool has0 = t0 < 2 * CT, two = t1 < 2 * CT;
-      if (has0) {
-        const int rt0 = t0 / CT, ct0 = t0 - rt0 * CT;
-        const int rt1 = two ? t1 / CT : rt0, ct1 = two ? t1 - (t1 / CT) * CT : ct0;
-        f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
-        // chain c reads A from pa[c] + q * sa and B from pb[c] + q * sb at its step q
-        const int steps = two ? D / 4 : D / 8, sa = two ? 4 : 8, sb = (two ? 4 : 8) * M;
-        const double *pa0 = &Gs[(16 * rt0 + l16) * GP + lq];
-        const double *pa1 = two ? &Gs[(16 * rt1 + l16) * GP + lq] : pa0 + 4;
-        const float *pb0 = &PH[lq * M + 16 * ct0 + l16];
-        const float *pb1 = two ? &PH[lq * M + 16 * ct1 + l16] : pb0 + 4 * M;
-        // operands of 16 steps are fetched before their MFMAs (the scheduling barrier keeps
-        // the compiler from sinking the loads back next to their uses), so that one LDS
-        // latency is paid per 32 MFMAs and not per step
-        for (int q0 = 0; q0 < steps; q0 += 16) {
-          double a0[16], a1[16];
-          float b0[16], b1[16];
+    for (int v = 0; v < 4; ++v)
 #pragma unroll
-          for (int u = 0; u < 16; ++u) {
-            a0[u] = pa0[(q0 + u) * sa];
-            b0[u] = pb0[(q0 + u) * sb];
-            a1[u] = pa1[(q0 + u) * sa];
-            b1[u] = pb1[(q0 + u) * sb];
-          }
-          __builtin_amdgcn_sched_barrier(0);
+      for (int at = 0; at < CT; ++at) pav[v][at] = PH[(32 * wv + 16 * t + 4 * v + lq) * M + 16 * at + l16];
 #pragma unroll
-          for (int u = 0; u < 16; ++u) {
-            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0[u], (double)b0[u], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[u], (double)b1[u], acc1, 0, 0, 0);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        if (!two) acc0 += acc1;
+    for (int v = 0; v < 4; ++v)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) Ts[(16 * rt0 + 4 * v + lq) * TP + 16 * ct0 + l16] = acc0[v];
-        if (two) {
+      for (int at = 0; at < CT; ++at)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) Ts[(16 * rt1 + 4 * v + lq) * TP + 16 * ct1 + l16] = acc1[v];
-        }
-      }
-    }
-    __syncthreads();
-    // S += Phi_I^T T_I: the wave's tiles side by side, operands fetched ahead as above
-    {
-      float pa[8][ST];
-      double tb[8][ST];
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-        for (int i = 0; i < ST; ++i) {
-          const int tile = wave + 4 * i;
-          const int at = tile < CT * CT ? tile / CT : 0, bt = tile < CT * CT ? tile - at * CT : 0;
-          pa[ks][i] = PH[(32 * I + 4 * ks + lq) * M + 16 * at + l16];
-          tb[ks][i] = Ts[(4 * ks + lq) * TP + 16 * bt + l16];
-        }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-        for (int i = 0; i < ST; ++i)
-          if (wave + 4 * i < CT * CT)
-            sacc[i] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)pa[ks][i], tb[ks][i], sacc[i], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+        for (int bt = 0; bt < CT; ++bt)
+          sacc[at * CT + bt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)pav[v][at], tacc[t][bt][v],
+                                                                    sacc[at * CT + bt], 0, 0, 0);
   }
-  __syncthreads();                                // S takes the place of the staging buffers
+  // S = (S_0 + S_2) + (S_1 + S_3), in this order whatever the waves' timing
+  auto put = [&](double *dst) {
 #pragma unroll
-  for (int i = 0; i < ST; ++i) {
-    const int tile = wave + 4 * i;
-    if (tile < CT * CT) {
-      const int at = tile / CT, bt = tile - at * CT;
+    for (int at = 0; at < CT; ++at)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) Ss[(16 * at + 4 * v + lq) * SP + 16 * bt + l16] = sacc[i][v];
-    }
+      for (int bt = 0; bt < CT; ++bt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dst[(16 * at + 4 * v + lq) * SP + 16 * bt + l16] = sacc[at * CT + bt][v];
+  };
+  auto add = [&](const double *src) {
+#pragma unroll
+    for (int at = 0; at < CT; ++at)
+#pragma unroll
+      for (int bt = 0; bt < CT; ++bt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sacc[at * CT + bt][v] += src[(16 * at + 4 * v + lq) * SP + 16 * bt + l16];
+  };
+  if (wave == 2) put(Ss);
+  if (wave == 3) put(Xs);
+  __syncthreads();
+  if (wave == 0) add(Ss);
+  if (wave == 1) add(Xs);
+  __syncthreads();
+  if (wave == 1) put(Xs);
+  __syncthreads();
+  if (wave == 0) {
+    add(Xs);
+    put(Ss);
   }
   __syncthreads();
 
