@@ -78,8 +78,8 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
   // a wave stages 16 tokens at a time (its 32 tokens of a step in two halves); measured, a third
   // workgroup per CU does not pay, the smaller staging buffer does on the long-context shapes
   __shared__ __attribute__((aligned(16))) uint16_t kl[4][16 * WPITCH];
-  __shared__ unsigned hl[HIST1_BINS / 2];   // first radix digit of the selection, tallied on the
-                                            // way out: two 16-bit counters per word
+  // first radix digit of the selection, tallied on the way out: two 16-bit counters per word
+  __shared__ __attribute__((aligned(16))) unsigned hl[HIST1_BINS / 2];
   // The scores collect here and leave in bursts: 4-byte stores trickling out between the
   // streaming reads cost 12 % of the kernel's time.
   constexpr int BURST = WL::BURST, BSTEPS = BURST / STEP;
@@ -134,19 +134,26 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
   };
 
   uint4 stA[NLD], stB[NLD];
-  load_step(0, stA);          // in flight while W^T is staged
+  load_step(0, stA);
   load_step(1, stB);
-
-  for (int i = tid; i < HIST1_BINS / 2; i += 256) hl[i] = 0;
+  // W^T follows the first two steps of keys through the load queue and waits in registers, so
+  // that the third step of keys can be requested as soon as the first has arrived and not only
+  // once W^T is in LDS: a workgroup starts with three steps in flight
+  constexpr int WN = (W_TERMS * WL::CHUNKS + 255) / 256;
+  uint4 wreg[WN];
   const uint16_t *wh = wt + (size_t)w.lhead * (W_TERMS * M * D);
-  for (int cidx = tid; cidx < W_TERMS * WL::CHUNKS; cidx += 256) {
-    const int t = cidx / WL::CHUNKS;
-    int row, ch;
-    WL::piece(cidx - t * WL::CHUNKS, row, ch);
-    *reinterpret_cast<uint4 *>(&wl[t * WL::PLANE + WL::row(row) + ch * 8]) =
-        *reinterpret_cast<const uint4 *>(wh + (t * M + row) * D + ch * 8);
+#pragma unroll
+  for (int i = 0; i < WN; ++i) {
+    const int cidx = tid + 256 * i;
+    wreg[i] = make_uint4(0, 0, 0, 0);
+    if (cidx < W_TERMS * WL::CHUNKS) {
+      const int t = cidx / WL::CHUNKS;
+      int row, ch;
+      WL::piece(cidx - t * WL::CHUNKS, row, ch);
+      wreg[i] = *reinterpret_cast<const uint4 *>(wh + (t * M + row) * D + ch * 8);
+    }
   }
-  __syncthreads();
+  for (int i = tid; i < HIST1_BINS / 2; i += 256) hl[i] = 0;
 
   float *sp = scores + s.score_off + (long long)w.head * n;
   uint16_t *kw = kl[wave];
@@ -240,9 +247,23 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
     }
   };
 
+  redistribute(stA);            // waits for the first step of keys only
+  load_step(2, stA);
+#pragma unroll
+  for (int i = 0; i < WN; ++i) {
+    const int cidx = tid + 256 * i;
+    if (cidx < W_TERMS * WL::CHUNKS) {
+      const int t = cidx / WL::CHUNKS;
+      int row, ch;
+      WL::piece(cidx - t * WL::CHUNKS, row, ch);
+      *reinterpret_cast<uint4 *>(&wl[t * WL::PLANE + WL::row(row) + ch * 8]) = wreg[i];
+    }
+  }
+  __syncthreads();
+
+  // on entry of an iteration the operands of step `it` are in registers (kb) and the loads of
+  // steps it + 1 (stB) and it + 2 (stA) are in flight
   for (int it = 0; it < nsteps; it += 2) {
-    redistribute(stA);
-    load_step(it + 2, stA);
     multiply(it);
     if (it + 1 < nsteps) {
       redistribute(stB);
@@ -255,6 +276,10 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
       __syncthreads();
       burst(b0, min(BURST, tok_end - tok_begin - b0));
       if (!last) __syncthreads();                   // before the next burst's scores overwrite these
+    }
+    if (!last) {
+      redistribute(stA);
+      load_step(it + 4, stA);
     }
   }
   if (__any(bad)) {
@@ -277,9 +302,16 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
   // a head that will be blended gets its histogram from the blend, over the final scores
   if (hist1 != nullptr && s.attn == nullptr) {   // integer adds: order independent
     int *h1 = hist1 + (size_t)(w.lhead / pool_heads(T, s)) * HIST1_BINS;
-    for (int i = tid; i < HIST1_BINS; i += 256) {
-      const int c = (int)((hl[i >> 1] >> (16 * (i & 1))) & 0xffffu);
-      if (c) atomicAdd(&h1[i], c);
+    // 16 consecutive bins per thread, fetched with two LDS reads; few of them are occupied
+    static_assert(HIST1_BINS == 16 * 256, "16 bins per thread");
+    const uint4 ha = *reinterpret_cast<const uint4 *>(&hl[8 * tid]);
+    const uint4 hb = *reinterpret_cast<const uint4 *>(&hl[8 * tid + 4]);
+    const unsigned wd[8] = {ha.x, ha.y, ha.z, ha.w, hb.x, hb.y, hb.z, hb.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int lo = (int)(wd[j] & 0xffffu), hi = (int)(wd[j] >> 16);
+      if (lo) atomicAdd(&h1[16 * tid + 2 * j], lo);
+      if (hi) atomicAdd(&h1[16 * tid + 2 * j + 1], hi);
     }
   }
 }
