@@ -617,6 +617,36 @@ def test_attention_scores_match_oracle(C, n):
         assert abs(raw.sum() - 256) < 1e-2
 
 
+@pytest.mark.parametrize("G,n", [(1, 300), (2, 513), (8, 600)])
+def test_attention_scores_group_sizes_strided_views_and_batches(C, G, n):
+    _say("attention scores: %d query heads per kv head, strided q and k views, two requests (n=%d and 77)" % (G, n))
+    L, H, pool = 1, 2, 7
+    ap = C.AttnParams(L, H, H * G, pool=pool)
+    reqs, want = [], []
+    for b, nb in enumerate((n, 77)):
+        # rows of 160 and 136 elements of which the first 128 are the head: token stride != d
+        qbuf = torch.zeros(L, H * G, nb, 160, dtype=torch.bfloat16, device=DEV)
+        kbuf = torch.zeros(L, H, nb, 136, dtype=torch.bfloat16, device=DEV)
+        qbuf[..., :128] = W.synthetic_queries(L, H * G, nb, device=DEV, seed=3, request=b)
+        kbuf[..., :128] = W.config1(device=DEV, L=L, H=H, n=nb).requests[0].k
+        q, k = qbuf[..., :128], kbuf[..., :128]
+        assert q.stride(2) == 160 and k.stride(2) == 136
+        reqs.append(C.AttnRequest(q, k))
+        for l in range(L):
+            for h in range(H):
+                K = O.bf16_bits_to_f64(W.bf16_bits(k[l, h]))
+                Qs = [O.bf16_bits_to_f64(W.bf16_bits(q[l, h * G + j])) for j in range(G)]
+                want.append(O.attention_scores(Qs, K, chunk=256, pool=pool))
+    a = C.compactor_attention_scores(ap, reqs)
+    torch.cuda.synchronize()
+    a = a.cpu().numpy()
+    want = np.concatenate(want)
+    assert a.shape == want.shape
+    err = np.abs(a - want)
+    assert np.all(err <= 1e-3 * np.abs(want) + 1e-6), float(np.max(err / np.maximum(want, 1e-12)))
+    _say("  max rel err %.3g" % float(np.max(err / np.maximum(want, 1e-12))))
+
+
 def test_attention_scores_low_rank_keys_and_blend_end_to_end(C):
     _say("attention scores on config-2 keys, then the full blend: compress with a from the GPU")
     L, H, G, n = 1, 4, 4, 4100
