@@ -28,13 +28,13 @@ MEASURED_TRAFFIC_BYTES = {
     ("config2_llama31_8b_n32768", "sketched", "score"): 2.232e9,
     ("config3_qwen25_7b_n131072", "sketched", "gather"): 3.041e9,
     ("config3_qwen25_7b_n131072", "sketched", "gram"): 3.783e9,
-    ("config3_qwen25_7b_n131072", "sketched", "score"): 3.840e9,
+    ("config3_qwen25_7b_n131072", "sketched", "score"): 3.842e9,
     ("config4_ragged_batch", "sketched", "gather"): 6.558e10,
     ("config4_ragged_batch", "sketched", "gram"): 4.335e10,
-    ("config4_ragged_batch", "sketched", "score"): 4.456e10,
+    ("config4_ragged_batch", "sketched", "score"): 4.458e10,
     ("config5_qwen25_32b_n100000", "sketched", "gather"): 1.691e10,
     ("config5_qwen25_32b_n100000", "sketched", "gram"): 1.313e10,
-    ("config5_qwen25_32b_n100000", "sketched", "score"): 1.341e10,
+    ("config5_qwen25_32b_n100000", "sketched", "score"): 1.342e10,
     ("config5_qwen25_32b_n100000", "exact,", "gather"): 1.691e10,
     ("config5_qwen25_32b_n100000", "exact,", "gram"): 1.313e10,
     ("config5_qwen25_32b_n100000", "exact,", "score"): 1.349e10,
