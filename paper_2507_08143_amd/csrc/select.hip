@@ -93,7 +93,7 @@ __device__ int radix_pass(const float *__restrict__ sp, uint32_t *keys, int n, i
     if (STORE) keys[tid] = k;
     tally(k);
   }
-#pragma unroll 4
+#pragma unroll 8        // a head of 32768 tokens: all of a thread's loads in flight at once
   for (int i = tid; i < nv; i += SELECT_THREADS) {
     uint4 k4;
     if (FROM_LDS) {
@@ -197,6 +197,21 @@ __device__ void emit_kept_lds(uint32_t *keys, int n, int k, uint32_t thr, int ne
     if (4 * r * SELECT_THREADS >= n) break;          // uniform
     const unsigned p = table[r * NW + wave] + before[r];
     int pg = (int)(p & 0xffffu), pe = (int)(p >> 16);
+    // keys equal to the threshold are rare (one, unless scores tie): a wave whose 256 tokens of
+    // this round hold none only has to place the keys above it
+    bool any_eq = false;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) any_eq |= i0 + q < n && key[r][q] == thr;
+    if (!__any(any_eq)) {
+      const int base = pg + min(pe, need_eq);
+#pragma unroll
+      for (int q = 0, at = base; q < 4; ++q) {
+        const bool is_gt = i0 + q < n && key[r][q] > thr;
+        if (is_gt && at < k) stage[at] = i0 + q;
+        at += is_gt;
+      }
+      continue;
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       if (i0 + q < n) {
