@@ -647,6 +647,12 @@ def test_attention_scores_group_sizes_strided_views_and_batches(C, G, n):
     _say("  max rel err %.3g" % float(np.max(err / np.maximum(want, 1e-12))))
 
 
+def test_attention_scores_with_every_cu_busy(C):
+    _say("attention scores: 2 layers x 8 kv heads x 4 query heads, n=16384 (1024 workgroups, two per CU)")
+    worst, _, _, _ = _attention_case(C, 2, 8, 4, 16384, W.config2)
+    _say("  max rel err %.3g" % worst)
+
+
 def test_attention_scores_low_rank_keys_and_blend_end_to_end(C):
     _say("attention scores on config-2 keys, then the full blend: compress with a from the GPU")
     L, H, G, n = 1, 4, 4, 4100
