@@ -136,13 +136,11 @@ GroupBytes group_bytes_needed(const compactor_params_t *p, const SegTable &T, bo
   g.wt = align_up((size_t)T.nheads * W_TERMS * m * D * sizeof(uint16_t));
   g.hist1 = align_up((size_t)T.nheads * HIST1_BINS * sizeof(int));
   g.sel = select_needs_pools(T) ? align_up((size_t)select_scratch(T).ints() * sizeof(int)) : 0;
-  // the blend's sums: two doubles per score workgroup and per selection chunk
+  // the blend's sums: four doubles per score workgroup
   g.bstat = 0;
-  if (blend_wanted(T)) {
-    const long long pairs = total_blocks(T, score_tokens_for(p, T, compute_units()), SCORE_STEP, false) +
-                            select_chunks(T);
-    g.bstat = align_up((size_t)pairs * 2 * sizeof(double));
-  }
+  if (blend_wanted(T))
+    g.bstat = align_up((size_t)total_blocks(T, score_tokens_for(p, T, compute_units()), SCORE_STEP, false) *
+                       4 * sizeof(double));
   g.scores = need_scores ? align_up((size_t)rows * sizeof(float)) : 0;
   return g;
 }
@@ -280,8 +278,7 @@ int enqueue_score(const compactor_params_t *p, const SegTable &T, long long rows
   HIP_TRY(launch_score(T, p->sketch_dim, score_tokens, wt, scores, status, hist1, ostat, st));
   MARK(m, COMPACTOR_STAGE_SCORE + 1);
   if (ostat != nullptr) {
-    double *astat = ostat + 2 * total_blocks(T, score_tokens, SCORE_STEP, false);
-    HIP_TRY(launch_blend(T, p->lambda_blend, score_tokens, scores, ostat, astat, hist1, st));
+    HIP_TRY(launch_blend(T, p->lambda_blend, score_tokens, scores, ostat, hist1, st));
   }
   MARK(m, COMPACTOR_STAGE_BLEND + 1);
   return COMPACTOR_OK;

@@ -297,19 +297,19 @@ hipError_t launch_srht_phi(int ks, const uint8_t *signs, const int32_t *cols, fl
 // scores[i] = || W^T k_i ||^2
 // Also tallies the scores of heads that will not be blended into hist1[selection pool][HIST1_BINS]
 // (top 12 key bits; the pool is the head, or the layer when T.layer_scope), which must be zero on
-// entry; hist1 may be null.  ostat, if not null, receives (sum, sum of squares) of every
-// workgroup's scores in fp64, two doubles per workgroup of the launch (for the blend).
+// entry; hist1 may be null.  ostat, if not null, receives four doubles per workgroup of the launch
+// (for the blend): sum and sum of squares of its scores, and of the attention scores a of the same
+// tokens (less the head's first element), for heads whose request has attn.
 hipError_t launch_score(const SegTable &T, int ks, int tokens_per_wg, const uint16_t *wt,
                         float *scores, int32_t *status, int *hist1, double *ostat, hipStream_t st);
 
 // s = z(a) + lambda z(o) in place over the scores of heads whose request has attn; their first
 // selection histogram goes to hist1 (may be null).  score_tokens: the tokens_per_wg the score
-// launch ran with (it decides which entries of ostat belong to a head); astat: scratch, two
-// doubles per selection chunk (select_chunks).
+// launch ran with (it decides which entries of ostat belong to a head).
 bool blend_wanted(const SegTable &T);
 long long select_chunks(const SegTable &T);
 hipError_t launch_blend(const SegTable &T, float lambda, int score_tokens, float *scores,
-                        const double *ostat, double *astat, int *hist1, hipStream_t st);
+                        const double *ostat, int *hist1, hipStream_t st);
 
 // hist1: per-head histogram of the top 12 key bits made by the score kernel, or null.
 hipError_t launch_select(const SegTable &T, const float *scores, const int *hist1,

@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
   constexpr int BURST = WL::BURST, BSTEPS = BURST / STEP;
   static_assert((BURST & (BURST - 1)) == 0 && BSTEPS % 2 == 0, "bursts end on even steps");
   __shared__ __attribute__((aligned(16))) float sc_l[BURST];
-  __shared__ double red[4][2];
+  __shared__ double red[4][4];
 
   // Where this workgroup works.  Every wave does this scalar work before its first load can
   // leave, so the per-segment numbers come precomputed in the table (index_score_blocks) and
@@ -219,12 +219,26 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
     }
   };
 
+  // For the blend (a head whose request brings attention scores a): this thread's share of the
+  // sums and sums of squares of the scores and of a over the workgroup's tokens.  a is shifted by
+  // the head's first element so that a nearly constant vector does not cancel.
   const bool want_stat = ostat != nullptr && s.attn != nullptr;
-  double s1 = 0.0, s2 = 0.0;       // this thread's share of (sum, sum of squares) for the blend
+  const float *ap = want_stat ? s.attn + (long long)w.head * n : nullptr;
+  const double a_shift = want_stat ? (double)ap[0] : 0.0;
+  double s1 = 0.0, s2 = 0.0, a1 = 0.0, a2 = 0.0;
   // The scores of tokens [b0, b0 + cnt) of the run leave as 16-byte streaming stores (they disturb
   // the other workgroups' reads least: 1 to 4 % of the kernel's time against plain stores); a
   // burst that does not start on a 16-byte boundary (odd n) gets up to 3 single stores in front.
-  auto burst = [&](int b0, int cnt) {
+  constexpr int APT = BURST / 256;          // a-values per thread and burst
+  auto fetch_a = [&](int b0, int cnt, float (&av)[APT]) {
+    const float *ab = ap + tok_begin + b0;
+#pragma unroll
+    for (int j = 0; j < APT; ++j) {
+      const int i = tid + 256 * j;
+      av[j] = (want_stat && i < cnt) ? ab[i] : 0.f;
+    }
+  };
+  auto burst = [&](int b0, int cnt, const float (&av)[APT]) {
     float *dst = sp + tok_begin + b0;
     const int mis = (int)((reinterpret_cast<uintptr_t>(dst) >> 2) & 3u);
     const int lead = min(cnt, mis ? 4 - mis : 0);
@@ -239,10 +253,16 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
     }
     for (int i = lead + ((cnt - lead) & ~3) + tid; i < cnt; i += 256) dst[i] = sc_l[i];
     if (want_stat) {
-      for (int i = tid; i < cnt; i += 256) {
-        const double x = (double)sc_l[i];
-        s1 += x;
-        s2 += x * x;
+#pragma unroll
+      for (int j = 0; j < APT; ++j) {
+        const int i = tid + 256 * j;
+        if (i < cnt) {
+          const double x = (double)sc_l[i], y = (double)av[j] - a_shift;
+          s1 += x;
+          s2 += x * x;
+          a1 += y;
+          a2 += y * y;
+        }
       }
     }
   };
@@ -272,9 +292,11 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
     }
     const bool last = it + 2 >= nsteps;
     if (last || (it + 2) % BSTEPS == 0) {          // uniform: a burst is complete
-      const int b0 = (it / BSTEPS) * BURST;
+      const int b0 = (it / BSTEPS) * BURST, cnt = min(BURST, tok_end - tok_begin - b0);
+      float av[APT];
+      fetch_a(b0, cnt, av);        // on their way while the waves meet
       __syncthreads();
-      burst(b0, min(BURST, tok_end - tok_begin - b0));
+      burst(b0, cnt, av);
       if (!last) __syncthreads();                   // before the next burst's scores overwrite these
     }
     if (!last) {
@@ -291,13 +313,13 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
     for (int d = 32; d >= 1; d >>= 1) {
       s1 += __shfl_xor(s1, d);
       s2 += __shfl_xor(s2, d);
+      a1 += __shfl_xor(a1, d);
+      a2 += __shfl_xor(a2, d);
     }
-    if (lane == 0) { red[wave][0] = s1; red[wave][1] = s2; }
+    if (lane == 0) { red[wave][0] = s1; red[wave][1] = s2; red[wave][2] = a1; red[wave][3] = a2; }
     __syncthreads();
-    if (tid == 0) {
-      ostat[2 * (size_t)blockIdx.x] = (red[0][0] + red[1][0]) + (red[2][0] + red[3][0]);
-      ostat[2 * (size_t)blockIdx.x + 1] = (red[0][1] + red[1][1]) + (red[2][1] + red[3][1]);
-    }
+    if (tid < 4)
+      ostat[4 * (size_t)blockIdx.x + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
   }
   // a head that will be blended gets its histogram from the blend, over the final scores
   if (hist1 != nullptr && s.attn == nullptr) {   // integer adds: order independent

@@ -766,71 +766,48 @@ __global__ __launch_bounds__(CHUNK_THREADS, 6) void msel_emit_kernel(const SegTa
 }
 
 // ---- blend: s = z(a) + lambda z(o) (paper Eq. "scoring"), population standard deviation ------
-// The sums that the two standardisations need are gathered on the way: those of o per score
-// workgroup in the score kernel's epilogue (ostat), those of a by blend_stats_kernel, one pair
-// per chunk of 8192 tokens (astat); both as fp64 (sum, sum of squares), a shifted by the head's
-// first element so that a nearly constant vector does not cancel.  blend_apply_kernel then adds
-// a head's pairs up in index order (every chunk of the head gets the same mean and deviation,
-// bit for bit), rewrites the scores in place and tallies the first selection histogram.
-__device__ __forceinline__ void block_sum2(double &x, double &y, double (*wd)[2]) {
+// The sums that the two standardisations need are gathered on the way, in the score kernel's
+// epilogue: per score workgroup the fp64 (sum, sum of squares) of its scores o and of the
+// attention scores a of the same tokens, a shifted by the head's first element so that a nearly
+// constant vector does not cancel (ostat, four doubles per workgroup).  blend_apply_kernel adds a
+// head's pairs up in index order (every chunk of the head gets the same mean and deviation, bit
+// for bit), rewrites the scores in place and tallies the first selection histogram.
+// Mean and reciprocal deviation of a head's scores o and attention scores a from `count`
+// quadruples (sum and sum of squares of o, then of a less `shift`), added in index order.
+struct Moments { double mo, io, ma, ia; };
+__device__ __forceinline__ Moments moments(const double *__restrict__ quads, int count, int n,
+                                           double shift, double (*wd)[4]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  double v[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int i = threadIdx.x; i < count; i += CHUNK_THREADS) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] += quads[4 * i + c];
+  }
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
-    x += __shfl_xor(x, d);
-    y += __shfl_xor(y, d);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) v[c] += __shfl_xor(v[c], d);
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) wd[wave][c] = v[c];
   }
   __syncthreads();
-  if (lane == 0) { wd[wave][0] = x; wd[wave][1] = y; }
-  __syncthreads();
-  double tx = 0.0, ty = 0.0;
+  double t[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-  for (int i = 0; i < CHUNK_THREADS / 64; ++i) { tx += wd[i][0]; ty += wd[i][1]; }
-  x = tx;
-  y = ty;
-}
-
-__global__ __launch_bounds__(CHUNK_THREADS) void blend_stats_kernel(const SegTable T,
-                                                                    double *__restrict__ astat) {
-  __shared__ double wd[CHUNK_THREADS / 64][2];
-  const SelWhere q = sel_locate(T, blockIdx.x);
-  const Seg &s = T.s[q.seg];
-  if (s.attn == nullptr) return;
-  const float *a = s.attn + (long long)q.head * s.n;
-  float f[SEL_ROUNDS][4];
-  const unsigned valid = load_chunk_scores(a, q, f);
-  const double shift = (double)a[0];
-  double s1 = 0.0, s2 = 0.0;
+  for (int i = 0; i < CHUNK_THREADS / 64; ++i) {
 #pragma unroll
-  for (int r = 0; r < SEL_ROUNDS; ++r)
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (valid >> (4 * r + e) & 1) {
-        const double x = (double)f[r][e] - shift;
-        s1 += x;
-        s2 += x * x;
-      }
-  block_sum2(s1, s2, wd);
-  if (threadIdx.x == 0) {
-    astat[2 * (size_t)blockIdx.x] = s1;
-    astat[2 * (size_t)blockIdx.x + 1] = s2;
+    for (int c = 0; c < 4; ++c) t[c] += wd[i][c];
   }
-}
-
-// Mean and reciprocal deviation from `count` (sum, sum of squares) pairs, added in index order.
-__device__ __forceinline__ void moments(const double *__restrict__ pairs, int count, int n,
-                                        double shift, double (*wd)[2], double &mean, double &inv_sd) {
-  double s1 = 0.0, s2 = 0.0;
-  for (int i = threadIdx.x; i < count; i += CHUNK_THREADS) {
-    s1 += pairs[2 * i];
-    s2 += pairs[2 * i + 1];
-  }
-  block_sum2(s1, s2, wd);
-  const double m = s1 / n;
-  double var = s2 / n - m * m;
-  if (!(var > 0.0)) var = 0.0;
-  mean = shift + m;
+  Moments m;
   // a constant vector (deviation 0) contributes nothing
-  inv_sd = var > 0.0 ? 1.0 / sqrt(var) : 0.0;
+  const double mo = t[0] / n, ma = t[2] / n;
+  double vo = t[1] / n - mo * mo, va = t[3] / n - ma * ma;
+  m.mo = mo;
+  m.io = vo > 0.0 ? 1.0 / sqrt(vo) : 0.0;
+  m.ma = shift + ma;
+  m.ia = va > 0.0 ? 1.0 / sqrt(va) : 0.0;
+  return m;
 }
 
 // Where a segment's pairs start in ostat (its first score workgroup) and how many a head has.
@@ -840,8 +817,8 @@ struct OstatIndex {
 };
 __global__ __launch_bounds__(CHUNK_THREADS) void blend_apply_kernel(
     const SegTable T, const OstatIndex X, float lambda, float *__restrict__ scores,
-    const double *__restrict__ ostat, const double *__restrict__ astat, int *__restrict__ hist1) {
-  __shared__ double wd[CHUNK_THREADS / 64][2];
+    const double *__restrict__ ostat, int *__restrict__ hist1) {
+  __shared__ double wd[CHUNK_THREADS / 64][4];
   __shared__ int hist[HIST1_BINS];
   const SelWhere q = sel_locate(T, blockIdx.x);
   const Seg &s = T.s[q.seg];
@@ -849,21 +826,17 @@ __global__ __launch_bounds__(CHUNK_THREADS) void blend_apply_kernel(
   const int n = s.n, tid = threadIdx.x;
   float *o = scores + s.score_off + (long long)q.head * n;
   const float *a = s.attn + (long long)q.head * n;
-  // where the head's pairs start: its first score workgroup, its first chunk
-  const int obph = X.per_head[q.seg], abph = s.sel_bph;
+  // where the head's sums start: its first score workgroup
+  const int obph = X.per_head[q.seg];
   const long long ob = X.first[q.seg] + (long long)(q.head - s.head_begin) * obph;
-  const long long ab = (long long)blockIdx.x - q.tile;
-  double mo, io, ma, ia;
-  moments(ostat + 2 * ob, obph, n, 0.0, wd, mo, io);
-  moments(astat + 2 * ab, abph, n, (double)a[0], wd, ma, ia);
-  io *= (double)lambda;
   if (hist1 != nullptr)
     for (int i = tid; i < HIST1_BINS; i += CHUNK_THREADS) hist[i] = 0;
-  __syncthreads();
+  const Moments M = moments(ostat + 4 * ob, obph, n, (double)a[0], wd);     // has a barrier
+  const double mo = M.mo, ma = M.ma, ia = M.ia, io = M.io * (double)lambda;
   typedef float f32x4_any __attribute__((ext_vector_type(4), aligned(4)));
   // the chunk in parts of PART rounds: the fp64 arithmetic of a whole chunk at once would take
   // so many registers that only three workgroups fit a CU
-  constexpr int PART = 2;
+  constexpr int PART = 4;
 #pragma unroll 1
   for (int r0 = 0; r0 < SEL_ROUNDS; r0 += PART) {
     if (q.tok_begin + 4 * r0 * CHUNK_THREADS >= q.tok_end) break;       // uniform
@@ -969,12 +942,10 @@ bool blend_wanted(const SegTable &T) {
 }
 
 hipError_t launch_blend(const SegTable &T, float lambda, int score_tokens, float *scores,
-                        const double *ostat, double *astat, int *hist1, hipStream_t st) {
+                        const double *ostat, int *hist1, hipStream_t st) {
   if (!blend_wanted(T) || T.nheads <= 0) return hipSuccess;
   const long long nb = select_chunks(T);
   if (nb > 0x7fffffffll) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(blend_stats_kernel, dim3((unsigned)nb), dim3(CHUNK_THREADS), 0, st, T, astat);
-  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   OstatIndex X;
   long long ob = 0;
   for (int i = 0; i < MAX_SEG; ++i) {
@@ -983,7 +954,7 @@ hipError_t launch_blend(const SegTable &T, float lambda, int score_tokens, float
     if (i < T.nseg) ob += (long long)X.per_head[i] * T.s[i].head_count;
   }
   hipLaunchKernelGGL(blend_apply_kernel, dim3((unsigned)nb), dim3(CHUNK_THREADS), 0, st, T, X, lambda,
-                     scores, ostat, astat, hist1);
+                     scores, ostat, hist1);
   return hipGetLastError();
 }
 
