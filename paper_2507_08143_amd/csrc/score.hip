@@ -10,6 +10,8 @@
 // W^T reaches the MFMA as a sum of bf16 planes (hi + lo = 16 mantissa bits with two planes):
 // bf16 x bf16 products are exact in the fp32 accumulator, so the only rounding besides the
 // accumulation itself is the 2^-17 relative error of the split.
+#include <type_traits>
+
 #include "common.h"
 
 namespace cmp {
@@ -159,8 +161,12 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
   uint16_t *kw = kl[wave];
   bool bad = false;
 
-  bf16x8 kb[NSUB][4];
-  auto redistribute = [&](const uint4 (&stg)[NLD]) {
+  // In exact mode W^T is 128 rows and its operand reads from LDS weigh as much as the key
+  // stream; there two steps are multiplied together, so that an operand of W^T read once serves
+  // four MFMAs (a second set of key operands).
+  constexpr bool PAIR = M == 128;
+  bf16x8 kb[PAIR ? 2 : 1][NSUB][4];
+  auto redistribute = [&](const uint4 (&stg)[NLD], int set = 0) {
     // redistribute through the wave's LDS buffer: rows in, B operands out.  Lanes exchange
     // data here without a workgroup barrier (LDS operations of one wave execute in order), so
     // wave-scope fences keep the compiler from moving the reads and writes across each other.
@@ -173,18 +179,24 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
       wave_lds_fence();
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        kb[st][kk] = *reinterpret_cast<const bf16x8 *>(&kw[t16 * WPITCH + 32 * kk + 8 * g]);
+        kb[PAIR ? set : 0][st][kk] = *reinterpret_cast<const bf16x8 *>(&kw[t16 * WPITCH + 32 * kk + 8 * g]);
     }
   };
-  auto multiply = [&](int it) {
-    float sums[NSUB];
+  // steps it .. it + NS - 1 (NS = 1, or 2 with both operand sets filled)
+  auto multiply_steps = [&](auto ns, int it) {
+    constexpr int NS = decltype(ns)::value;
+    float sums[NS][NSUB];
 #pragma unroll
-    for (int st = 0; st < NSUB; ++st) sums[st] = 0.f;
+    for (int p = 0; p < NS; ++p)
+#pragma unroll
+      for (int st = 0; st < NSUB; ++st) sums[p][st] = 0.f;
 #pragma unroll 1
     for (int jb = 0; jb < M / 16; ++jb) {   // kept rolled: unrolling hoists every W^T operand
-      f32x4 acc[NSUB];
+      f32x4 acc[NS][NSUB];
 #pragma unroll
-      for (int st = 0; st < NSUB; ++st) acc[st] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int p = 0; p < NS; ++p)
+#pragma unroll
+        for (int st = 0; st < NSUB; ++st) acc[p][st] = f32x4{0.f, 0.f, 0.f, 0.f};
       const int wrow = WL::row(jb * 16 + t16), nblk = WL::blocks(jb);    // nblk is wave-uniform
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
@@ -193,31 +205,39 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
           for (int t = 0; t < W_TERMS; ++t) {
             const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&wl[t * WL::PLANE + wrow + 32 * kk + 8 * g]);
 #pragma unroll
-            for (int st = 0; st < NSUB; ++st)
-              acc[st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, kb[st][kk], acc[st], 0, 0, 0);
+            for (int p = 0; p < NS; ++p)
+#pragma unroll
+              for (int st = 0; st < NSUB; ++st)
+                acc[p][st] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, kb[p][st][kk], acc[p][st], 0, 0, 0);
           }
         }
       }
 #pragma unroll
-      for (int st = 0; st < NSUB; ++st)
-        sums[st] += acc[st][0] * acc[st][0] + acc[st][1] * acc[st][1] + acc[st][2] * acc[st][2] +
-                    acc[st][3] * acc[st][3];
+      for (int p = 0; p < NS; ++p)
+#pragma unroll
+        for (int st = 0; st < NSUB; ++st)
+          sums[p][st] += acc[p][st][0] * acc[p][st][0] + acc[p][st][1] * acc[p][st][1] +
+                         acc[p][st][2] * acc[p][st][2] + acc[p][st][3] * acc[p][st][3];
     }
-    // lanes (t16, g = 0..3) hold the four quarter-sums of token t16 of both sub-tiles; after
-    // the exchange lanes with g < 2 hold the full sum of sub-tile g
-    float x0 = sums[0] + __shfl_xor(sums[0], 32);
-    float x1 = sums[1] + __shfl_xor(sums[1], 32);
-    const bool up = g & 1;
-    float x = up ? x1 : x0;
-    x += __shfl_xor(up ? x0 : x1, 16);
-    const int tok = tok_begin + it * STEP + wave * WTOK + (lane & 31);   // 16*(g&1) + t16
-    if (g < 2 && tok < tok_end) {
-      sc_l[(tok - tok_begin) & (BURST - 1)] = x;
-      bad |= !(fabsf(x) <= 3.0e38f);
-      const uint32_t bin = score_key(x) >> 20;
-      atomicAdd(&hl[bin >> 1], 1u << (16 * (bin & 1)));
+#pragma unroll
+    for (int p = 0; p < NS; ++p) {
+      // lanes (t16, g = 0..3) hold the four quarter-sums of token t16 of both sub-tiles; after
+      // the exchange lanes with g < 2 hold the full sum of sub-tile g
+      float x0 = sums[p][0] + __shfl_xor(sums[p][0], 32);
+      float x1 = sums[p][1] + __shfl_xor(sums[p][1], 32);
+      const bool up = g & 1;
+      float x = up ? x1 : x0;
+      x += __shfl_xor(up ? x0 : x1, 16);
+      const int tok = tok_begin + (it + p) * STEP + wave * WTOK + (lane & 31);   // 16*(g&1) + t16
+      if (g < 2 && tok < tok_end) {
+        sc_l[(tok - tok_begin) & (BURST - 1)] = x;
+        bad |= !(fabsf(x) <= 3.0e38f);
+        const uint32_t bin = score_key(x) >> 20;
+        atomicAdd(&hl[bin >> 1], 1u << (16 * (bin & 1)));
+      }
     }
   };
+  auto multiply = [&](int it) { multiply_steps(std::integral_constant<int, 1>{}, it); };
 
   // For the blend (a head whose request brings attention scores a): this thread's share of the
   // sums and sums of squares of the scores and of a over the workgroup's tokens.  a is shifted by
@@ -284,11 +304,17 @@ __global__ __launch_bounds__(256, 2) void score_kernel(
   // on entry of an iteration the operands of step `it` are in registers (kb) and the loads of
   // steps it + 1 (stB) and it + 2 (stA) are in flight
   for (int it = 0; it < nsteps; it += 2) {
-    multiply(it);
-    if (it + 1 < nsteps) {
-      redistribute(stB);
+    if (PAIR && it + 1 < nsteps) {
+      redistribute(stB, 1);
       load_step(it + 3, stB);
-      multiply(it + 1);
+      multiply_steps(std::integral_constant<int, PAIR ? 2 : 1>{}, it);
+    } else {
+      multiply(it);
+      if (it + 1 < nsteps) {
+        redistribute(stB);
+        load_step(it + 3, stB);
+        multiply(it + 1);
+      }
     }
     const bool last = it + 2 >= nsteps;
     if (last || (it + 2) % BSTEPS == 0) {          // uniform: a burst is complete
