@@ -114,6 +114,41 @@ __device__ __forceinline__ void fetch_first_splits(const PartialRows &P, int t, 
   if (P.nsplit > 1) fetch_partial_rows(P, 1, t, v1);
 }
 
+// Cholesky factor of a 16 x 16 diagonal block held one row per lane (lanes 0..15 of one wave):
+// lrow[k] = L[lane][k]; 1 / L[k][k] goes to rs[k] (LDS); returns false if a pivot was dropped.
+// The 16 pivots are one dependent chain.  What the next pivot needs of this one (column k + 1)
+// comes by a lane read; the rest of the column goes through LDS (col, 64 doubles) and is applied
+// one pivot later, behind that pivot's reciprocal square root, so no LDS round trip sits on the
+// chain.  Every element still receives its updates in pivot order.
+__device__ __forceinline__ bool chol16(double (&row)[16], double d0_mine, bool rowlane, int lane,
+                                       double *rs, double *col, double (&lrow)[16]) {
+  bool all_ok = true;
+  double cv[16], lk_prev = 0.0;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const double piv = readlane_f64(row[k], k);
+    const double d0k = readlane_f64(d0_mine, k);
+    const bool ok = piv > PIVOT_REL * d0k && piv < 1.0e300;      // false for NaN too
+    const double r = ok ? rsqrt(piv) : 0.0;
+    all_ok &= ok;
+    if (lane == k) rs[k] = r;
+    const double lk = (rowlane && lane >= k) ? row[k] * r : 0.0;   // L[lane][k]
+    lrow[k] = lk;
+    if (k > 0) {
+#pragma unroll
+      for (int j = k + 1; j < 16; ++j) row[j] -= lk_prev * cv[j];  // pivot k - 1, cv[j] = L[j][k-1]
+    }
+    if (k < 15) row[k + 1] -= lk * readlane_f64(lk, k + 1);        // pivot k, the column needed next
+    wave_fence();
+    col[lane] = lk;
+    wave_fence();
+#pragma unroll
+    for (int j = k + 2; j < 16; ++j) cv[j] = col[j];               // L[j][k], for the next round
+    lk_prev = lk;
+  }
+  return all_ok;
+}
+
 template <int M>
 __global__ __launch_bounds__(256, M > 48 ? 1 : 2) void sketch_solve_kernel(
     const SegTable T, int tiles_per_wg, const float *__restrict__ partials,
@@ -264,22 +299,8 @@ __global__ __launch_bounds__(256, M > 48 ? 1 : 2) void sketch_solve_kernel(
 #pragma unroll
       for (int j = 0; j < 16; ++j) row[j] = rowlane ? Ss[(base + lane) * SP + base + j] : 0.0;
       const double d0_mine = rowlane ? d0_s[base + lane] : 0.0;
-#pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        const double piv = readlane_f64(row[k], k);
-        const double d0k = readlane_f64(d0_mine, k);
-        const bool ok = piv > PIVOT_REL * d0k && piv < 1.0e300;      // false for NaN too
-        const double rs = ok ? rsqrt(piv) : 0.0;
-        if (lane == k) rs_s[base + k] = rs;
-        if (!ok && lane == 0) flag_s = COMPACTOR_STATUS_PIVOT;
-        const double lk = (rowlane && lane >= k) ? row[k] * rs : 0.0;   // L[lane][k]
-        lrow[k] = lk;
-        wave_fence();
-        col_s[lane] = lk;
-        wave_fence();
-#pragma unroll
-        for (int j = k + 1; j < 16; ++j) row[j] -= lk * col_s[j];       // col_s[j] = L[j][k]
-      }
+      if (!chol16(row, d0_mine, rowlane, lane, rs_s + base, col_s, lrow) && lane == 0)
+        flag_s = COMPACTOR_STATUS_PIVOT;
       if (rowlane) {
 #pragma unroll
         for (int k = 0; k < 16; ++k) Ss[(base + lane) * SP + base + k] = lrow[k];
@@ -485,22 +506,8 @@ __global__ __launch_bounds__(256) void exact_solve_kernel(
 #pragma unroll
       for (int j = 0; j < 16; ++j) row[j] = rowlane ? Ss[(base + lane) * SP + base + j] : 0.0;
       const double d0_mine = rowlane ? d0_s[base + lane] : 0.0;
-#pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        const double piv = readlane_f64(row[k], k);
-        const double d0k = readlane_f64(d0_mine, k);
-        const bool ok = piv > PIVOT_REL * d0k && piv < 1.0e300;      // false for NaN too
-        const double rs = ok ? rsqrt(piv) : 0.0;
-        if (lane == k) rs_s[base + k] = rs;
-        if (!ok && lane == 0) flag_s = COMPACTOR_STATUS_PIVOT;
-        const double lk = (rowlane && lane >= k) ? row[k] * rs : 0.0;   // L[lane][k]
-        lrow[k] = lk;
-        wave_fence();
-        col_s[lane] = lk;
-        wave_fence();
-#pragma unroll
-        for (int j = k + 1; j < 16; ++j) row[j] -= lk * col_s[j];       // col_s[j] = L[j][k]
-      }
+      if (!chol16(row, d0_mine, rowlane, lane, rs_s + base, col_s, lrow) && lane == 0)
+        flag_s = COMPACTOR_STATUS_PIVOT;
       if (rowlane) {
 #pragma unroll
         for (int k = 0; k < 16; ++k) Ss[(base + lane) * SP + base + k] = lrow[k];
