@@ -306,14 +306,17 @@ __global__ __launch_bounds__(256, M > 48 ? 1 : 2) void sketch_solve_kernel(
         for (int k = 0; k < 16; ++k) Ss[(base + lane) * SP + base + k] = lrow[k];
       }
       wave_fence();
-      // X_pp = L_pp^{-1}: lane j solves column j by forward substitution
-      double x[16];
+      // X_pp = L_pp^{-1}: lane j solves column j by forward substitution.  Column by column of
+      // L: as soon as x[k] is known every later row takes its term, so the dependent chain is 16
+      // steps long and not 120 (each row still adds its terms in the order k = 0, 1, ...)
+      double x[16], acc[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        double sum = (i == lane) ? 1.0 : 0.0;
+      for (int i = 0; i < 16; ++i) acc[i] = (i == lane) ? 1.0 : 0.0;
 #pragma unroll
-        for (int k = 0; k < i; ++k) sum -= Ss[(base + i) * SP + base + k] * x[k];
-        x[i] = sum * rs_s[base + i];
+      for (int k = 0; k < 16; ++k) {
+        x[k] = acc[k] * rs_s[base + k];
+#pragma unroll
+        for (int i = k + 1; i < 16; ++i) acc[i] -= Ss[(base + i) * SP + base + k] * x[k];
       }
       if (rowlane) {
 #pragma unroll
@@ -513,14 +516,17 @@ __global__ __launch_bounds__(256) void exact_solve_kernel(
         for (int k = 0; k < 16; ++k) Ss[(base + lane) * SP + base + k] = lrow[k];
       }
       wave_fence();
-      // X_pp = L_pp^{-1}: lane j solves column j by forward substitution
-      double x[16];
+      // X_pp = L_pp^{-1}: lane j solves column j by forward substitution.  Column by column of
+      // L: as soon as x[k] is known every later row takes its term, so the dependent chain is 16
+      // steps long and not 120 (each row still adds its terms in the order k = 0, 1, ...)
+      double x[16], acc[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        double sum = (i == lane) ? 1.0 : 0.0;
+      for (int i = 0; i < 16; ++i) acc[i] = (i == lane) ? 1.0 : 0.0;
 #pragma unroll
-        for (int k = 0; k < i; ++k) sum -= Ss[(base + i) * SP + base + k] * x[k];
-        x[i] = sum * rs_s[base + i];
+      for (int k = 0; k < 16; ++k) {
+        x[k] = acc[k] * rs_s[base + k];
+#pragma unroll
+        for (int i = k + 1; i < 16; ++i) acc[i] -= Ss[(base + i) * SP + base + k] * x[k];
       }
       if (rowlane) {
 #pragma unroll
