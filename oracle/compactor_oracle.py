@@ -262,7 +262,8 @@ def attention_scores(Q_heads, K: np.ndarray, chunk: int = 256, pool: int = 7,
     the query heads that share the kv-head (grouped-query attention), then mean-pooled.
 
     The paper leaves the reduction over a group's query heads and the pooling width open;
-    mean over the group and width 7 are this build's readings.
+    mean over the group and an odd width (default 7), zero padding at both ends of the
+    sequence and division by the full width are this build's readings.
     """
     raw = np.mean([attention_scores_raw(Q, K, chunk, scale) for Q in Q_heads], axis=0)
     return mean_pool(raw, pool)
